@@ -1,0 +1,34 @@
+"""CPU oracle for one SwarmSGD interaction (arXiv 1910.12308).
+
+TEST INFRASTRUCTURE ONLY.  This package is the plain, slow reference that the
+HIP library is checked against.  It shares no code with the HIP path and must
+never be imported by the product package: only the tests, the smoke entry
+point and the benchmark's CPU-baseline leg may use it.
+
+Everything here follows the paper's Algorithm 1, its Section 3 prose
+("Parallel Execution", "The Communication Procedure") and Corollary 2.1
+(the quantizer's three properties).  Floating point is float64 except where a
+float decides an integer (the stochastic-rounding decision and the decoding
+key), which is done in float32 with single IEEE operations so that both sides
+take the same decision.
+
+Pin status per function (what each is checked against, other than itself):
+  philox4x32_10            rocRAND's Philox4x32-10 host-callable engine, compiled
+                           at test time from the vendor header (library routine)
+  stochastic_round         closed-form up-probability, exhaustive over all 2^16
+                           random halves; unbiasedness on averaged trials
+  code / decode            brute force over integers for every b
+  pack / unpack            round trip + explicit byte images
+  gossip_round (bits=0)    swarm mean preserved; potential drop = |Xi-Xj|^2/2
+                           (appendix, proof of the per-step potential bound)
+  gossip_round (quantized) both members of a pair hold the same average when
+                           both decodes succeed; contraction on the complete
+                           graph by enumeration
+  interact (Algorithm 1)   responder receives the plain average; snapshot rule
+  local steps, diagonal    closed form w_H = c + (1-eta a)^H (w_0 - c) at sigma=0
+  local steps, least sq.   numpy gradient A^T(Ax-b) on the same batch
+  local steps, MLP         torch.autograd in float64 on the same batch
+  sample_matching          validity + brute-force greedy on tiny graphs + chi^2
+  potential                definition, and the Laplacian inequality of the appendix
+  whole trajectories       parity unpinned beyond the invariants above
+"""

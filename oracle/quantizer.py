@@ -1,0 +1,106 @@
+"""Lattice quantizer with a decoding key (instantiates Corollary 2.1).
+
+The paper states the quantizer by its properties only: unbiased, error
+proportional to eps and independent of the norm of x, and decodable from any
+key y close enough to x, with more bits buying a larger distance.  This build
+realises it as stochastic rounding to the lattice eps*Z^d, sending each lattice
+coordinate modulo 2^b, and decoding to the representative of that residue
+class nearest to the key.  Test infrastructure only.
+
+The rounding decision and the key's lattice cell are float32 decisions (single
+IEEE operations: one multiply, floor, one subtract, one compare; one multiply
+and one round-to-nearest-even), identical on CPU and GPU.
+"""
+import numpy as np
+
+F32 = np.float32
+CLAMP = F32(2.0 ** 29)     # |x/eps| is clamped here so z_i + z_j' fits int32
+SUPPORTED_BITS = (2, 4, 8, 16)
+
+
+def inv_eps_of(eps):
+    return F32(1.0) / F32(eps)
+
+
+def lattice_coordinate(x, eps):
+    """t = clamp(x * (1/eps)) in float32, and whether the clamp was active."""
+    t = np.asarray(x, dtype=F32) * inv_eps_of(eps)
+    clamped = np.abs(t) > CLAMP
+    return np.clip(t, -CLAMP, CLAMP).astype(F32), clamped
+
+
+def stochastic_round(x, eps, r16):
+    """z = floor(t) + [r16 + 1/2 < frac(t) * 2^16],  t = x/eps (float32).
+
+    r16 is uniform on {0..65535}, so P(up) = ceil(frac*2^16 - 1/2) / 2^16:
+    within 2^-17 of frac, which makes E[eps*z] = x up to that resolution
+    (Corollary 2.1 item 1) and |eps*z - x| < eps (item 2's analogue)."""
+    t, _ = lattice_coordinate(x, eps)
+    f = np.floor(t)
+    frac = (t - f).astype(F32)
+    up = (np.asarray(r16).astype(F32) + F32(0.5)) < frac * F32(65536.0)
+    return f.astype(np.int64) + up.astype(np.int64)
+
+
+def code(z, bits):
+    """The b low bits of the lattice coordinate: z mod 2^b."""
+    return (np.asarray(z, dtype=np.int64) & ((1 << bits) - 1)).astype(np.uint32)
+
+
+def key_cell(y, eps):
+    """Lattice coordinate nearest to the key (ties to even)."""
+    t, _ = lattice_coordinate(y, eps)
+    return np.rint(t).astype(np.int64)
+
+
+def decode(c, y, eps, bits):
+    """The integer congruent to c (mod 2^b) in [k - 2^(b-1), k + 2^(b-1) - 1],
+    k = key_cell(y).  Equals the sender's z iff z - k lies in that window,
+    which holds whenever |x - y| <= (2^(b-1) - 5/2) eps in every coordinate."""
+    k = key_cell(y, eps)
+    m = 1 << bits
+    delta = (np.asarray(c, dtype=np.int64) - k) % m       # in [0, 2^b)
+    delta = np.where(delta >= m // 2, delta - m, delta)   # sign-extend
+    return k + delta
+
+
+def pack(c, bits):
+    """Codes -> bytes, coordinate k in bits [k*b, (k+1)*b) of a little-endian
+    bit stream.  len(c) must be a multiple of 8."""
+    c = np.asarray(c, dtype=np.uint32)
+    assert c.size % 8 == 0 and bits in SUPPORTED_BITS
+    if bits == 16:
+        return c.astype('<u2').view(np.uint8).copy()
+    if bits == 8:
+        return c.astype(np.uint8)
+    per = 8 // bits
+    c = c.reshape(-1, per).astype(np.uint32)
+    out = np.zeros(c.shape[0], dtype=np.uint32)
+    for m in range(per):
+        out |= c[:, m] << np.uint32(m * bits)
+    return out.astype(np.uint8)
+
+
+def unpack(buf, bits, count):
+    buf = np.asarray(buf, dtype=np.uint8)
+    assert bits in SUPPORTED_BITS
+    if bits == 16:
+        return buf.view('<u2').astype(np.uint32)[:count]
+    if bits == 8:
+        return buf.astype(np.uint32)[:count]
+    per = 8 // bits
+    shifts = (np.arange(per, dtype=np.uint32) * np.uint32(bits))
+    c = (buf.astype(np.uint32)[:, None] >> shifts[None, :]) & np.uint32((1 << bits) - 1)
+    return c.reshape(-1)[:count]
+
+
+def quantize(x, eps, bits, r16):
+    """Enc: packed codes of the stochastically rounded lattice point."""
+    return pack(code(stochastic_round(x, eps, r16), bits), bits)
+
+
+def dequantize(buf, key, eps, bits):
+    """Dec: lattice point nearest the key in the code's class, times eps (float64)."""
+    key = np.asarray(key, dtype=F32)
+    z = decode(unpack(buf, bits, key.size), key, eps, bits)
+    return z.astype(np.float64) * float(F32(eps))

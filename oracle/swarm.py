@@ -1,0 +1,201 @@
+"""One swarm interaction, step by step (Algorithm 1 and Section 3 of the paper).
+
+Test infrastructure only.  State (columns [k0, k1) of each):
+  X     current / communicated model of every node  ("current model" register)
+  W     live copy carrying the local steps not yet applied (the node "computes
+        H local gradient steps, which it does not yet apply")
+  Xhat  model at the node's last initiation (sequential model only)
+  ring  S+1 slots of packed codes: slot r mod (S+1) holds Enc(X_r) of every node
+All node models start equal (Algorithm 1, initial models), zero by default.
+"""
+import numpy as np
+
+from . import quantizer as qz
+from . import rng
+
+
+class SwarmOracle:
+    def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None,
+                 k0=0, k1=None, state_dtype=np.float32):
+        self.n, self.d = int(n), int(d)
+        self.k0 = int(k0)
+        self.k1 = self.d if k1 is None else int(k1)
+        assert self.k0 % 8 == 0 and self.k1 % 8 == 0 and self.d % 8 == 0
+        self.edges = np.asarray(edges, dtype=np.int64).reshape(-1, 2)
+        self.bits, self.eps = int(bits), float(np.float32(eps))
+        self.H, self.lr = int(H), float(np.float32(lr))
+        self.S, self.seed = int(stale_max), int(seed)
+        assert self.bits in (0,) + qz.SUPPORTED_BITS and (self.bits > 0 or self.S == 0)
+        self.dtype = state_dtype
+        dw = self.k1 - self.k0
+        self.X = np.zeros((self.n, dw), dtype=state_dtype)
+        if x0 is not None:
+            self.X[:] = np.asarray(x0)[self.k0:self.k1]
+        self.W = self.X.copy()
+        self.Xhat = self.X.copy()
+        self.pending = np.zeros(self.n, dtype=bool)      # W_i carries unapplied steps
+        self.ring = [[None] * self.n for _ in range(self.S + 1)]
+        self.round = 0            # gossip rounds done
+        self.interactions = 0     # pairwise interactions done (the paper's unit of time)
+        self.bits_communicated = 0
+        self.decode_failures = 0
+        self.range_clamped = False
+        self.objective = None
+        self.adj = [sorted(set(self.edges[self.edges[:, 0] == i, 1]) |
+                           set(self.edges[self.edges[:, 1] == i, 0])) for i in range(self.n)]
+
+    # ---- local steps: h~_i^q = g~_i(base - eta sum_{s<q} h~_i^s), fresh sample each q ----
+    def local_steps(self, nodes=None, sequential=False):
+        nodes = range(self.n) if nodes is None else nodes
+        event = self.interactions if sequential else self.round
+        for i in nodes:
+            base = self.Xhat[i] if sequential else self.X[i]
+            w = base.astype(np.float64)
+            for q in range(self.H):
+                w = w - self.lr * self.objective.gradient(i, w, self.seed, event, q)
+            self.W[i] = w
+            self.pending[i] = True
+
+    def _delta(self, i, base):
+        """Pending update -eta h~_i = W_i - base (zero if no local steps are pending)."""
+        if not self.pending[i]:
+            return 0.0
+        return self.W[i].astype(np.float64) - base.astype(np.float64)
+
+    # ---- pair selection -----------------------------------------------------------------
+    def sample_pair(self):
+        """Initiator uniform over nodes, responder uniform over its neighbours."""
+        w = rng.stream(self.seed, rng.TAG_PICK, 0, 0, self.interactions, np.array([0]))
+        i = int(rng.scaled_index(w[0][0], self.n))
+        nb = self.adj[i]
+        return i, int(nb[int(rng.scaled_index(w[1][0], len(nb)))])
+
+    def edge_priorities(self, r=None):
+        r = self.round if r is None else r
+        e = np.arange(len(self.edges), dtype=np.uint64)
+        w0 = rng.stream(self.seed, rng.TAG_MATCH, 0, e, r, np.zeros_like(e))[0]
+        return (w0.astype(np.uint64) << np.uint64(32)) | e
+
+    def sample_matching(self):
+        """Random maximal matching: scan edges by increasing random priority and
+        keep an edge when both endpoints are still free.  Pairs are listed by
+        increasing edge index, each in the orientation of the edge list."""
+        prio = self.edge_priorities()
+        free = np.ones(self.n, dtype=bool)
+        chosen = []
+        for e in np.argsort(prio):
+            u, v = self.edges[e]
+            if free[u] and free[v]:
+                free[u] = free[v] = False
+                chosen.append(int(e))
+        return self.edges[sorted(chosen)].copy()
+
+    def sample_stale(self):
+        """Per node: how many rounds old the partner's code it reads is,
+        uniform on {0..S}, limited to the rounds that exist."""
+        i = np.arange(self.n, dtype=np.uint64)
+        w0 = rng.stream(self.seed, rng.TAG_STALE, 0, i, self.round, np.zeros_like(i))[0]
+        return np.minimum(rng.scaled_index(w0, self.S + 1), self.round).astype(np.int64)
+
+    # ---- quantized exchange -------------------------------------------------------------
+    def _lattice_point(self, i, event):
+        r16 = rng.sr_halves(self.seed, i, event, self.k0, self.k1)
+        z = qz.stochastic_round(self.X[i], self.eps, r16)
+        self.range_clamped |= bool(qz.lattice_coordinate(self.X[i], self.eps)[1].any())
+        return z
+
+    def _read(self, reader, sender, slot, z_true=None):
+        """reader decodes the sender's published code against its own model."""
+        c = qz.unpack(self.ring[slot][sender], self.bits, self.k1 - self.k0)
+        z = qz.decode(c, self.X[reader], self.eps, self.bits)
+        self.range_clamped |= bool(qz.lattice_coordinate(self.X[reader], self.eps)[1].any())
+        self.bits_communicated += self.d * self.bits
+        if z_true is not None:
+            self.decode_failures += int((z != z_true).sum())
+        return z
+
+    def gossip_round(self, pairs, stale=None):
+        """Round model: the matched pairs interact at once, every matched node
+        acting as the initiator of its own update:
+            X_i' = (Q(X_i) + Q(X_j)) / 2 - eta h~_i ,  likewise for j,
+        where Q(X_j) is decoded by i from the code j published `stale[i]` rounds
+        ago, with i's own model as key.  Unmatched nodes apply their own steps."""
+        pairs = np.asarray(pairs, dtype=np.int64).reshape(-1, 2)
+        r, dw = self.round, self.k1 - self.k0
+        stale = np.zeros(self.n, dtype=np.int64) if stale is None else np.asarray(stale)
+        new = {}
+        matched = np.zeros(self.n, dtype=bool)
+        if self.bits == 0:                                   # Q = identity (Corollary 4.2)
+            for i, j in pairs:
+                avg = 0.5 * (self.X[i].astype(np.float64) + self.X[j].astype(np.float64))
+                new[i] = avg + self._delta(i, self.X[i])
+                new[j] = avg + self._delta(j, self.X[j])
+                self.bits_communicated += 2 * self.d * 32
+        else:
+            slot = r % (self.S + 1)
+            z = {}
+            for i in range(self.n):                          # everyone publishes Enc(X_r^i)
+                z[i] = self._lattice_point(i, r)
+                self.ring[slot][i] = qz.pack(qz.code(z[i], self.bits), self.bits)
+            for i, j in pairs:
+                si, sj = min(int(stale[i]), r), min(int(stale[j]), r)
+                assert 0 <= si <= self.S and 0 <= sj <= self.S
+                zj_seen = self._read(i, j, (r - si) % (self.S + 1), z[j] if si == 0 else None)
+                zi_seen = self._read(j, i, (r - sj) % (self.S + 1), z[i] if sj == 0 else None)
+                new[i] = (z[i] + zj_seen) * (0.5 * self.eps) + self._delta(i, self.X[i])
+                new[j] = (z[j] + zi_seen) * (0.5 * self.eps) + self._delta(j, self.X[j])
+        for i, j in pairs:
+            assert not matched[i] and not matched[j] and i != j
+            matched[i] = matched[j] = True
+        for u in range(self.n):
+            if matched[u]:
+                self.X[u] = new[u]
+            elif self.pending[u]:
+                self.X[u] = self.W[u]
+        self.pending[:] = False
+        self.round += 1
+        self.interactions += len(pairs)
+
+    def interact(self, i, j):
+        """One step of Algorithm 1: initiator i, responder j.
+            X_i' = (Q(X_i) + Q(X_j)) / 2 - eta h~_i(Xhat_i) ,  X_j' = (Q(X_i) + Q(X_j)) / 2,
+        i's snapshot becomes X_i'; j's snapshot and pending steps are untouched."""
+        assert self.S == 0 and j in self.adj[i]
+        t = self.interactions
+        if self.H > 0 and self.objective is not None:
+            self.local_steps([i], sequential=True)
+        delta = self._delta(i, self.Xhat[i])
+        if self.bits == 0:
+            avg = 0.5 * (self.X[i].astype(np.float64) + self.X[j].astype(np.float64))
+            self.bits_communicated += 2 * self.d * 32
+        else:
+            zi, zj = self._lattice_point(i, t), self._lattice_point(j, t)
+            self.ring[0][i] = qz.pack(qz.code(zi, self.bits), self.bits)
+            self.ring[0][j] = qz.pack(qz.code(zj, self.bits), self.bits)
+            zj_seen = self._read(i, j, 0, zj)                 # i reads j's register ...
+            self.bits_communicated += self.d * self.bits      # ... and writes the average back
+            avg = (zi + zj_seen) * (0.5 * self.eps)
+        self.X[i] = avg + delta
+        self.X[j] = avg
+        self.Xhat[i] = self.X[i]
+        self.pending[i] = False
+        self.interactions += 1
+
+    def step_sequential(self):
+        i, j = self.sample_pair()
+        self.interact(i, j)
+        return i, j
+
+    # ---- potentials ---------------------------------------------------------------------
+    def mean(self):
+        return self.X.astype(np.float64).mean(axis=0)
+
+    def potential(self):
+        """Gamma = sum_i |X_i - mu|^2."""
+        x = self.X.astype(np.float64)
+        return float(((x - x.mean(axis=0)) ** 2).sum())
+
+    def potential_hat(self):
+        """Gamma-hat = sum_i |Xhat_i - mu|^2 (appendix, auxiliary potentials)."""
+        mu = self.mean()
+        return float(((self.Xhat.astype(np.float64) - mu) ** 2).sum())

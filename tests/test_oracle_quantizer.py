@@ -1,0 +1,128 @@
+"""Pins for the oracle's quantizer (the properties Corollary 2.1 asks for)."""
+from fractions import Fraction
+import math
+
+import numpy as np
+import pytest
+
+from oracle import quantizer as qz
+from oracle import rng
+
+ALL_R16 = np.arange(65536, dtype=np.uint32)
+
+
+@pytest.mark.parametrize("x,eps", [(0.3, 1.0), (-0.3, 1.0), (5.0 + 1 / 1024, 0.125), (-7.75, 0.5),
+                                   (3.0, 1.0), (1e-3, 2.0 ** -12), (-2.718281, 0.01), (123.456, 0.1)])
+def test_sr_up_probability_closed_form(x, eps):
+    """Exhaustive over the 2^16 random halves: #up = ceil(frac 2^16 - 1/2)."""
+    z = qz.stochastic_round(np.full(65536, x, dtype=np.float32), eps, ALL_R16)
+    t = Fraction(float(np.float32(x) * (np.float32(1) / np.float32(eps))))   # the float32 product, exactly
+    fl = math.floor(t)
+    frac = Fraction(float(np.float32(float(t - fl))))                         # one float32 subtraction
+    assert set(np.unique(z).tolist()) <= {fl, fl + 1}
+    n_up = int((z == fl + 1).sum())
+    assert n_up == max(0, math.ceil(frac * 65536 - Fraction(1, 2)))
+    assert abs(Fraction(n_up, 65536) - frac) <= Fraction(1, 2 ** 17)          # unbiased to 2^-17
+
+
+def test_sr_lattice_points_are_fixed_and_error_below_eps():
+    eps = 0.25
+    ints = np.arange(-50, 50)
+    z = qz.stochastic_round((ints * eps).astype(np.float32), eps, np.full(ints.size, 65535))
+    assert np.array_equal(z, ints)
+    gen = np.random.Generator(np.random.PCG64(1))
+    x = (gen.standard_normal(100000) * 10).astype(np.float32)
+    z = qz.stochastic_round(x, eps, gen.integers(0, 65536, x.size))
+    assert np.all(np.abs(z * eps - x.astype(np.float64)) < eps)
+
+
+def test_sr_unbiased_on_averaged_trials():
+    """Corollary 2.1 item 1: the mean of eps*z over independent Philox draws -> x."""
+    eps, d, trials = 2.0 ** -4, 512, 4000
+    gen = np.random.Generator(np.random.PCG64(2))
+    x = gen.standard_normal(d).astype(np.float32)
+    acc = np.zeros(d)
+    for ev in range(trials):
+        acc += qz.stochastic_round(x, eps, rng.sr_halves(5, 0, ev, 0, d)) * eps
+    err = acc / trials - x
+    assert np.abs(err).max() < 5 * (eps / 2) / math.sqrt(trials) + eps * 2 ** -16
+    assert abs(err.mean()) < 5 * (eps / 2) / math.sqrt(trials * d) + eps * 2 ** -16
+    # second moment: E (Q(x)-x)^2 = eps^2 frac (1 - frac) <= eps^2 / 4
+    frac = x / eps - np.floor(x / eps)
+    z = qz.stochastic_round(np.tile(x, 64), eps, np.random.Generator(np.random.PCG64(3)).integers(0, 65536, d * 64))
+    emp = ((z * eps - np.tile(x, 64)) ** 2).mean()
+    assert emp == pytest.approx((eps ** 2 * frac * (1 - frac)).mean(), rel=0.05)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8, 16])
+def test_decode_brute_force_window(bits):
+    """z' == z  iff  z - k in [-2^(b-1), 2^(b-1)-1]; z' is always the member of
+    the code's residue class inside that window around the key's cell k."""
+    half = 1 << (bits - 1)
+    span = 300 if bits <= 8 else 40000
+    zs = np.arange(-span, span + 1, 7 if bits == 16 else 1)
+    ks = np.array([-span, -257, -129, -3, -1, 0, 1, 2, 100, 255, span])
+    eps = 0.5
+    for k in ks:
+        key = np.full(zs.size, k * eps, dtype=np.float32)          # key sits exactly on cell k
+        zd = qz.decode(qz.code(zs, bits), key, eps, bits)
+        ok = (zs - k >= -half) & (zs - k <= half - 1)
+        assert np.array_equal(zd == zs, ok)
+        assert np.all((zd - zs) % (1 << bits) == 0)
+        assert np.all((zd - k >= -half) & (zd - k <= half - 1))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_decode_radius_on_random_reals(bits):
+    """|x - y| <= (2^(b-1) - 5/2) eps in every coordinate => exact recovery."""
+    gen = np.random.Generator(np.random.PCG64(bits))
+    eps = 2.0 ** -6
+    radius = ((1 << (bits - 1)) - 2.5) * eps
+    x = (gen.standard_normal(200000) * 3).astype(np.float32)
+    y = (x + gen.uniform(-radius, radius, x.size)).astype(np.float32)
+    y = np.where(np.abs(y.astype(np.float64) - x) <= radius, y, x)
+    z = qz.stochastic_round(x, eps, gen.integers(0, 65536, x.size))
+    assert np.array_equal(qz.decode(qz.code(z, bits), y, eps, bits), z)
+    far = (x + 3 * (1 << bits) * eps).astype(np.float32)               # far outside: wraps
+    zf = qz.decode(qz.code(z, bits), far, eps, bits)
+    assert np.all(zf != z) and np.all((zf - z) % (1 << bits) == 0)
+
+
+def test_key_cell_ties_to_even():
+    assert qz.key_cell(np.array([0.5, 1.5, 2.5, -0.5, -1.5], dtype=np.float32), 1.0).tolist() == [0, 2, 2, 0, -2]
+
+
+def test_pack_byte_images():
+    assert qz.pack([1, 2, 3, 4, 5, 6, 7, 8], 4).tolist() == [0x21, 0x43, 0x65, 0x87]
+    assert qz.pack([0, 1, 2, 3, 3, 2, 1, 0], 2).tolist() == [0xE4, 0x1B]
+    assert qz.pack([1, 2, 3, 4, 5, 6, 7, 255], 8).tolist() == [1, 2, 3, 4, 5, 6, 7, 255]
+    assert qz.pack([0x1234, 1, 2, 3, 4, 5, 6, 0xFFFF], 16).tolist()[:4] == [0x34, 0x12, 0x01, 0x00]
+    gen = np.random.Generator(np.random.PCG64(0))
+    for bits in (2, 4, 8, 16):
+        c = gen.integers(0, 1 << bits, 256).astype(np.uint32)
+        buf = qz.pack(c, bits)
+        assert buf.size == 256 * bits // 8
+        assert np.array_equal(qz.unpack(buf, bits, 256), c)
+
+
+def test_negative_lattice_points_use_twos_complement_residues():
+    assert qz.code([-1, -2, -16, -17], 4).tolist() == [15, 14, 0, 15]
+
+
+def test_clamp_flag_and_bound():
+    t, clamped = qz.lattice_coordinate(np.array([1e12, -1e12, 1.0], dtype=np.float32), 1e-3)
+    assert clamped.tolist() == [True, True, False]
+    assert abs(t[0]) == 2.0 ** 29 and abs(t[1]) == 2.0 ** 29
+    z = qz.stochastic_round(np.array([1e12], dtype=np.float32), 1e-3, [7])
+    assert int(z[0]) == 2 ** 29
+
+
+def test_quantize_dequantize_round_trip_with_own_model_as_key():
+    gen = np.random.Generator(np.random.PCG64(4))
+    x = gen.standard_normal(4096).astype(np.float32)
+    eps = 2.0 ** -5
+    for bits in (2, 4, 8, 16):
+        buf = qz.quantize(x, eps, bits, rng.sr_halves(1, 0, 0, 0, x.size))
+        # key = the vector itself: z - rint(t) is in {-1, 0, 1}, inside even the 2-bit window [-2, 1]
+        q = qz.dequantize(buf, x, eps, bits)
+        assert np.all(np.abs(q - x) < eps)
