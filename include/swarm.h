@@ -1,0 +1,186 @@
+/*
+ * swarm.h -- C ABI of the MI355X swarm-interaction library.
+ *
+ * One handle simulates the n nodes of SwarmSGD (arXiv 1910.12308) on one GPU: every
+ * node's model is a row of an n x d float32 matrix in device memory.  The calls are
+ * the steps of one swarm interaction as the paper states them: n >= 2 nodes on a
+ * communication graph G, pairwise interactions, H local SGD steps that are computed
+ * but not yet applied, b-bit quantized exchange decoded against the receiver's own
+ * model, and non-blocking (possibly stale) reads of the partner's buffer
+ * (Section 2 "The Distributed System Model", Section 3, Algorithm 1, Corollary 2.1).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *   - The handle OWNS the model matrices X (current / communicated), W (live copy with
+ *     the pending local steps), Xhat (model at the node's last initiation, created on
+ *     first use of swarm_interact), and the ring of packed code rows.  Objective data
+ *     passed to swarm_set_objective_* is BORROWED: it must outlive the handle.
+ *   - Host arrays are only read (or written) during the call.
+ *   - Kernels are enqueued on the HIP stream given at swarm_init.  Calls return after
+ *     enqueueing, except those documented as synchronising.
+ *   - Every call returns a swarm_status; nothing throws or aborts across the ABI.
+ *     swarm_last_error() gives the text of the last failure on a handle.
+ *   - One host thread per handle; calls on one handle must not overlap.
+ */
+#ifndef SWARM_H
+#define SWARM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct swarm_ctx *swarm_t;
+
+typedef enum {
+    SWARM_OK = 0,
+    SWARM_EINVAL = 1,   /* bad argument: not an edge of G, node repeated, size, bits ...  */
+    SWARM_ENOMEM = 2,   /* device or host allocation failed                               */
+    SWARM_EDEVICE = 3,  /* a HIP call failed                                              */
+    SWARM_ESTATE = 4,   /* call not valid in the handle's state (e.g. no objective set)   */
+    SWARM_ERANGE = 5    /* reported by swarm_counters: |x/eps| reached the clamp 2^29     */
+} swarm_status;
+
+enum { SWARM_MODELS_COMM = 0,  /* X: current / communicated models                        */
+       SWARM_MODELS_LIVE = 1,  /* W: live copies carrying the pending local steps         */
+       SWARM_MODELS_SNAP = 2   /* Xhat: models at the last initiation (Algorithm 1)       */ };
+
+/* Problem statement (Section 2; Section 3 "Sequential model"; Corollary 2.1 parameters). */
+typedef struct {
+    uint32_t n;             /* number of nodes, >= 2                                       */
+    uint64_t d;             /* model dimension, a positive multiple of 8                   */
+    uint32_t n_edges;       /* edges of the undirected simple graph G                      */
+    const uint32_t *edges;  /* host, 2*n_edges endpoints (u, v), u != v; copied at init    */
+    uint32_t bits;          /* b: code width, one of 0 (Q = identity, Corollary 4.2),
+                               2, 4, 8, 16                                                 */
+    float eps;              /* lattice scale eps > 0 (ignored when bits = 0)               */
+    uint32_t H;             /* local SGD steps per interaction (constant, as in the
+                               paper's experiments), 0..255                                */
+    float lr;               /* learning rate eta                                           */
+    uint32_t stale_max;     /* S: a read may use the partner's code from up to S rounds
+                               ago; the ring keeps S+1 slots. Must be 0 when bits = 0.     */
+    uint64_t seed;          /* key of every random stream                                  */
+} swarm_config;
+
+/* Create a handle.  x0_dev: d floats (device) copied into every node's model, or NULL
+ * for zeros (all nodes start from the same model: Algorithm 1, initial models; the
+ * registers initially hold zero vectors).  hip_stream: a hipStream_t (NULL = default
+ * stream).  Allocates (2 n d) floats + (S+1) n d b/8 bytes of device memory.
+ * Synchronises the stream. */
+swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_stream,
+                        swarm_t *out);
+swarm_status swarm_destroy(swarm_t h);
+
+/* Node objectives f_i (the paper needs only unbiased stochastic gradients with bounded
+ * variance: Section 2 "Stochastic Optimization").  Data are n-major device arrays.
+ *  diag: f_i(x) = 1/2 sum_k a_ik (x_k - c_ik)^2, gradient + sigma N(0, I);  a, c: n x d.
+ *  lsq : f_i(x) = 1/2 |A_i x - b_i|^2, A: n x m_rows x d, b: n x m_rows; each step draws
+ *        `batch` rows uniformly with replacement and scales by m_rows / batch
+ *        (batch a multiple of 4, at most 64).
+ *  mlp : d = hid*in + hid + out*hid + out (W1 row-major hid x in, b1, W2 out x hid, b2),
+ *        ReLU, softmax cross-entropy averaged over `batch` samples of a Gaussian mixture:
+ *        class y ~ label_cdf[node] (n x out float32 CDF rows), features
+ *        class_means[y] (out x in) + data_sigma N(0, I).  in, hid, out, batch are
+ *        multiples of 32.  Allocates activation workspace for all n nodes. */
+swarm_status swarm_set_objective_diag(swarm_t h, const float *a_dev, const float *c_dev,
+                                      float sigma);
+swarm_status swarm_set_objective_lsq(swarm_t h, const float *A_dev, const float *b_dev,
+                                     uint32_t m_rows, uint32_t batch);
+swarm_status swarm_set_objective_mlp(swarm_t h, uint32_t n_in, uint32_t n_hid, uint32_t n_out,
+                                     const float *class_means_dev, const float *label_cdf_dev,
+                                     float data_sigma, uint32_t batch);
+
+/* Local steps (Section 3 "The Communication Procedure"; appendix, definition of
+ * h~_i^q): for q = 1..H, w <- w - eta g~_i(w) starting from the node's current model X_i,
+ * result stored in W_i and marked pending (computed, "not yet applied").
+ * nodes: host array of `count` distinct node ids, or NULL for all nodes. */
+swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count);
+
+/* Random maximal matching of G for the current round (round model: nodes meet in
+ * disjoint pairs).  Edges get random 64-bit priorities; an edge is kept when both
+ * endpoints are free, scanning by increasing priority.  pairs_host receives up to
+ * floor(n/2) pairs (2 uint32 each) in increasing edge index.  Synchronises. */
+swarm_status swarm_sample_matching(swarm_t h, uint32_t *pairs_host, uint32_t *npairs);
+
+/* Draws, for every node, the staleness of its next read: uniform on {0..S}, limited to
+ * the number of rounds done.  stale_host: n bytes.  Does not touch the device. */
+swarm_status swarm_sample_stale(swarm_t h, uint8_t *stale_host);
+
+/* One gossip round (Section 3 "Parallel Execution"): every node publishes the code of
+ * its model X_i into ring slot r mod (S+1); for every pair (i, j), i decodes the code j
+ * published stale[i] rounds ago against X_i and sets
+ *     X_i <- (Q(X_i) + Q(X_j)) / 2 + (W_i - X_i),
+ * and j does the same with roles swapped; unmatched nodes apply their own pending steps
+ * (X_u <- W_u).  Clears the pending marks and advances the round counter.
+ * pairs_host: npairs disjoint edges of G (2 uint32 each), or NULL to sample the matching
+ * internally.  stale_host: n bytes indexed by reading node, or NULL for fresh reads. */
+swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t npairs,
+                                const uint8_t *stale_host);
+
+/* One step of Algorithm 1 (sequential model), initiator i, responder j adjacent to i:
+ * i runs its H local steps from its snapshot Xhat_i, then
+ *     X_i <- (Q(X_i) + Q(X_j)) / 2 + (W_i - Xhat_i),   X_j <- (Q(X_i) + Q(X_j)) / 2,
+ * Xhat_i <- X_i.  Requires stale_max = 0. */
+swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j);
+
+/* Algorithm 1's sampling: initiator uniform over nodes, responder uniform over its
+ * neighbours, for the current interaction number.  Does not touch the device. */
+swarm_status swarm_sample_pair(swarm_t h, uint32_t *i, uint32_t *j);
+
+/* Stateless codec (Corollary 2.1: Enc, and Dec with a decoding key).
+ * quantize: x_dev (d floats) -> codes_dev (d*bits/8 bytes; coordinate k occupies bits
+ * [k*bits, (k+1)*bits) of a little-endian bit stream), stochastic rounding drawn from the
+ * stream (seed, node, event).  dequantize: out[k] = eps * (member of the code's residue
+ * class nearest to key[k]/eps).  d a multiple of 8; bits in {2,4,8,16}. */
+swarm_status swarm_quantize(const float *x_dev, uint64_t d, float eps, uint32_t bits,
+                            uint64_t seed, uint32_t node, uint32_t event, void *codes_dev,
+                            void *hip_stream);
+swarm_status swarm_dequantize(const void *codes_dev, const float *key_dev, uint64_t d, float eps,
+                              uint32_t bits, float *out_dev, void *hip_stream);
+
+/* Copy columns [k0, k0+len) of nodes [node0, node0+count) between the device matrix
+ * `which` (SWARM_MODELS_*) and a host array of count x len floats.  Writing LIVE marks
+ * those nodes pending; writing COMM clears the mark.  Synchronise. */
+swarm_status swarm_read_models(swarm_t h, uint32_t which, uint32_t node0, uint32_t count,
+                               uint64_t k0, uint64_t len, float *dst_host);
+swarm_status swarm_write_models(swarm_t h, uint32_t which, uint32_t node0, uint32_t count,
+                                uint64_t k0, uint64_t len, const float *src_host);
+/* Device address of a model matrix (n x d floats, row-major), for zero-copy views. */
+swarm_status swarm_models_ptr(swarm_t h, uint32_t which, float **ptr_dev);
+
+/* Packed codes a node published `age` rounds before the last completed round
+ * (age <= S): bytes [byte0, byte0+len) of its code row.  Synchronises. */
+swarm_status swarm_read_codes(swarm_t h, uint32_t age, uint32_t node, uint64_t byte0,
+                              uint64_t len, uint8_t *dst_host);
+
+/* Reductions.  potential: Gamma = sum_i |X_i - mu|^2 with mu the mean model (Section 4,
+ * "Proof Overview"), accumulated in float64; mu_dev (d floats, device) may be NULL.
+ * pair_linf: max_k |X_i[k] - X_j[k]| for each given pair (the distance that decides
+ * whether decoding succeeds).  Both synchronise. */
+swarm_status swarm_potential(swarm_t h, double *gamma_host, float *mu_dev);
+swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npairs,
+                             float *linf_host);
+
+/* Counters since init.  interactions: pairwise interactions (the paper's unit of time);
+ * bits_communicated: bits read from or written to another node's buffer; decode_failures:
+ * coordinates where a fresh read decoded to another lattice point than the sender's.
+ * Returns SWARM_ERANGE if the clamp was reached since init.  Synchronises. */
+swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions,
+                            uint64_t *bits_communicated, uint64_t *decode_failures);
+
+/* Timing aid: the library brackets the fused gossip pass of every swarm_gossip_round /
+ * swarm_interact and the kernels of every swarm_local_steps with HIP events on the
+ * handle's stream (up to 1024 calls of each kind between resets; later calls are not
+ * recorded).  swarm_kernel_times synchronises and returns the summed device milliseconds
+ * and the number of recorded calls since the last swarm_timing_reset. */
+swarm_status swarm_timing_reset(swarm_t h);
+swarm_status swarm_kernel_times(swarm_t h, double *gossip_ms, uint32_t *gossip_calls,
+                                double *local_ms, uint32_t *local_calls);
+
+const char *swarm_last_error(swarm_t h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWARM_H */

@@ -1,0 +1,403 @@
+// Fused quantized gossip pass (Section 3, "Parallel Execution"; Algorithm 1, the
+// decode / average / write-back lines): for each matched pair, one pass over the two
+// model rows does stochastic rounding to the lattice, b-bit code packing and
+// publication, decoding of the partner's (possibly stale) code against the reader's
+// own model, averaging, and adding the pending local update.
+//
+// Thread layout (wave64): one wave owns a tile of 512 consecutive coordinates = 128
+// float4; lane l holds float4 number l and l+64 of the tile, so every 128-bit load and
+// store of a wave covers 1 KiB of consecutive addresses.  One Philox call serves the 8
+// coordinates [8g, 8g+8) = float4 2g and 2g+1; the even lane of each lane pair
+// generates the call for group l/2, the odd lane the call for group 32 + l/2, and the
+// two swap halves through a DPP quad permute.
+#include "internal.h"
+#include "philox.hpp"
+#include "quant.hpp"
+
+namespace swarm {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int TILE = 512;          // coordinates per wave
+constexpr int WAVES = 4;           // waves per workgroup
+
+__device__ __forceinline__ f4 ldg_nt(const float *p) { return __builtin_nontemporal_load((const f4 *)p); }
+__device__ __forceinline__ void stg_nt(float *p, f4 v) { __builtin_nontemporal_store(v, (f4 *)p); }
+__device__ __forceinline__ uint32_t swap_with_neighbour(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+}
+
+// Packed code of one float4 (4 coordinates, 4*BITS bits, coordinate m at bit m*BITS).
+template <int BITS> struct CodeWord;
+template <> struct CodeWord<2>  { typedef uint8_t  type; };
+template <> struct CodeWord<4>  { typedef uint16_t type; };
+template <> struct CodeWord<8>  { typedef uint32_t type; };
+template <> struct CodeWord<16> { typedef uint64_t type; };
+
+template <int BITS>
+__device__ __forceinline__ uint64_t load_code(const uint8_t *row, uint64_t f) {
+    return (uint64_t)__builtin_nontemporal_load((const typename CodeWord<BITS>::type *)(row + f * (BITS / 2)));
+}
+template <int BITS>
+__device__ __forceinline__ void store_code(uint8_t *row, uint64_t f, uint64_t c) {
+    __builtin_nontemporal_store((typename CodeWord<BITS>::type)c,
+                                (typename CodeWord<BITS>::type *)(row + f * (BITS / 2)));
+}
+
+// The two random words of the float4 this lane holds in the tile's first half (lo*)
+// and second half (hi*), for one row.
+struct LaneRandom { uint32_t a0, a1, b0, b1; };
+
+__device__ __forceinline__ LaneRandom row_random(uint64_t seed, uint32_t node, uint32_t event,
+                                                 uint64_t tile, uint32_t lane) {
+    const bool odd = lane & 1u;
+    const uint64_t group = tile * (TILE / 8) + (lane >> 1) + (odd ? 32u : 0u);
+    const Words4 w = stream(seed, TAG_SR, 0, node, event, group);
+    // even lane keeps words 0,1 of group A and needs words 0,1 of group B (made by the odd lane);
+    // odd lane keeps words 2,3 of group B and needs words 2,3 of group A (made by the even lane).
+    const uint32_t r0 = swap_with_neighbour(odd ? w.w0 : w.w2);
+    const uint32_t r1 = swap_with_neighbour(odd ? w.w1 : w.w3);
+    LaneRandom out;
+    out.a0 = odd ? r0 : w.w0;  out.a1 = odd ? r1 : w.w1;
+    out.b0 = odd ? w.w2 : r0;  out.b1 = odd ? w.w3 : r1;
+    return out;
+}
+
+template <int BITS>
+__device__ __forceinline__ uint64_t round_float4(f4 x, uint32_t w_lo, uint32_t w_hi, float inv_eps,
+                                                 int z[4], bool &clamped) {
+    z[0] = stochastic_round(x.x, inv_eps, w_lo & 0xFFFFu, clamped);
+    z[1] = stochastic_round(x.y, inv_eps, w_lo >> 16, clamped);
+    z[2] = stochastic_round(x.z, inv_eps, w_hi & 0xFFFFu, clamped);
+    z[3] = stochastic_round(x.w, inv_eps, w_hi >> 16, clamped);
+    constexpr uint64_t MASK = (1ull << BITS) - 1;
+    return ((uint64_t)z[0] & MASK) | (((uint64_t)z[1] & MASK) << BITS) |
+           (((uint64_t)z[2] & MASK) << (2 * BITS)) | (((uint64_t)z[3] & MASK) << (3 * BITS));
+}
+
+// Average of own lattice point and the partner's decoded one, plus the pending update.
+template <int BITS>
+__device__ __forceinline__ f4 averaged(const int z_own[4], uint64_t partner_code, f4 key, f4 delta,
+                                       float inv_eps, float half_eps, const int *z_true, int &fails,
+                                       bool &clamped) {
+    constexpr uint32_t MASK = (uint32_t)((1ull << BITS) - 1);
+    const float k[4] = {key.x, key.y, key.z, key.w};
+    const float dl[4] = {delta.x, delta.y, delta.z, delta.w};
+    float o[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int zp = decode_near<BITS>((uint32_t)(partner_code >> (m * BITS)) & MASK,
+                                         key_cell(k[m], inv_eps, clamped));
+        if (z_true) fails += (zp != z_true[m]);
+        o[m] = (float)(z_own[m] + zp) * half_eps + dl[m];
+    }
+    return f4{o[0], o[1], o[2], o[3]};
+}
+
+__device__ __forceinline__ void report(DeviceCounters *c, int fails, bool clamped) {
+    if (__builtin_expect(__any(fails != 0), 0)) {
+        for (int off = 32; off > 0; off >>= 1) fails += __shfl_xor(fails, off);
+        if ((threadIdx.x & 63) == 0) atomicAdd(&c->decode_failures, (unsigned long long)fails);
+    }
+    if (__builtin_expect(__any(clamped), 0)) {
+        if ((threadIdx.x & 63) == 0) atomicOr(&c->range_clamped, 1u);
+    }
+}
+
+template <int BITS, int DELTA, int STALE>
+__global__ __launch_bounds__(WAVES * 64) void gossip_pairs_kernel(const GossipArgs a) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
+    const bool inA = kA < a.d, inB = kB < a.d;
+    if (tile * TILE >= a.d) return;
+    const uint32_t ni = a.pairs[2 * blockIdx.y], nj = a.pairs[2 * blockIdx.y + 1];
+    float *xi = a.X + (uint64_t)ni * a.d, *xj = a.X + (uint64_t)nj * a.d;
+    const float *wi = a.W + (uint64_t)ni * a.d, *wj = a.W + (uint64_t)nj * a.d;
+
+    const bool di = DELTA == 1 || (DELTA == 2 && a.pending[ni]);
+    const bool dj = DELTA == 1 || (DELTA == 2 && a.pending[nj]);
+    const uint32_t si = STALE == 0 ? 0u : (uint32_t)a.stale[ni];   // age of the code i reads from j
+    const uint32_t sj = STALE == 0 ? 0u : (uint32_t)a.stale[nj];
+    const bool stale_i = STALE == 1 || (STALE == 2 && si != 0), stale_j = STALE == 1 || (STALE == 2 && sj != 0);
+
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    f4 xiA = zero, xiB = zero, xjA = zero, xjB = zero, wiA, wiB, wjA, wjB;
+    if (inA) { xiA = ldg_nt(xi + kA); xjA = ldg_nt(xj + kA); }
+    if (inB) { xiB = ldg_nt(xi + kB); xjB = ldg_nt(xj + kB); }
+    wiA = xiA; wiB = xiB; wjA = xjA; wjB = xjB;
+    if (di) { if (inA) wiA = ldg_nt(wi + kA); if (inB) wiB = ldg_nt(wi + kB); }
+    if (dj) { if (inA) wjA = ldg_nt(wj + kA); if (inB) wjB = ldg_nt(wj + kB); }
+
+    const uint64_t slot_bytes = (uint64_t)a.n * a.row_bytes;
+    uint8_t *pub_i = a.ring + a.slot_now * slot_bytes + ni * a.row_bytes;
+    uint8_t *pub_j = a.ring + a.slot_now * slot_bytes + nj * a.row_bytes;
+    uint64_t seenjA = 0, seenjB = 0, seeniA = 0, seeniB = 0;       // partner codes as read
+    if (stale_i) {   // i reads what j published si rounds ago
+        const uint8_t *src = a.ring + ((a.slot_now + a.ring_depth - si) % a.ring_depth) * slot_bytes + nj * a.row_bytes;
+        if (inA) seenjA = load_code<BITS>(src, kA / 4);
+        if (inB) seenjB = load_code<BITS>(src, kB / 4);
+    }
+    if (stale_j) {
+        const uint8_t *src = a.ring + ((a.slot_now + a.ring_depth - sj) % a.ring_depth) * slot_bytes + ni * a.row_bytes;
+        if (inA) seeniA = load_code<BITS>(src, kA / 4);
+        if (inB) seeniB = load_code<BITS>(src, kB / 4);
+    }
+
+    const LaneRandom ri = row_random(a.seed, ni, a.event, tile, lane);
+    const LaneRandom rj = row_random(a.seed, nj, a.event, tile, lane);
+
+    bool clamped = false;
+    int fails = 0;
+    int ziA[4], ziB[4], zjA[4], zjB[4];
+    const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, a.inv_eps, ziA, clamped);
+    const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, a.inv_eps, ziB, clamped);
+    const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, a.inv_eps, zjA, clamped);
+    const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, a.inv_eps, zjB, clamped);
+    const float half_eps = 0.5f * a.eps;
+
+    const f4 oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, xiA, wiA - xiA, a.inv_eps, half_eps,
+                                  stale_i ? nullptr : zjA, fails, clamped);
+    const f4 oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, xiB, wiB - xiB, a.inv_eps, half_eps,
+                                  stale_i ? nullptr : zjB, fails, clamped);
+    const f4 ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, xjA, wjA - xjA, a.inv_eps, half_eps,
+                                  stale_j ? nullptr : ziA, fails, clamped);
+    const f4 ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, xjB, wjB - xjB, a.inv_eps, half_eps,
+                                  stale_j ? nullptr : ziB, fails, clamped);
+    if (inA) {
+        stg_nt(xi + kA, oiA); stg_nt(xj + kA, ojA);
+        store_code<BITS>(pub_i, kA / 4, ciA); store_code<BITS>(pub_j, kA / 4, cjA);
+    }
+    if (inB) {
+        stg_nt(xi + kB, oiB); stg_nt(xj + kB, ojB);
+        store_code<BITS>(pub_i, kB / 4, ciB); store_code<BITS>(pub_j, kB / 4, cjB);
+    }
+    if (!inA) { fails = 0; clamped = false; }    // lanes past the row end hold zeros only
+    report(a.counters, fails, clamped);
+}
+
+// Q = identity (Corollary 4.2): plain pairwise averaging plus the pending update.
+template <int DELTA>
+__global__ __launch_bounds__(WAVES * 64) void average_pairs_kernel(const GossipArgs a) {
+    const uint64_t k = ((uint64_t)blockIdx.x * (WAVES * 64) + threadIdx.x) * 4;
+    if (k >= a.d) return;
+    const uint32_t ni = a.pairs[2 * blockIdx.y], nj = a.pairs[2 * blockIdx.y + 1];
+    float *xi = a.X + (uint64_t)ni * a.d + k, *xj = a.X + (uint64_t)nj * a.d + k;
+    const f4 vi = ldg_nt(xi), vj = ldg_nt(xj);
+    f4 di = {0.f, 0.f, 0.f, 0.f}, dj = di;
+    if (DELTA == 1 || (DELTA == 2 && a.pending[ni])) di = ldg_nt(a.W + (uint64_t)ni * a.d + k) - vi;
+    if (DELTA == 1 || (DELTA == 2 && a.pending[nj])) dj = ldg_nt(a.W + (uint64_t)nj * a.d + k) - vj;
+    const f4 avg = 0.5f * (vi + vj);
+    stg_nt(xi, avg + di);
+    stg_nt(xj, avg + dj);
+}
+
+// Unmatched nodes: publish the code of X_u, then apply the node's own pending steps.
+template <int BITS>
+__global__ __launch_bounds__(WAVES * 64) void gossip_singles_kernel(const GossipArgs a) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
+    const bool inA = kA < a.d, inB = kB < a.d;
+    if (tile * TILE >= a.d) return;
+    const uint32_t u = a.singles[blockIdx.y];
+    float *xu = a.X + (uint64_t)u * a.d;
+    const float *wu = a.W + (uint64_t)u * a.d;
+    const bool pend = a.pending[u];
+    if constexpr (BITS > 0) {
+        const f4 zero = {0.f, 0.f, 0.f, 0.f};
+        const f4 xA = inA ? ldg_nt(xu + kA) : zero, xB = inB ? ldg_nt(xu + kB) : zero;
+        const LaneRandom r = row_random(a.seed, u, a.event, tile, lane);
+        bool clamped = false;
+        int zA[4], zB[4];
+        const uint64_t cA = round_float4<BITS>(xA, r.a0, r.a1, a.inv_eps, zA, clamped);
+        const uint64_t cB = round_float4<BITS>(xB, r.b0, r.b1, a.inv_eps, zB, clamped);
+        uint8_t *pub = a.ring + a.slot_now * ((uint64_t)a.n * a.row_bytes) + u * a.row_bytes;
+        if (inA) store_code<BITS>(pub, kA / 4, cA);
+        if (inB) store_code<BITS>(pub, kB / 4, cB);
+        report(a.counters, 0, clamped);
+    }
+    if (pend) {
+        if (inA) stg_nt(xu + kA, ldg_nt(wu + kA));
+        if (inB) stg_nt(xu + kB, ldg_nt(wu + kB));
+    }
+}
+
+// One step of Algorithm 1: the initiator i averages with responder j, adds the steps it
+// computed at its snapshot, refreshes the snapshot; j receives the plain average.
+template <int BITS>
+__global__ __launch_bounds__(WAVES * 64) void interact_kernel(const GossipArgs a, uint32_t ni, uint32_t nj,
+                                                              int has_delta) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
+    const bool inA = kA < a.d, inB = kB < a.d;
+    if (tile * TILE >= a.d) return;
+    float *xi = a.X + (uint64_t)ni * a.d, *xj = a.X + (uint64_t)nj * a.d, *hi = a.Xhat + (uint64_t)ni * a.d;
+    const float *wi = a.W + (uint64_t)ni * a.d;
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const f4 xiA = inA ? ldg_nt(xi + kA) : zero, xiB = inB ? ldg_nt(xi + kB) : zero;
+    const f4 xjA = inA ? ldg_nt(xj + kA) : zero, xjB = inB ? ldg_nt(xj + kB) : zero;
+    f4 dA = zero, dB = zero;
+    if (has_delta) {
+        if (inA) dA = ldg_nt(wi + kA) - ldg_nt(hi + kA);
+        if (inB) dB = ldg_nt(wi + kB) - ldg_nt(hi + kB);
+    }
+    f4 avgA, avgB;
+    if constexpr (BITS > 0) {
+        const LaneRandom ri = row_random(a.seed, ni, a.event, tile, lane);
+        const LaneRandom rj = row_random(a.seed, nj, a.event, tile, lane);
+        bool clamped = false;
+        int fails = 0;
+        int ziA[4], ziB[4], zjA[4], zjB[4];
+        const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, a.inv_eps, ziA, clamped);
+        const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, a.inv_eps, ziB, clamped);
+        const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, a.inv_eps, zjA, clamped);
+        const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, a.inv_eps, zjB, clamped);
+        const float half_eps = 0.5f * a.eps;
+        avgA = averaged<BITS>(ziA, cjA, xiA, zero, a.inv_eps, half_eps, zjA, fails, clamped);
+        avgB = averaged<BITS>(ziB, cjB, xiB, zero, a.inv_eps, half_eps, zjB, fails, clamped);
+        uint8_t *pub_i = a.ring + ni * a.row_bytes, *pub_j = a.ring + nj * a.row_bytes;
+        if (inA) { store_code<BITS>(pub_i, kA / 4, ciA); store_code<BITS>(pub_j, kA / 4, cjA); }
+        if (inB) { store_code<BITS>(pub_i, kB / 4, ciB); store_code<BITS>(pub_j, kB / 4, cjB); }
+        if (!inA) { fails = 0; clamped = false; }
+        report(a.counters, fails, clamped);
+    } else {
+        avgA = 0.5f * (xiA + xjA);
+        avgB = 0.5f * (xiB + xjB);
+    }
+    if (inA) { const f4 o = avgA + dA; stg_nt(xi + kA, o); stg_nt(hi + kA, o); stg_nt(xj + kA, avgA); }
+    if (inB) { const f4 o = avgB + dB; stg_nt(xi + kB, o); stg_nt(hi + kB, o); stg_nt(xj + kB, avgB); }
+}
+
+// Stateless codec kernels (thread = 8 consecutive coordinates = one Philox call).
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__ x, uint64_t d, float inv_eps,
+                                                       uint64_t seed, uint32_t node, uint32_t event,
+                                                       uint8_t *__restrict__ codes, DeviceCounters *counters) {
+    const uint64_t g = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    bool clamped = false;
+    if (g * 8 < d) {
+        const Words4 w = stream(seed, TAG_SR, 0, node, event, g);
+        const f4 lo = *(const f4 *)(x + g * 8), hi = *(const f4 *)(x + g * 8 + 4);
+        int z[4];
+        store_code<BITS>(codes, 2 * g, round_float4<BITS>(lo, w.w0, w.w1, inv_eps, z, clamped));
+        store_code<BITS>(codes, 2 * g + 1, round_float4<BITS>(hi, w.w2, w.w3, inv_eps, z, clamped));
+    }
+    if (counters) report(counters, 0, clamped);
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void dequantize_kernel(const uint8_t *__restrict__ codes,
+                                                         const float *__restrict__ key, uint64_t d, float eps,
+                                                         float inv_eps, float *__restrict__ out) {
+    const uint64_t f = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (f * 4 >= d) return;
+    constexpr uint32_t MASK = (uint32_t)((1ull << BITS) - 1);
+    const uint64_t c = load_code<BITS>(codes, f);
+    const f4 kv = *(const f4 *)(key + f * 4);
+    const float k[4] = {kv.x, kv.y, kv.z, kv.w};
+    float o[4];
+    bool clamped = false;
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        o[m] = (float)decode_near<BITS>((uint32_t)(c >> (m * BITS)) & MASK, key_cell(k[m], inv_eps, clamped)) * eps;
+    *(f4 *)(out + f * 4) = f4{o[0], o[1], o[2], o[3]};
+}
+
+static dim3 tile_grid(uint64_t d, uint32_t rows) {
+    const uint64_t tiles = (d + TILE - 1) / TILE;
+    return dim3((unsigned)((tiles + WAVES - 1) / WAVES), rows, 1);
+}
+
+template <int BITS>
+static void launch_pairs_bits(const GossipArgs &a, int delta_mode, int stale_mode, dim3 grid, hipStream_t st) {
+#define SWARM_CASE(D, S)                                                                      \
+    if (delta_mode == D && stale_mode == S) {                                                 \
+        gossip_pairs_kernel<BITS, D, S><<<grid, WAVES * 64, 0, st>>>(a);                      \
+        return;                                                                               \
+    }
+    SWARM_CASE(0, 0) SWARM_CASE(0, 1) SWARM_CASE(0, 2)
+    SWARM_CASE(1, 0) SWARM_CASE(1, 1) SWARM_CASE(1, 2)
+    SWARM_CASE(2, 0) SWARM_CASE(2, 1) SWARM_CASE(2, 2)
+#undef SWARM_CASE
+}
+
+hipError_t launch_gossip_pairs(const GossipArgs &a, uint32_t bits, int delta_mode, int stale_mode,
+                               uint32_t npairs, hipStream_t st) {
+    if (npairs == 0) return hipSuccess;
+    if (bits == 0) {
+        const dim3 grid((unsigned)((a.d / 4 + WAVES * 64 - 1) / (WAVES * 64)), npairs, 1);
+        if (delta_mode == 0) average_pairs_kernel<0><<<grid, WAVES * 64, 0, st>>>(a);
+        else if (delta_mode == 1) average_pairs_kernel<1><<<grid, WAVES * 64, 0, st>>>(a);
+        else average_pairs_kernel<2><<<grid, WAVES * 64, 0, st>>>(a);
+        return hipGetLastError();
+    }
+    const dim3 grid = tile_grid(a.d, npairs);
+    switch (bits) {
+        case 2: launch_pairs_bits<2>(a, delta_mode, stale_mode, grid, st); break;
+        case 4: launch_pairs_bits<4>(a, delta_mode, stale_mode, grid, st); break;
+        case 8: launch_pairs_bits<8>(a, delta_mode, stale_mode, grid, st); break;
+        case 16: launch_pairs_bits<16>(a, delta_mode, stale_mode, grid, st); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gossip_singles(const GossipArgs &a, uint32_t bits, uint32_t nsingles, hipStream_t st) {
+    if (nsingles == 0) return hipSuccess;
+    const dim3 grid = tile_grid(a.d, nsingles);
+    switch (bits) {
+        case 0: gossip_singles_kernel<0><<<grid, WAVES * 64, 0, st>>>(a); break;
+        case 2: gossip_singles_kernel<2><<<grid, WAVES * 64, 0, st>>>(a); break;
+        case 4: gossip_singles_kernel<4><<<grid, WAVES * 64, 0, st>>>(a); break;
+        case 8: gossip_singles_kernel<8><<<grid, WAVES * 64, 0, st>>>(a); break;
+        case 16: gossip_singles_kernel<16><<<grid, WAVES * 64, 0, st>>>(a); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_interact(const GossipArgs &a, uint32_t bits, uint32_t i, uint32_t j, bool has_delta,
+                           hipStream_t st) {
+    const dim3 grid = tile_grid(a.d, 1);
+    switch (bits) {
+        case 0: interact_kernel<0><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
+        case 2: interact_kernel<2><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
+        case 4: interact_kernel<4><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
+        case 8: interact_kernel<8><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
+        case 16: interact_kernel<16><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize(const float *x, uint64_t d, float eps, float inv_eps, uint32_t bits, uint64_t seed,
+                           uint32_t node, uint32_t event, uint8_t *codes, DeviceCounters *counters,
+                           hipStream_t st) {
+    (void)eps;
+    const unsigned blocks = (unsigned)((d / 8 + 255) / 256);
+    switch (bits) {
+        case 2: quantize_kernel<2><<<blocks, 256, 0, st>>>(x, d, inv_eps, seed, node, event, codes, counters); break;
+        case 4: quantize_kernel<4><<<blocks, 256, 0, st>>>(x, d, inv_eps, seed, node, event, codes, counters); break;
+        case 8: quantize_kernel<8><<<blocks, 256, 0, st>>>(x, d, inv_eps, seed, node, event, codes, counters); break;
+        case 16: quantize_kernel<16><<<blocks, 256, 0, st>>>(x, d, inv_eps, seed, node, event, codes, counters); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(const uint8_t *codes, const float *key, uint64_t d, float eps, float inv_eps,
+                             uint32_t bits, float *out, hipStream_t st) {
+    const unsigned blocks = (unsigned)((d / 4 + 255) / 256);
+    switch (bits) {
+        case 2: dequantize_kernel<2><<<blocks, 256, 0, st>>>(codes, key, d, eps, inv_eps, out); break;
+        case 4: dequantize_kernel<4><<<blocks, 256, 0, st>>>(codes, key, d, eps, inv_eps, out); break;
+        case 8: dequantize_kernel<8><<<blocks, 256, 0, st>>>(codes, key, d, eps, inv_eps, out); break;
+        case 16: dequantize_kernel<16><<<blocks, 256, 0, st>>>(codes, key, d, eps, inv_eps, out); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace swarm

@@ -1,0 +1,67 @@
+// Internal launch interfaces between the C-ABI translation unit and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace swarm {
+
+// Device-side counters shared by the kernels (one per handle).
+struct DeviceCounters {
+    unsigned long long decode_failures;
+    unsigned int range_clamped;
+    unsigned int pad;
+};
+
+struct GossipArgs {
+    float *X;                 // n x d current models (updated in place)
+    const float *W;           // n x d live copies
+    float *Xhat;              // n x d snapshots (Algorithm 1 only), may be null
+    uint8_t *ring;            // (S+1) x n x row_bytes packed codes
+    const uint32_t *pairs;    // device: 2 per pair
+    const uint32_t *singles;  // device: unmatched nodes
+    const uint8_t *pending;   // device: n flags, W_i carries unapplied steps
+    const uint8_t *stale;     // device: n, rounds of staleness of node's read
+    DeviceCounters *counters;
+    uint64_t d;
+    uint64_t row_bytes;       // d * bits / 8
+    uint64_t seed;
+    uint32_t n;
+    uint32_t event;           // round number (or interaction number in Algorithm 1)
+    uint32_t slot_now;        // ring slot written this round
+    uint32_t ring_depth;      // S + 1
+    float eps, inv_eps;
+};
+
+// delta_mode / stale_mode: 0 = none of the nodes, 1 = all of them, 2 = per-node flags.
+hipError_t launch_gossip_pairs(const GossipArgs &a, uint32_t bits, int delta_mode, int stale_mode,
+                               uint32_t npairs, hipStream_t st);
+hipError_t launch_gossip_singles(const GossipArgs &a, uint32_t bits, uint32_t nsingles, hipStream_t st);
+hipError_t launch_interact(const GossipArgs &a, uint32_t bits, uint32_t i, uint32_t j, bool has_delta,
+                           hipStream_t st);
+hipError_t launch_quantize(const float *x, uint64_t d, float eps, float inv_eps, uint32_t bits,
+                           uint64_t seed, uint32_t node, uint32_t event, uint8_t *codes,
+                           DeviceCounters *counters, hipStream_t st);
+hipError_t launch_dequantize(const uint8_t *codes, const float *key, uint64_t d, float eps, float inv_eps,
+                             uint32_t bits, float *out, hipStream_t st);
+
+// Local steps, diagonal quadratics: nodes == nullptr means rows 0..count-1.
+hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const uint32_t *nodes,
+                             uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
+                             uint32_t event, hipStream_t st);
+
+// Reductions.
+hipError_t launch_potential(const float *X, uint32_t n, uint64_t d, float *mu, double *partials,
+                            uint32_t npartials, double *gamma_out, hipStream_t st);
+uint32_t potential_partials(uint64_t d);
+hipError_t launch_pair_linf(const float *X, uint64_t d, const uint32_t *pairs, uint32_t npairs,
+                            uint32_t *linf_bits, hipStream_t st);
+
+// Matching: one workgroup; outputs pairs (increasing edge index), their count, the
+// unmatched nodes and their count.
+hipError_t launch_matching(const uint32_t *edges, uint32_t n_edges, uint32_t n, uint64_t seed, uint32_t round,
+                           uint32_t *prio_scratch /*n_edges words*/, uint32_t *pairs, uint32_t *singles,
+                           uint32_t *counts /*[0]=pairs,[1]=singles*/, hipStream_t st);
+constexpr uint32_t MATCHING_MAX_NODES = 4096;
+constexpr uint32_t MATCHING_MAX_EDGES = 1u << 20;
+
+}  // namespace swarm

@@ -1,0 +1,58 @@
+// Local SGD steps for diagonal-quadratic node objectives
+//   f_i(x) = 1/2 sum_k a_ik (x_k - c_ik)^2,   g~ = a (w - c) + sigma N(0, I)
+// (appendix, definition of the local steps: the q-th gradient is taken at the base
+// model minus eta times the sum of the previous ones, with a fresh sample).  All H
+// steps of a coordinate stay in registers: one read of the base model, a and c, one
+// write of the live copy W.  One thread owns one float4; one Philox call per step
+// gives its four normals.
+#include "internal.h"
+#include "philox.hpp"
+
+namespace swarm {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+template <bool NOISE>
+__global__ __launch_bounds__(256) void local_diag_kernel(const float *__restrict__ X, float *__restrict__ W,
+                                                         const float *__restrict__ A, const float *__restrict__ C,
+                                                         const uint32_t *__restrict__ nodes, uint64_t d, uint32_t H,
+                                                         float lr, float sigma, uint64_t seed, uint32_t event) {
+    const uint64_t f = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (f * 4 >= d) return;
+    const uint32_t node = nodes ? nodes[blockIdx.y] : blockIdx.y;
+    const uint64_t off = (uint64_t)node * d + f * 4;
+    f4 w = __builtin_nontemporal_load((const f4 *)(X + off));
+    const f4 a = __builtin_nontemporal_load((const f4 *)(A + off));
+    const f4 c = __builtin_nontemporal_load((const f4 *)(C + off));
+    for (uint32_t q = 0; q < H; ++q) {
+        f4 noise = {0.f, 0.f, 0.f, 0.f};
+        if (NOISE) {
+            const Words4 r = stream(seed, TAG_NOISE, q, node, event, f);
+            float n0, n1, n2, n3;
+            box_muller(r.w0, r.w1, n0, n1);
+            box_muller(r.w2, r.w3, n2, n3);
+            noise = f4{n0, n1, n2, n3} * sigma;
+        }
+        const f4 t = w - c;
+        f4 g;
+        g.x = fmaf(a.x, t.x, noise.x); g.y = fmaf(a.y, t.y, noise.y);
+        g.z = fmaf(a.z, t.z, noise.z); g.w = fmaf(a.w, t.w, noise.w);
+        w.x = fmaf(-lr, g.x, w.x); w.y = fmaf(-lr, g.y, w.y);
+        w.z = fmaf(-lr, g.z, w.z); w.w = fmaf(-lr, g.w, w.w);
+    }
+    __builtin_nontemporal_store(w, (f4 *)(W + off));
+}
+
+hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const uint32_t *nodes,
+                             uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
+                             uint32_t event, hipStream_t st) {
+    if (count == 0) return hipSuccess;
+    const dim3 grid((unsigned)((d / 4 + 255) / 256), count, 1);
+    if (sigma != 0.0f)
+        local_diag_kernel<true><<<grid, 256, 0, st>>>(X, W, a, c, nodes, d, H, lr, sigma, seed, event);
+    else
+        local_diag_kernel<false><<<grid, 256, 0, st>>>(X, W, a, c, nodes, d, H, lr, sigma, seed, event);
+    return hipGetLastError();
+}
+
+}  // namespace swarm

@@ -1,0 +1,39 @@
+// Node objectives: borrowed data pointers, workspaces and the local-step launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace swarm {
+
+struct DiagObjective { const float *a; const float *c; float sigma; };
+
+constexpr uint32_t LSQ_MAX_BATCH = 64;
+struct LsqObjective {
+    const float *A = nullptr;    // n x m_rows x d
+    const float *b = nullptr;    // n x m_rows
+    uint32_t m_rows = 0, batch = 0;
+};
+
+struct MlpObjective {
+    uint32_t n_in = 0, n_hid = 0, n_out = 0, batch = 0;
+    const float *means = nullptr;   // n_out x n_in
+    const float *cdf = nullptr;     // n x n_out
+    float data_sigma = 0.f;
+    // workspace for all nodes (owned): inputs, labels, hidden activations, logits gradient, hidden gradient
+    float *x = nullptr, *hid = nullptr, *dlogits = nullptr, *dhid = nullptr;
+    uint32_t *labels = nullptr;
+    uint32_t n_nodes = 0;
+};
+
+hipError_t launch_local_lsq(const float *base, float *W, const LsqObjective &o, const uint32_t *nodes,
+                            uint32_t count, uint64_t d, uint32_t H, float lr, uint64_t seed, uint32_t event,
+                            hipStream_t st);
+void free_lsq(LsqObjective &o);
+
+hipError_t alloc_mlp(MlpObjective &o, uint32_t n_nodes);
+void free_mlp(MlpObjective &o);
+hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, const uint32_t *nodes,
+                            uint32_t count, uint32_t n, uint64_t d, uint32_t H, float lr, uint64_t seed,
+                            uint32_t event, hipStream_t st);
+
+}  // namespace swarm

@@ -1,0 +1,41 @@
+// Lattice quantizer with a decoding key (realises the Enc/Dec of Corollary 2.1):
+// stochastic rounding to eps*Z, b low bits sent, decoded to the member of the
+// residue class nearest to the receiver's own coordinate.
+// Every float that decides an integer is one IEEE float32 operation (the library is
+// built with -ffp-contract=off), so the codes are reproducible bit for bit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace swarm {
+
+constexpr float LATTICE_CLAMP = 536870912.0f;   // 2^29: keeps z_i + z_j' inside int32
+
+__device__ __forceinline__ float lattice_coord(float x, float inv_eps, bool &clamped) {
+    const float t = x * inv_eps;
+    clamped |= fabsf(t) > LATTICE_CLAMP;
+    return fminf(fmaxf(t, -LATTICE_CLAMP), LATTICE_CLAMP);
+}
+
+// z = floor(t) + [r16 + 1/2 < frac(t) 2^16]: P(up) is within 2^-17 of frac(t).
+__device__ __forceinline__ int stochastic_round(float x, float inv_eps, uint32_t r16, bool &clamped) {
+    const float t = lattice_coord(x, inv_eps, clamped);
+    const float f = floorf(t);
+    const float frac = t - f;
+    const int up = ((float)r16 + 0.5f) < frac * 65536.0f;
+    return (int)f + up;
+}
+
+// Lattice cell of the key (round to nearest, ties to even).
+__device__ __forceinline__ int key_cell(float y, float inv_eps, bool &clamped) {
+    return (int)rintf(lattice_coord(y, inv_eps, clamped));
+}
+
+// The integer congruent to c (mod 2^BITS) inside [k - 2^(BITS-1), k + 2^(BITS-1) - 1].
+template <int BITS>
+__device__ __forceinline__ int decode_near(uint32_t c, int k) {
+    const int delta = ((int)((c - (uint32_t)k) << (32 - BITS))) >> (32 - BITS);
+    return k + delta;
+}
+
+}  // namespace swarm

@@ -1,0 +1,664 @@
+// C ABI of the swarm-interaction library: handle, validation, host-side bookkeeping and
+// kernel sequencing.  Every arithmetic step of an interaction runs in the kernels of
+// this directory; the host code below only validates arguments, keeps the small
+// per-round metadata (pairs, unmatched nodes, staleness, pending marks) and enqueues.
+#include "swarm.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "internal.h"
+#include "objectives.h"
+#include "philox.hpp"
+
+using namespace swarm;
+
+namespace {
+
+constexpr int DESC_SLOTS = 4;   // pinned staging slots for per-round metadata
+
+enum ObjectiveKind { OBJ_NONE = 0, OBJ_DIAG, OBJ_LSQ, OBJ_MLP };
+
+}  // namespace
+
+struct swarm_ctx {
+    swarm_config cfg{};
+    std::vector<uint32_t> edges;                 // 2 per edge, as given
+    std::vector<uint64_t> edge_keys;             // sorted (min << 32 | max) for membership tests
+    std::vector<std::vector<uint32_t>> adj;      // sorted neighbour lists
+    hipStream_t stream = nullptr;
+    int device = 0;
+    float inv_eps = 0.f;
+    uint64_t row_bytes = 0;
+
+    float *X = nullptr, *W = nullptr, *Xhat = nullptr;
+    uint8_t *ring = nullptr;
+    uint32_t *edges_dev = nullptr, *prio_dev = nullptr, *counts_dev = nullptr, *nodes_dev = nullptr;
+    uint32_t *linf_dev = nullptr;
+    uint8_t *desc_dev = nullptr;                 // pairs | singles | stale | pending
+    DeviceCounters *counters_dev = nullptr;
+    double *partials_dev = nullptr, *gamma_dev = nullptr;
+
+    // pinned host staging
+    uint8_t *desc_host[DESC_SLOTS] = {nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t desc_free[DESC_SLOTS] = {nullptr, nullptr, nullptr, nullptr};
+    unsigned desc_next = 0;
+    uint32_t *match_host = nullptr;              // counts[2] | pairs | singles
+    double *scalar_host = nullptr;
+
+    size_t off_pairs = 0, off_singles = 0, off_stale = 0, off_pending = 0, desc_bytes = 0;
+
+    std::vector<uint8_t> pending;                // host mirror: W_i carries unapplied steps
+    ObjectiveKind kind = OBJ_NONE;
+    DiagObjective diag{};
+    LsqObjective lsq{};
+    MlpObjective mlp{};
+
+    uint64_t round = 0, interactions = 0, bits_communicated = 0;
+    std::vector<hipEvent_t> ev_gossip, ev_local;   // start/stop pairs, created on demand
+    uint32_t timed_gossip = 0, timed_local = 0;    // recorded calls since the last reset
+    std::string err;
+
+    uint32_t *pairs_dev() const { return (uint32_t *)(desc_dev + off_pairs); }
+    uint32_t *singles_dev() const { return (uint32_t *)(desc_dev + off_singles); }
+    uint8_t *stale_dev() const { return desc_dev + off_stale; }
+    uint8_t *pending_dev() const { return desc_dev + off_pending; }
+};
+
+namespace {
+
+thread_local std::string g_init_error;
+
+swarm_status fail(swarm_t h, swarm_status code, const std::string &msg) {
+    if (h) h->err = msg; else g_init_error = msg;
+    return code;
+}
+
+#define SWARM_HIP(h, expr)                                                                          \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess)                                                                       \
+            return fail(h, e_ == hipErrorOutOfMemory ? SWARM_ENOMEM : SWARM_EDEVICE,                \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));                         \
+    } while (0)
+
+bool valid_bits(uint32_t b) { return b == 2 || b == 4 || b == 8 || b == 16; }
+
+uint64_t edge_key(uint32_t u, uint32_t v) { return ((uint64_t)std::min(u, v) << 32) | std::max(u, v); }
+
+GossipArgs gossip_args(swarm_t h, uint32_t event, uint32_t slot) {
+    GossipArgs a{};
+    a.X = h->X; a.W = h->W; a.Xhat = h->Xhat; a.ring = h->ring;
+    a.pairs = h->pairs_dev(); a.singles = h->singles_dev();
+    a.pending = h->pending_dev(); a.stale = h->stale_dev();
+    a.counters = h->counters_dev;
+    a.d = h->cfg.d; a.row_bytes = h->row_bytes; a.seed = h->cfg.seed;
+    a.n = h->cfg.n; a.event = event; a.slot_now = slot; a.ring_depth = h->cfg.stale_max + 1;
+    a.eps = h->cfg.eps; a.inv_eps = h->inv_eps;
+    return a;
+}
+
+// Take the next pinned staging slot once the copy that last used it has completed.
+swarm_status acquire_desc(swarm_t h, uint8_t **slot, unsigned *index) {
+    const unsigned s = h->desc_next++ % DESC_SLOTS;
+    SWARM_HIP(h, hipEventSynchronize(h->desc_free[s]));
+    *slot = h->desc_host[s];
+    *index = s;
+    return SWARM_OK;
+}
+
+constexpr uint32_t MAX_TIMED_CALLS = 1024;
+
+// Record the start (which = 0) or stop (which = 1) event of timed call number `call`.
+swarm_status record_timing(swarm_t h, std::vector<hipEvent_t> &events, uint32_t call, int which) {
+    if (call >= MAX_TIMED_CALLS) return SWARM_OK;
+    while (events.size() < 2 * (size_t)(call + 1)) {
+        hipEvent_t e = nullptr;
+        SWARM_HIP(h, hipEventCreate(&e));
+        events.push_back(e);
+    }
+    SWARM_HIP(h, hipEventRecord(events[2 * call + which], h->stream));
+    return SWARM_OK;
+}
+
+#define SWARM_TRY(expr)                     \
+    do {                                    \
+        const swarm_status rc_ = (expr);    \
+        if (rc_ != SWARM_OK) return rc_;    \
+    } while (0)
+
+swarm_status run_local_steps(swarm_t h, const float *base, const uint32_t *nodes_dev, uint32_t count,
+                             uint32_t single_node, uint32_t event) {
+    const swarm_config &c = h->cfg;
+    hipError_t e = hipSuccess;
+    switch (h->kind) {
+        case OBJ_DIAG:
+            e = launch_local_diag(base, h->W, h->diag.a, h->diag.c, nodes_dev, count, c.d, c.H, c.lr,
+                                  h->diag.sigma, c.seed, event, h->stream);
+            break;
+        case OBJ_LSQ:
+            e = launch_local_lsq(base, h->W, h->lsq, nodes_dev, count, c.d, c.H, c.lr, c.seed, event, h->stream);
+            break;
+        case OBJ_MLP:
+            e = launch_local_mlp(base, h->W, h->mlp, nodes_dev, count, c.n, c.d, c.H, c.lr, c.seed, event,
+                                 h->stream);
+            break;
+        default:
+            return fail(h, SWARM_ESTATE, "no objective set");
+    }
+    (void)single_node;
+    SWARM_HIP(h, e);
+    return SWARM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *swarm_last_error(swarm_t h) { return h ? h->err.c_str() : g_init_error.c_str(); }
+
+swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_stream, swarm_t *out) {
+    if (!cfg || !out) return fail(nullptr, SWARM_EINVAL, "null config or output");
+    *out = nullptr;
+    if (cfg->n < 2) return fail(nullptr, SWARM_EINVAL, "n must be >= 2");
+    if (cfg->n > MATCHING_MAX_NODES) return fail(nullptr, SWARM_EINVAL, "n exceeds 4096");
+    if (cfg->d == 0 || cfg->d % 8 != 0) return fail(nullptr, SWARM_EINVAL, "d must be a positive multiple of 8");
+    if (cfg->bits != 0 && !valid_bits(cfg->bits)) return fail(nullptr, SWARM_EINVAL, "bits must be 0, 2, 4, 8 or 16");
+    if (cfg->bits != 0 && !(cfg->eps > 0.f) ) return fail(nullptr, SWARM_EINVAL, "eps must be positive");
+    if (cfg->bits == 0 && cfg->stale_max != 0) return fail(nullptr, SWARM_EINVAL, "stale reads need quantized codes");
+    if (cfg->stale_max > 254) return fail(nullptr, SWARM_EINVAL, "stale_max exceeds 254");
+    if (cfg->H > 255) return fail(nullptr, SWARM_EINVAL, "H exceeds 255");
+    if (cfg->n_edges == 0 || !cfg->edges) return fail(nullptr, SWARM_EINVAL, "graph has no edges");
+    if (cfg->n_edges > MATCHING_MAX_EDGES) return fail(nullptr, SWARM_EINVAL, "too many edges");
+
+    swarm_ctx *h = new (std::nothrow) swarm_ctx();
+    if (!h) return fail(nullptr, SWARM_ENOMEM, "host allocation failed");
+    h->cfg = *cfg;
+    h->edges.assign(cfg->edges, cfg->edges + 2 * (size_t)cfg->n_edges);
+    h->cfg.edges = h->edges.data();
+    h->adj.resize(cfg->n);
+    for (uint32_t e = 0; e < cfg->n_edges; ++e) {
+        const uint32_t u = h->edges[2 * e], v = h->edges[2 * e + 1];
+        if (u >= cfg->n || v >= cfg->n || u == v) {
+            delete h;
+            return fail(nullptr, SWARM_EINVAL, "edge endpoint out of range or self loop");
+        }
+        h->edge_keys.push_back(edge_key(u, v));
+        h->adj[u].push_back(v);
+        h->adj[v].push_back(u);
+    }
+    std::sort(h->edge_keys.begin(), h->edge_keys.end());
+    if (std::adjacent_find(h->edge_keys.begin(), h->edge_keys.end()) != h->edge_keys.end()) {
+        delete h;
+        return fail(nullptr, SWARM_EINVAL, "duplicate edge");
+    }
+    for (auto &a : h->adj) std::sort(a.begin(), a.end());
+    h->stream = (hipStream_t)hip_stream;
+    h->inv_eps = cfg->bits ? 1.0f / cfg->eps : 0.f;
+    h->row_bytes = cfg->d * cfg->bits / 8;
+    h->pending.assign(cfg->n, 0);
+
+    const uint32_t n = cfg->n;
+    h->off_pairs = 0;
+    h->off_singles = h->off_pairs + sizeof(uint32_t) * 2 * (n / 2);
+    h->off_stale = h->off_singles + sizeof(uint32_t) * n;
+    h->off_pending = h->off_stale + n;
+    h->desc_bytes = h->off_pending + n;
+
+    swarm_status rc = SWARM_OK;
+    auto body = [&]() -> swarm_status {
+        SWARM_HIP(h, hipGetDevice(&h->device));
+        const size_t model_bytes = (size_t)n * cfg->d * sizeof(float);
+        SWARM_HIP(h, hipMalloc((void **)&h->X, model_bytes));
+        SWARM_HIP(h, hipMalloc((void **)&h->W, model_bytes));
+        if (cfg->bits) {
+            const size_t ring_bytes = (size_t)(cfg->stale_max + 1) * n * h->row_bytes;
+            SWARM_HIP(h, hipMalloc((void **)&h->ring, ring_bytes));
+            SWARM_HIP(h, hipMemsetAsync(h->ring, 0, ring_bytes, h->stream));   // registers start as zero vectors
+        }
+        SWARM_HIP(h, hipMalloc((void **)&h->edges_dev, sizeof(uint32_t) * 2 * cfg->n_edges));
+        SWARM_HIP(h, hipMalloc((void **)&h->prio_dev, sizeof(uint32_t) * cfg->n_edges));
+        SWARM_HIP(h, hipMalloc((void **)&h->counts_dev, sizeof(uint32_t) * 2));
+        SWARM_HIP(h, hipMalloc((void **)&h->nodes_dev, sizeof(uint32_t) * n));
+        SWARM_HIP(h, hipMalloc((void **)&h->linf_dev, sizeof(uint32_t) * (n / 2)));
+        SWARM_HIP(h, hipMalloc((void **)&h->desc_dev, h->desc_bytes));
+        SWARM_HIP(h, hipMalloc((void **)&h->counters_dev, sizeof(DeviceCounters)));
+        SWARM_HIP(h, hipMalloc((void **)&h->partials_dev, sizeof(double) * potential_partials(cfg->d)));
+        SWARM_HIP(h, hipMalloc((void **)&h->gamma_dev, sizeof(double)));
+        for (int s = 0; s < DESC_SLOTS; ++s) {
+            SWARM_HIP(h, hipHostMalloc((void **)&h->desc_host[s], h->desc_bytes, hipHostMallocDefault));
+            SWARM_HIP(h, hipEventCreateWithFlags(&h->desc_free[s], hipEventDisableTiming));
+            SWARM_HIP(h, hipEventRecord(h->desc_free[s], h->stream));
+        }
+        SWARM_HIP(h, hipHostMalloc((void **)&h->match_host, sizeof(uint32_t) * (2 + 2 * (n / 2) + n),
+                                   hipHostMallocDefault));
+        SWARM_HIP(h, hipHostMalloc((void **)&h->scalar_host, 64, hipHostMallocDefault));
+        SWARM_HIP(h, hipMemcpyAsync(h->edges_dev, h->edges.data(), sizeof(uint32_t) * 2 * cfg->n_edges,
+                                    hipMemcpyHostToDevice, h->stream));
+        SWARM_HIP(h, hipMemsetAsync(h->counters_dev, 0, sizeof(DeviceCounters), h->stream));
+        SWARM_HIP(h, hipMemsetAsync(h->desc_dev, 0, h->desc_bytes, h->stream));
+        if (x0_dev) {
+            SWARM_HIP(h, hipMemcpy2DAsync(h->X, cfg->d * sizeof(float), x0_dev, 0, cfg->d * sizeof(float), n,
+                                          hipMemcpyDeviceToDevice, h->stream));
+        } else {
+            SWARM_HIP(h, hipMemsetAsync(h->X, 0, model_bytes, h->stream));
+        }
+        SWARM_HIP(h, hipMemcpyAsync(h->W, h->X, model_bytes, hipMemcpyDeviceToDevice, h->stream));
+        SWARM_HIP(h, hipStreamSynchronize(h->stream));
+        return SWARM_OK;
+    };
+    rc = body();
+    if (rc != SWARM_OK) {
+        g_init_error = h->err;
+        swarm_destroy(h);
+        return rc;
+    }
+    *out = h;
+    return SWARM_OK;
+}
+
+swarm_status swarm_destroy(swarm_t h) {
+    if (!h) return SWARM_OK;
+    (void)hipStreamSynchronize(h->stream);
+    free_lsq(h->lsq);
+    free_mlp(h->mlp);
+    void *dev[] = {h->X, h->W, h->Xhat, h->ring, h->edges_dev, h->prio_dev, h->counts_dev, h->nodes_dev,
+                   h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev};
+    for (void *p : dev) if (p) (void)hipFree(p);
+    for (int s = 0; s < DESC_SLOTS; ++s) {
+        if (h->desc_host[s]) (void)hipHostFree(h->desc_host[s]);
+        if (h->desc_free[s]) (void)hipEventDestroy(h->desc_free[s]);
+    }
+    if (h->match_host) (void)hipHostFree(h->match_host);
+    if (h->scalar_host) (void)hipHostFree(h->scalar_host);
+    for (hipEvent_t e : h->ev_gossip) (void)hipEventDestroy(e);
+    for (hipEvent_t e : h->ev_local) (void)hipEventDestroy(e);
+    delete h;
+    return SWARM_OK;
+}
+
+swarm_status swarm_set_objective_diag(swarm_t h, const float *a_dev, const float *c_dev, float sigma) {
+    if (!h) return SWARM_EINVAL;
+    if (!a_dev || !c_dev || !(sigma >= 0.f)) return fail(h, SWARM_EINVAL, "diag objective: null data or negative sigma");
+    h->diag = DiagObjective{a_dev, c_dev, sigma};
+    h->kind = OBJ_DIAG;
+    return SWARM_OK;
+}
+
+swarm_status swarm_set_objective_lsq(swarm_t h, const float *A_dev, const float *b_dev, uint32_t m_rows,
+                                     uint32_t batch) {
+    if (!h) return SWARM_EINVAL;
+    if (!A_dev || !b_dev || m_rows == 0 || batch == 0 || batch % 4 != 0 || batch > LSQ_MAX_BATCH)
+        return fail(h, SWARM_EINVAL, "lsq objective: batch must be a multiple of 4, at most 64");
+    free_lsq(h->lsq);
+    h->lsq = LsqObjective{};
+    h->lsq.A = A_dev; h->lsq.b = b_dev; h->lsq.m_rows = m_rows; h->lsq.batch = batch;
+    h->kind = OBJ_LSQ;
+    return SWARM_OK;
+}
+
+swarm_status swarm_set_objective_mlp(swarm_t h, uint32_t n_in, uint32_t n_hid, uint32_t n_out,
+                                     const float *class_means_dev, const float *label_cdf_dev, float data_sigma,
+                                     uint32_t batch) {
+    if (!h) return SWARM_EINVAL;
+    if (!class_means_dev || !label_cdf_dev) return fail(h, SWARM_EINVAL, "mlp objective: null data");
+    if (n_in % 32 || n_hid % 32 || n_out % 32 || batch % 32 || !n_in || !n_hid || !n_out || !batch)
+        return fail(h, SWARM_EINVAL, "mlp objective: sizes must be positive multiples of 32");
+    if ((uint64_t)n_hid * n_in + n_hid + (uint64_t)n_out * n_hid + n_out != h->cfg.d)
+        return fail(h, SWARM_EINVAL, "mlp objective: d != hid*in + hid + out*hid + out");
+    free_mlp(h->mlp);
+    h->mlp = MlpObjective{};
+    h->mlp.n_in = n_in; h->mlp.n_hid = n_hid; h->mlp.n_out = n_out; h->mlp.batch = batch;
+    h->mlp.means = class_means_dev; h->mlp.cdf = label_cdf_dev; h->mlp.data_sigma = data_sigma;
+    const hipError_t e = alloc_mlp(h->mlp, h->cfg.n);
+    if (e != hipSuccess) return fail(h, e == hipErrorOutOfMemory ? SWARM_ENOMEM : SWARM_EDEVICE,
+                                     std::string("mlp workspace: ") + hipGetErrorString(e));
+    h->kind = OBJ_MLP;
+    return SWARM_OK;
+}
+
+swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count) {
+    if (!h) return SWARM_EINVAL;
+    if (h->kind == OBJ_NONE) return fail(h, SWARM_ESTATE, "no objective set");
+    const uint32_t n = h->cfg.n;
+    const uint32_t *nodes_dev = nullptr;
+    if (nodes) {
+        if (count == 0 || count > n) return fail(h, SWARM_EINVAL, "node count out of range");
+        std::vector<uint8_t> seen(n, 0);
+        for (uint32_t k = 0; k < count; ++k) {
+            if (nodes[k] >= n || seen[nodes[k]]) return fail(h, SWARM_EINVAL, "node id out of range or repeated");
+            seen[nodes[k]] = 1;
+        }
+        SWARM_HIP(h, hipMemcpyAsync(h->nodes_dev, nodes, sizeof(uint32_t) * count, hipMemcpyHostToDevice, h->stream));
+        nodes_dev = h->nodes_dev;
+    } else {
+        count = n;
+    }
+    SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 0));
+    SWARM_TRY(run_local_steps(h, h->X, nodes_dev, count, 0, (uint32_t)h->round));
+    SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 1));
+    h->timed_local += 1;
+    if (nodes) for (uint32_t k = 0; k < count; ++k) h->pending[nodes[k]] = 1;
+    else std::fill(h->pending.begin(), h->pending.end(), 1);
+    return SWARM_OK;
+}
+
+static swarm_status sample_matching_device(swarm_t h, uint32_t *npairs, uint32_t *nsingles) {
+    const swarm_config &c = h->cfg;
+    SWARM_HIP(h, launch_matching(h->edges_dev, c.n_edges, c.n, c.seed, (uint32_t)h->round, h->prio_dev,
+                                 h->pairs_dev(), h->singles_dev(), h->counts_dev, h->stream));
+    const uint32_t maxp = c.n / 2;
+    SWARM_HIP(h, hipMemcpyAsync(h->match_host, h->counts_dev, sizeof(uint32_t) * 2, hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2, h->pairs_dev(), sizeof(uint32_t) * 2 * maxp,
+                                hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2 + 2 * maxp, h->singles_dev(), sizeof(uint32_t) * c.n,
+                                hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    *npairs = h->match_host[0];
+    *nsingles = h->match_host[1];
+    if (*npairs > maxp || *nsingles > c.n || 2 * *npairs + *nsingles != c.n)
+        return fail(h, SWARM_EDEVICE, "matching kernel returned inconsistent counts");
+    return SWARM_OK;
+}
+
+swarm_status swarm_sample_matching(swarm_t h, uint32_t *pairs_host, uint32_t *npairs) {
+    if (!h) return SWARM_EINVAL;
+    if (!pairs_host || !npairs) return fail(h, SWARM_EINVAL, "null output");
+    uint32_t np = 0, ns = 0;
+    const swarm_status rc = sample_matching_device(h, &np, &ns);
+    if (rc != SWARM_OK) return rc;
+    std::memcpy(pairs_host, h->match_host + 2, sizeof(uint32_t) * 2 * np);
+    *npairs = np;
+    return SWARM_OK;
+}
+
+swarm_status swarm_sample_stale(swarm_t h, uint8_t *stale_host) {
+    if (!h) return SWARM_EINVAL;
+    if (!stale_host) return fail(h, SWARM_EINVAL, "null output");
+    for (uint32_t i = 0; i < h->cfg.n; ++i) {
+        const uint32_t s = scaled_index(stream(h->cfg.seed, TAG_STALE, 0, i, (uint32_t)h->round, 0).w0,
+                                        h->cfg.stale_max + 1);
+        stale_host[i] = (uint8_t)std::min<uint64_t>(s, h->round);
+    }
+    return SWARM_OK;
+}
+
+swarm_status swarm_sample_pair(swarm_t h, uint32_t *i, uint32_t *j) {
+    if (!h) return SWARM_EINVAL;
+    if (!i || !j) return fail(h, SWARM_EINVAL, "null output");
+    const Words4 w = stream(h->cfg.seed, TAG_PICK, 0, 0, (uint32_t)h->interactions, 0);
+    *i = scaled_index(w.w0, h->cfg.n);
+    const std::vector<uint32_t> &nb = h->adj[*i];
+    if (nb.empty()) return fail(h, SWARM_ESTATE, "initiator has no neighbour");
+    *j = nb[scaled_index(w.w1, (uint32_t)nb.size())];
+    return SWARM_OK;
+}
+
+swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t npairs, const uint8_t *stale_host) {
+    if (!h) return SWARM_EINVAL;
+    const swarm_config &c = h->cfg;
+    const uint32_t n = c.n;
+    std::vector<uint32_t> pairs, singles;
+    uint32_t nsingles = 0;
+    bool device_pairs = false;
+    if (pairs_host) {
+        if (npairs > n / 2) return fail(h, SWARM_EINVAL, "more pairs than floor(n/2)");
+        std::vector<uint8_t> used(n, 0);
+        for (uint32_t p = 0; p < npairs; ++p) {
+            const uint32_t u = pairs_host[2 * p], v = pairs_host[2 * p + 1];
+            if (u >= n || v >= n || u == v) return fail(h, SWARM_EINVAL, "pair endpoint out of range");
+            if (!std::binary_search(h->edge_keys.begin(), h->edge_keys.end(), edge_key(u, v)))
+                return fail(h, SWARM_EINVAL, "pair is not an edge of the graph");
+            if (used[u] || used[v]) return fail(h, SWARM_EINVAL, "node appears in two pairs");
+            used[u] = used[v] = 1;
+        }
+        pairs.assign(pairs_host, pairs_host + 2 * (size_t)npairs);
+        for (uint32_t u = 0; u < n; ++u) if (!used[u]) singles.push_back(u);
+        nsingles = (uint32_t)singles.size();
+    } else {
+        const swarm_status rc = sample_matching_device(h, &npairs, &nsingles);
+        if (rc != SWARM_OK) return rc;
+        pairs.assign(h->match_host + 2, h->match_host + 2 + 2 * (size_t)npairs);
+        singles.assign(h->match_host + 2 + 2 * (n / 2), h->match_host + 2 + 2 * (n / 2) + nsingles);
+        device_pairs = true;
+    }
+    std::vector<uint8_t> stale(n, 0);
+    if (stale_host) {
+        for (uint32_t u = 0; u < n; ++u) {
+            if (stale_host[u] > c.stale_max) return fail(h, SWARM_EINVAL, "staleness exceeds stale_max");
+            stale[u] = (uint8_t)std::min<uint64_t>(stale_host[u], h->round);   // only rounds that exist
+        }
+    }
+    // Which kernel specialisation serves all pairs?
+    uint32_t with_delta = 0, with_stale = 0;
+    for (uint32_t k = 0; k < 2 * npairs; ++k) {
+        with_delta += h->pending[pairs[k]] != 0;
+        with_stale += stale[pairs[k]] != 0;
+    }
+    const int delta_mode = with_delta == 0 ? 0 : (with_delta == 2 * npairs ? 1 : 2);
+    const int stale_mode = with_stale == 0 ? 0 : (with_stale == 2 * npairs ? 1 : 2);
+
+    uint8_t *slot = nullptr;
+    unsigned slot_index = 0;
+    const swarm_status rc = acquire_desc(h, &slot, &slot_index);
+    if (rc != SWARM_OK) return rc;
+    std::memcpy(slot + h->off_stale, stale.data(), n);
+    std::memcpy(slot + h->off_pending, h->pending.data(), n);
+    if (!device_pairs) {
+        if (npairs) std::memcpy(slot + h->off_pairs, pairs.data(), sizeof(uint32_t) * 2 * npairs);
+        if (nsingles) std::memcpy(slot + h->off_singles, singles.data(), sizeof(uint32_t) * nsingles);
+        SWARM_HIP(h, hipMemcpyAsync(h->desc_dev, slot, h->desc_bytes, hipMemcpyHostToDevice, h->stream));
+    } else {
+        SWARM_HIP(h, hipMemcpyAsync(h->desc_dev + h->off_stale, slot + h->off_stale, 2 * (size_t)n,
+                                    hipMemcpyHostToDevice, h->stream));
+    }
+    SWARM_HIP(h, hipEventRecord(h->desc_free[slot_index], h->stream));
+
+    const GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
+    SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
+    SWARM_HIP(h, launch_gossip_pairs(a, c.bits, delta_mode, stale_mode, npairs, h->stream));
+    SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
+    h->timed_gossip += 1;
+    // unmatched nodes: publish their code (needed by later stale reads) and apply their own steps
+    bool singles_work = c.bits != 0;
+    for (uint32_t u : singles) singles_work |= h->pending[u] != 0;
+    if (singles_work) SWARM_HIP(h, launch_gossip_singles(a, c.bits, nsingles, h->stream));
+
+    std::fill(h->pending.begin(), h->pending.end(), 0);
+    h->round += 1;
+    h->interactions += npairs;
+    h->bits_communicated += 2ull * npairs * c.d * (c.bits ? c.bits : 32);
+    return SWARM_OK;
+}
+
+swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
+    if (!h) return SWARM_EINVAL;
+    const swarm_config &c = h->cfg;
+    if (c.stale_max != 0) return fail(h, SWARM_EINVAL, "Algorithm 1 steps need stale_max = 0");
+    if (i >= c.n || j >= c.n || i == j ||
+        !std::binary_search(h->edge_keys.begin(), h->edge_keys.end(), edge_key(i, j)))
+        return fail(h, SWARM_EINVAL, "responder is not a neighbour of the initiator");
+    const size_t model_bytes = (size_t)c.n * c.d * sizeof(float);
+    if (!h->Xhat) {   // snapshots start equal to the models
+        SWARM_HIP(h, hipMalloc((void **)&h->Xhat, model_bytes));
+        SWARM_HIP(h, hipMemcpyAsync(h->Xhat, h->X, model_bytes, hipMemcpyDeviceToDevice, h->stream));
+    }
+    bool has_delta = h->pending[i] != 0;
+    if (c.H > 0 && h->kind != OBJ_NONE) {
+        SWARM_HIP(h, hipMemcpyAsync(h->nodes_dev, &i, sizeof(uint32_t), hipMemcpyHostToDevice, h->stream));
+        SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 0));
+        SWARM_TRY(run_local_steps(h, h->Xhat, h->nodes_dev, 1, i, (uint32_t)h->interactions));
+        SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 1));
+        h->timed_local += 1;
+        has_delta = true;
+    }
+    const GossipArgs a = gossip_args(h, (uint32_t)h->interactions, 0);
+    SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
+    SWARM_HIP(h, launch_interact(a, c.bits, i, j, has_delta, h->stream));
+    SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
+    h->timed_gossip += 1;
+    h->pending[i] = 0;
+    h->interactions += 1;
+    h->bits_communicated += 2ull * c.d * (c.bits ? c.bits : 32);
+    return SWARM_OK;
+}
+
+swarm_status swarm_quantize(const float *x_dev, uint64_t d, float eps, uint32_t bits, uint64_t seed, uint32_t node,
+                            uint32_t event, void *codes_dev, void *hip_stream) {
+    if (!x_dev || !codes_dev || d == 0 || d % 8 != 0 || !valid_bits(bits) || !(eps > 0.f))
+        return fail(nullptr, SWARM_EINVAL, "quantize: bad argument");
+    const hipError_t e = launch_quantize(x_dev, d, eps, 1.0f / eps, bits, seed, node, event, (uint8_t *)codes_dev,
+                                         nullptr, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SWARM_OK : fail(nullptr, SWARM_EDEVICE, hipGetErrorString(e));
+}
+
+swarm_status swarm_dequantize(const void *codes_dev, const float *key_dev, uint64_t d, float eps, uint32_t bits,
+                              float *out_dev, void *hip_stream) {
+    if (!codes_dev || !key_dev || !out_dev || d == 0 || d % 8 != 0 || !valid_bits(bits) || !(eps > 0.f))
+        return fail(nullptr, SWARM_EINVAL, "dequantize: bad argument");
+    const hipError_t e = launch_dequantize((const uint8_t *)codes_dev, key_dev, d, eps, 1.0f / eps, bits, out_dev,
+                                           (hipStream_t)hip_stream);
+    return e == hipSuccess ? SWARM_OK : fail(nullptr, SWARM_EDEVICE, hipGetErrorString(e));
+}
+
+static float *matrix_of(swarm_t h, uint32_t which) {
+    switch (which) {
+        case SWARM_MODELS_COMM: return h->X;
+        case SWARM_MODELS_LIVE: return h->W;
+        case SWARM_MODELS_SNAP: return h->Xhat;
+        default: return nullptr;
+    }
+}
+
+static swarm_status check_window(swarm_t h, uint32_t which, uint32_t node0, uint32_t count, uint64_t k0, uint64_t len,
+                                 const void *host) {
+    if (which > SWARM_MODELS_SNAP) return fail(h, SWARM_EINVAL, "unknown model matrix");
+    if (!matrix_of(h, which)) return fail(h, SWARM_ESTATE, "snapshots exist only after swarm_interact");
+    if (!host || count == 0 || len == 0 || (uint64_t)node0 + count > h->cfg.n || k0 + len > h->cfg.d)
+        return fail(h, SWARM_EINVAL, "window out of range");
+    return SWARM_OK;
+}
+
+swarm_status swarm_read_models(swarm_t h, uint32_t which, uint32_t node0, uint32_t count, uint64_t k0, uint64_t len,
+                               float *dst_host) {
+    if (!h) return SWARM_EINVAL;
+    const swarm_status rc = check_window(h, which, node0, count, k0, len, dst_host);
+    if (rc != SWARM_OK) return rc;
+    const float *src = matrix_of(h, which) + (uint64_t)node0 * h->cfg.d + k0;
+    SWARM_HIP(h, hipMemcpy2DAsync(dst_host, len * sizeof(float), src, h->cfg.d * sizeof(float), len * sizeof(float),
+                                  count, hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    return SWARM_OK;
+}
+
+swarm_status swarm_write_models(swarm_t h, uint32_t which, uint32_t node0, uint32_t count, uint64_t k0, uint64_t len,
+                                const float *src_host) {
+    if (!h) return SWARM_EINVAL;
+    const swarm_status rc = check_window(h, which, node0, count, k0, len, src_host);
+    if (rc != SWARM_OK) return rc;
+    float *dst = matrix_of(h, which) + (uint64_t)node0 * h->cfg.d + k0;
+    SWARM_HIP(h, hipMemcpy2DAsync(dst, h->cfg.d * sizeof(float), src_host, len * sizeof(float), len * sizeof(float),
+                                  count, hipMemcpyHostToDevice, h->stream));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    if (which == SWARM_MODELS_LIVE) for (uint32_t u = node0; u < node0 + count; ++u) h->pending[u] = 1;
+    if (which == SWARM_MODELS_COMM) for (uint32_t u = node0; u < node0 + count; ++u) h->pending[u] = 0;
+    return SWARM_OK;
+}
+
+swarm_status swarm_models_ptr(swarm_t h, uint32_t which, float **ptr_dev) {
+    if (!h) return SWARM_EINVAL;
+    if (!ptr_dev || which > SWARM_MODELS_SNAP) return fail(h, SWARM_EINVAL, "unknown model matrix");
+    *ptr_dev = matrix_of(h, which);
+    return *ptr_dev ? SWARM_OK : fail(h, SWARM_ESTATE, "snapshots exist only after swarm_interact");
+}
+
+swarm_status swarm_read_codes(swarm_t h, uint32_t age, uint32_t node, uint64_t byte0, uint64_t len,
+                              uint8_t *dst_host) {
+    if (!h) return SWARM_EINVAL;
+    const swarm_config &c = h->cfg;
+    if (!c.bits) return fail(h, SWARM_ESTATE, "no codes with bits = 0");
+    if (!dst_host || node >= c.n || age > c.stale_max || byte0 + len > h->row_bytes || len == 0)
+        return fail(h, SWARM_EINVAL, "code window out of range");
+    // the last completed event wrote slot (round-1) mod depth in round mode; Algorithm 1 steps write slot 0
+    const uint64_t depth = c.stale_max + 1;
+    const uint64_t last = h->round ? (h->round - 1) % depth : 0;
+    const uint64_t slot = (last + depth - age) % depth;
+    const uint8_t *src = h->ring + (slot * c.n + node) * h->row_bytes + byte0;
+    SWARM_HIP(h, hipMemcpyAsync(dst_host, src, len, hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    return SWARM_OK;
+}
+
+swarm_status swarm_potential(swarm_t h, double *gamma_host, float *mu_dev) {
+    if (!h) return SWARM_EINVAL;
+    if (!gamma_host) return fail(h, SWARM_EINVAL, "null output");
+    SWARM_HIP(h, launch_potential(h->X, h->cfg.n, h->cfg.d, mu_dev, h->partials_dev, potential_partials(h->cfg.d),
+                                  h->gamma_dev, h->stream));
+    SWARM_HIP(h, hipMemcpyAsync(h->scalar_host, h->gamma_dev, sizeof(double), hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    *gamma_host = *h->scalar_host;
+    return SWARM_OK;
+}
+
+swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npairs, float *linf_host) {
+    if (!h) return SWARM_EINVAL;
+    if (!pairs_host || !linf_host || npairs == 0 || npairs > h->cfg.n / 2)
+        return fail(h, SWARM_EINVAL, "pair list out of range");
+    for (uint32_t k = 0; k < 2 * npairs; ++k)
+        if (pairs_host[k] >= h->cfg.n) return fail(h, SWARM_EINVAL, "pair endpoint out of range");
+    SWARM_HIP(h, hipMemcpyAsync(h->pairs_dev(), pairs_host, sizeof(uint32_t) * 2 * npairs, hipMemcpyHostToDevice,
+                                h->stream));
+    SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * npairs, h->stream));
+    SWARM_HIP(h, launch_pair_linf(h->X, h->cfg.d, h->pairs_dev(), npairs, h->linf_dev, h->stream));
+    SWARM_HIP(h, hipMemcpyAsync(linf_host, h->linf_dev, sizeof(uint32_t) * npairs, hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    return SWARM_OK;
+}
+
+swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions, uint64_t *bits_communicated,
+                            uint64_t *decode_failures) {
+    if (!h) return SWARM_EINVAL;
+    DeviceCounters *dc = (DeviceCounters *)h->scalar_host;
+    SWARM_HIP(h, hipMemcpyAsync(dc, h->counters_dev, sizeof(DeviceCounters), hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    if (rounds) *rounds = h->round;
+    if (interactions) *interactions = h->interactions;
+    if (bits_communicated) *bits_communicated = h->bits_communicated;
+    if (decode_failures) *decode_failures = dc->decode_failures;
+    if (dc->range_clamped) return fail(h, SWARM_ERANGE, "|x/eps| reached the clamp 2^29");
+    return SWARM_OK;
+}
+
+swarm_status swarm_timing_reset(swarm_t h) {
+    if (!h) return SWARM_EINVAL;
+    h->timed_gossip = h->timed_local = 0;
+    return SWARM_OK;
+}
+
+swarm_status swarm_kernel_times(swarm_t h, double *gossip_ms, uint32_t *gossip_calls, double *local_ms,
+                                uint32_t *local_calls) {
+    if (!h) return SWARM_EINVAL;
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    auto total = [&](const std::vector<hipEvent_t> &ev, uint32_t calls, double *ms, uint32_t *count) -> swarm_status {
+        const uint32_t recorded = std::min(calls, MAX_TIMED_CALLS);
+        double sum = 0.0;
+        for (uint32_t k = 0; k < recorded; ++k) {
+            float t = 0.f;
+            SWARM_HIP(h, hipEventElapsedTime(&t, ev[2 * k], ev[2 * k + 1]));
+            sum += t;
+        }
+        if (ms) *ms = sum;
+        if (count) *count = recorded;
+        return SWARM_OK;
+    };
+    SWARM_TRY(total(h->ev_gossip, h->timed_gossip, gossip_ms, gossip_calls));
+    SWARM_TRY(total(h->ev_local, h->timed_local, local_ms, local_calls));
+    return SWARM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,43 @@
+"""Shared helpers of the GPU parity tests: build the oracle and the HIP swarm from one
+configuration and force the oracle's state into the device ("teacher forcing")."""
+import numpy as np
+
+from oracle.swarm import SwarmOracle
+
+TOL_ELEMENTWISE = 1e-6     # averaging and elementwise updates (float32 path vs float64 oracle)
+TOL_GEMM = 1e-4            # GEMM-based gradients
+
+
+def close(gpu, cpu, tol):
+    """|gpu - cpu| <= tol * max(1, |cpu|) elementwise (relative error is ill-defined near 0)."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    cpu = np.asarray(cpu, dtype=np.float64)
+    return np.abs(gpu - cpu) <= tol * np.maximum(1.0, np.abs(cpu))
+
+
+def assert_close(gpu, cpu, tol, what=""):
+    ok = close(gpu, cpu, tol)
+    if not ok.all():
+        bad = np.argwhere(~ok)
+        idx = tuple(bad[0])
+        raise AssertionError(f"{what}: {(~ok).sum()} of {ok.size} entries differ, first at {idx}: "
+                             f"gpu={np.asarray(gpu)[idx]!r} cpu={np.asarray(cpu)[idx]!r}")
+
+
+def make_both(swarm_mod, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0):
+    gpu = swarm_mod.Swarm(n, d, edges, bits, eps, H, lr, stale_max, seed)
+    cpu = SwarmOracle(n, d, edges, bits, eps, H, lr, stale_max, seed)
+    return gpu, cpu
+
+
+def force_state(swarm_mod, gpu, cpu):
+    """Upload the oracle's X, and W of the nodes with pending local steps."""
+    gpu.write_models(swarm_mod.COMM, cpu.X)
+    for i in np.flatnonzero(cpu.pending):
+        gpu.write_models(swarm_mod.LIVE, cpu.W[i:i + 1], node0=int(i))
+
+
+def ring_row(cpu, node, age=0):
+    depth = cpu.S + 1
+    last = (cpu.round - 1) % depth if cpu.round else 0
+    return cpu.ring[(last - age) % depth][node]

@@ -1,0 +1,256 @@
+"""GPU parity: the HIP library against the CPU oracle on identical seeded inputs.
+Integer work (codes, matchings, random streams) must be bit-exact; float32 results are
+within 1e-6 * max(1, |oracle|) for averaging and elementwise updates."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import quantizer as qz
+from oracle import rng
+from oracle.objectives import DiagQuadratic
+from helpers import TOL_ELEMENTWISE, assert_close, force_state, make_both, ring_row
+
+pytestmark = pytest.mark.gpu
+
+D_RAGGED = 8 * 5231          # 81.7 tiles of 512 coordinates: several workgroups and a ragged tail
+
+
+def models(gen, n, d, scale=1.0):
+    return (gen.standard_normal((n, d)) * scale).astype(np.float32)
+
+
+# ------------------------------------------------------------------ stateless codec
+@pytest.mark.parametrize("bits", [2, 4, 8, 16])
+@pytest.mark.parametrize("d", [8, 512, D_RAGGED])
+def test_quantize_codes_bit_exact(gpu, bits, d):
+    gen = np.random.Generator(np.random.PCG64(bits * 1000 + d))
+    x = (gen.standard_normal(d) * 3).astype(np.float32)
+    x[:: 7] *= -1
+    if d > 100:
+        x[5], x[6], x[17], x[18] = 0.0, -0.0, 1e-40, -1e-40
+    for eps in (2.0 ** -5, 0.01):
+        seed, node, event = 0x1234567890ABCDEF, 3, 77
+        got = gpu.quantize(torch.from_numpy(x).cuda(), eps, bits, seed, node, event).cpu().numpy()
+        want = qz.quantize(x, eps, bits, rng.sr_halves(seed, node, event, 0, d))
+        assert np.array_equal(got, want), f"bits={bits} d={d} eps={eps}"
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8, 16])
+def test_dequantize_against_key(gpu, bits):
+    gen = np.random.Generator(np.random.PCG64(bits))
+    d, eps = D_RAGGED, 2.0 ** -4
+    x = models(gen, 1, d)[0]
+    key = (x + gen.uniform(-1, 1, d) * eps * (1 << bits)).astype(np.float32)     # some inside, some outside the radius
+    codes = qz.quantize(x, eps, bits, rng.sr_halves(1, 0, 0, 0, d))
+    got = gpu.dequantize(torch.from_numpy(codes).cuda(), torch.from_numpy(key).cuda(), eps, bits).cpu().numpy()
+    want = qz.dequantize(codes, key, eps, bits)
+    assert np.array_equal(got.astype(np.float64), want)      # eps is a power of two: exact
+
+
+def test_quantize_clamps_like_the_oracle(gpu):
+    x = np.zeros(64, dtype=np.float32)
+    x[3], x[9] = 3e9, -3e9
+    eps = 1.0
+    got = gpu.quantize(torch.from_numpy(x).cuda(), eps, 8, 0, 0, 0).cpu().numpy()
+    assert np.array_equal(got, qz.quantize(x, eps, 8, rng.sr_halves(0, 0, 0, 0, 64)))
+
+
+# ------------------------------------------------------------------ fused gossip pass
+@pytest.mark.parametrize("bits", [2, 4, 8, 16])
+def test_gossip_round_teacher_forced_fresh(gpu, bits):
+    """Three rounds, fresh reads; local-step deltas absent / on every node / on some."""
+    n, d, eps = 8, D_RAGGED, 2.0 ** -4
+    edges = wl.complete_graph(n)
+    g, c = make_both(gpu, n, d, edges, bits, eps, 0, 0.0, 0, seed=bits)
+    gen = np.random.Generator(np.random.PCG64(bits))
+    spread = {2: 0.01, 4: 0.1, 8: 1.0, 16: 3.0}[bits]
+    for rnd, pend in enumerate([[], list(range(n)), [0, 3, 4, 6]]):
+        base = models(gen, 1, d)
+        c.X[:] = base + models(gen, n, d, spread)
+        c.pending[:] = False
+        for i in pend:
+            c.W[i] = c.X[i] + models(gen, 1, d, 0.05)[0]
+            c.pending[i] = True
+        force_state(gpu, g, c)
+        pairs = [(0, 5), (2, 3), (7, 1)]
+        c.gossip_round(pairs)
+        g.gossip_round(pairs)
+        for i in range(n):
+            assert np.array_equal(g.read_codes(i), ring_row(c, i)), f"codes of node {i}, round {rnd}"
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"X after round {rnd}")
+    cnt = g.counters()
+    assert cnt["rounds"] == 3 and cnt["interactions"] == 9
+    assert cnt["bits_communicated"] == c.bits_communicated
+    assert cnt["decode_failures"] == c.decode_failures
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_gossip_round_teacher_forced_stale(gpu, bits):
+    """Ring of 3 slots; reads 0, 1 or 2 rounds old, uniform and mixed within a pair."""
+    n, d, eps, S = 6, D_RAGGED, 2.0 ** -3, 2
+    edges = wl.complete_graph(n)
+    g, c = make_both(gpu, n, d, edges, bits, eps, 0, 0.0, S, seed=40 + bits)
+    gen = np.random.Generator(np.random.PCG64(40 + bits))
+    base = models(gen, 1, d)
+    spread = 0.05 if bits == 4 else 1.0
+    plans = [([(0, 1), (2, 3)], [0] * n), ([(0, 2), (1, 5)], [1] * n), ([(3, 4), (0, 5)], [2, 2, 2, 2, 2, 2]),
+             ([(1, 2), (4, 5)], [0, 1, 2, 0, 0, 1]), ([(0, 3)], [2, 0, 0, 1, 0, 0]), ([(2, 5), (1, 4)], [1] * n)]
+    for rnd, (pairs, stale) in enumerate(plans):
+        c.X[:] = base + models(gen, n, d, spread)
+        c.pending[:] = False
+        for i in range(0, n, 2):
+            c.W[i] = c.X[i] + models(gen, 1, d, 0.02)[0]
+            c.pending[i] = True
+        force_state(gpu, g, c)
+        c.gossip_round(pairs, stale)
+        g.gossip_round(pairs, stale)
+        for i in range(n):
+            for age in range(min(S, rnd) + 1):
+                assert np.array_equal(g.read_codes(i, age=age), ring_row(c, i, age)), (rnd, i, age)
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"X after round {rnd}")
+    assert g.counters()["decode_failures"] == c.decode_failures
+
+
+def test_decode_failures_wrap_identically(gpu):
+    """Rows farther apart than the radius: both sides land on the same wrong lattice point."""
+    n, d, eps, bits = 4, 1024, 0.5, 4
+    g, c = make_both(gpu, n, d, wl.complete_graph(n), bits, eps, 0, 0.0, 0, seed=1)
+    gen = np.random.Generator(np.random.PCG64(1))
+    c.X[:] = models(gen, n, d, 4.0)
+    force_state(gpu, g, c)
+    c.gossip_round([(0, 1), (2, 3)])
+    g.gossip_round([(0, 1), (2, 3)])
+    assert c.decode_failures > 0
+    assert g.counters()["decode_failures"] == c.decode_failures
+    assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, "wrapped averages")
+
+
+def test_identity_quantizer_round_preserves_the_mean(gpu):
+    n, d = 8, D_RAGGED
+    g, c = make_both(gpu, n, d, wl.torus_graph(2, 4), 0, 0.0, 0, 0.0, 0)
+    gen = np.random.Generator(np.random.PCG64(2))
+    c.X[:] = models(gen, n, d)
+    force_state(gpu, g, c)
+    mean0 = c.X.astype(np.float64).mean(axis=0)
+    pairs = [(0, 1), (2, 6), (3, 7)]
+    c.gossip_round(pairs)
+    g.gossip_round(pairs)
+    X = g.read_models(gpu.COMM)
+    assert_close(X, c.X, TOL_ELEMENTWISE, "plain averages")
+    assert np.abs(X.astype(np.float64).mean(axis=0) - mean0).max() < 1e-6
+    assert np.array_equal(X[0], X[1]) and np.array_equal(X[4], c.X[4])
+
+
+def test_range_clamp_is_reported(gpu):
+    n, d = 2, 64
+    g, c = make_both(gpu, n, d, wl.complete_graph(n), 8, 2.0 ** -20, 0, 0.0)
+    c.X[:] = 1e6
+    force_state(gpu, g, c)
+    c.gossip_round([(0, 1)])
+    g.gossip_round([(0, 1)])
+    assert c.range_clamped and g.counters(raise_on_range=False)["range_clamped"]
+    with pytest.raises(gpu.SwarmError):
+        g.counters()
+
+
+# ------------------------------------------------------------------ local steps, diagonal quadratics
+@pytest.mark.parametrize("sigma", [0.0, 0.1])
+def test_local_steps_diag_quadratic(gpu, sigma):
+    n, d, H, lr = 6, D_RAGGED, 3, 0.1
+    a, cc = wl.diag_quadratic_data(n, d, 5)
+    g, c = make_both(gpu, n, d, wl.complete_graph(n), 8, 2.0 ** -4, H, lr, 0, seed=9)
+    c.objective = DiagQuadratic(a, cc, sigma)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), sigma)
+    gen = np.random.Generator(np.random.PCG64(3))
+    c.X[:] = models(gen, n, d)
+    force_state(gpu, g, c)
+    c.local_steps()
+    g.local_steps()
+    assert_close(g.read_models(gpu.LIVE), c.W, TOL_ELEMENTWISE, "W after local steps")
+    assert np.array_equal(g.read_models(gpu.COMM), c.X)            # not applied yet
+    # the pending update reaches X through the gossip pass, and unmatched nodes apply their own
+    pairs = [(0, 1), (2, 3)]
+    c.gossip_round(pairs)
+    g.gossip_round(pairs)
+    assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, "X after the round")
+    # a subset of nodes, next round's random stream
+    force_state(gpu, g, c)
+    c.local_steps([4, 1])
+    g.local_steps([4, 1])
+    W = g.read_models(gpu.LIVE)
+    assert_close(W[[4, 1]], c.W[[4, 1]], TOL_ELEMENTWISE, "W of the chosen nodes")
+
+
+# ------------------------------------------------------------------ pair selection
+@pytest.mark.parametrize("graph", ["torus", "regular4", "regular8", "complete"])
+def test_matching_identical_to_oracle(gpu, graph):
+    n, edges = {"torus": (64, wl.torus_graph(8, 8)), "regular4": (64, wl.random_regular_graph(64, 4, 2)),
+                "regular8": (256, wl.random_regular_graph(256, 8, 3)), "complete": (33, wl.complete_graph(33))}[graph]
+    g, c = make_both(gpu, n, 8, edges, 8, 1.0, 0, 0.0, 0, seed=123)
+    for r in range(12):
+        want = c.sample_matching()
+        got = g.sample_matching()
+        assert np.array_equal(got, want.astype(np.uint32)), f"round {r}"
+        c.gossip_round(want)
+        g.gossip_round(None)                   # samples the same matching internally
+        assert g.counters()["interactions"] == c.interactions
+
+
+def test_stale_and_pair_draws_identical_to_oracle(gpu):
+    n = 32
+    g, c = make_both(gpu, n, 8, wl.random_regular_graph(n, 4, 4), 8, 1.0, 0, 0.0, 2, seed=77)
+    for r in range(6):
+        assert np.array_equal(g.sample_stale(), c.sample_stale().astype(np.uint8))
+        c.gossip_round([])
+        g.gossip_round([])
+    g2, c2 = make_both(gpu, n, 8, wl.random_regular_graph(n, 4, 4), 0, 0.0, 0, 0.0, 0, seed=78)
+    for t in range(40):
+        pair = c2.sample_pair()
+        assert g2.sample_pair() == pair
+        c2.interact(*pair)
+        g2.interact(*pair)
+
+
+# ------------------------------------------------------------------ reductions
+def test_potential_mean_and_pair_linf(gpu):
+    n, d = 12, D_RAGGED
+    g, c = make_both(gpu, n, d, wl.complete_graph(n), 8, 1.0, 0, 0.0)
+    gen = np.random.Generator(np.random.PCG64(8))
+    c.X[:] = models(gen, n, d) + 100.0          # large common offset: the shifted sums must not cancel badly
+    force_state(gpu, g, c)
+    mu = torch.empty(d, dtype=torch.float32, device="cuda")
+    gamma = g.potential(mu)
+    assert gamma == pytest.approx(c.potential(), rel=1e-9)
+    assert_close(mu.cpu().numpy(), c.mean(), TOL_ELEMENTWISE, "mean model")
+    pairs = [(0, 1), (5, 2), (11, 7)]
+    want = [np.abs(c.X[i] - c.X[j]).max() for i, j in pairs]
+    assert np.array_equal(g.pair_linf(pairs), np.array(want, dtype=np.float32))
+
+
+# ------------------------------------------------------------------ boundary errors
+def test_boundary_rejects_bad_arguments(gpu):
+    edges = wl.torus_graph(2, 4)
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(8, 12, edges, 8, 1.0, 0, 0.0)                       # d not a multiple of 8
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(8, 64, edges, 3, 1.0, 0, 0.0)                       # unsupported code width
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(8, 64, edges, 0, 1.0, 0, 0.0, stale_max=1)          # stale reads need codes
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(8, 64, [(0, 0)], 8, 1.0, 0, 0.0)                    # self loop
+    g = gpu.Swarm(8, 64, edges, 8, 1.0, 1, 0.1, stale_max=1)
+    for bad in ([(0, 5)], [(0, 1), (1, 2)], [(0, 9)]):                 # not an edge / node twice / out of range
+        with pytest.raises(gpu.SwarmError) as err:
+            g.gossip_round(bad)
+        assert err.value.status == gpu.EINVAL
+    with pytest.raises(gpu.SwarmError):
+        g.gossip_round([(0, 1)], stale=[2] * 8)                        # beyond stale_max
+    with pytest.raises(gpu.SwarmError) as err:
+        g.local_steps()                                                # no objective set
+    assert err.value.status == gpu.ESTATE
+    with pytest.raises(gpu.SwarmError):
+        g.interact(0, 1)                                               # Algorithm 1 needs stale_max = 0
+    assert g.counters()["rounds"] == 0                                 # rejected calls change nothing
+    g.gossip_round([])                                                 # an empty round is legal
+    assert g.counters()["rounds"] == 1

@@ -1,0 +1,48 @@
+"""CPU-side checks of the boundary: the shared library loads and exports every entry
+point the header declares (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "swarm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(swarm_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_calls_of_the_interaction():
+    names = declared_symbols()
+    for must in ["swarm_init", "swarm_local_steps", "swarm_gossip_round", "swarm_quantize", "swarm_dequantize",
+                 "swarm_read_models", "swarm_interact", "swarm_sample_matching", "swarm_potential"]:
+        assert must in names
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    import paper_1910_12308_amd as swarm
+    if not os.path.exists(swarm.LIB_PATH):
+        pytest.fail("libswarm.so is not built: run __graft_entry__.build()")
+    lib = ctypes.CDLL(swarm.LIB_PATH)
+    for name in declared_symbols():
+        assert hasattr(lib, name), f"{name} declared in swarm.h but not exported"
+    assert sorted(swarm.EXPORTS) == declared_symbols()
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    import paper_1910_12308_amd as swarm
+    monkeypatch.setattr(swarm, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(ImportError):
+        swarm.load_library()
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1910_12308_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".hpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f

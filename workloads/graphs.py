@@ -32,21 +32,32 @@ def _connected(n, edges):
 
 
 def random_regular_graph(n, degree, seed):
-    """Pairing model with rejection until the graph is simple and connected."""
+    """Random simple connected `degree`-regular graph: stubs are paired at random, a pair
+    that would make a loop or a repeated edge goes back into the pool, and the attempt
+    restarts when only unusable stubs remain."""
     assert (n * degree) % 2 == 0 and degree < n
     gen = np.random.Generator(np.random.PCG64(seed))
     while True:
+        edges = set()
         stubs = np.repeat(np.arange(n), degree)
-        gen.shuffle(stubs)
-        pairs = stubs.reshape(-1, 2)
-        if (pairs[:, 0] == pairs[:, 1]).any():
+        stuck = False
+        while stubs.size and not stuck:
+            gen.shuffle(stubs)
+            left = []
+            for u, v in stubs.reshape(-1, 2).tolist():
+                key = (min(u, v), max(u, v))
+                if u != v and key not in edges:
+                    edges.add(key)
+                else:
+                    left += [u, v]
+            stuck = len(left) == stubs.size and not any(
+                u != v and (min(u, v), max(u, v)) not in edges for u in set(left) for v in set(left))
+            stubs = np.array(left, dtype=np.int64)
+        if stuck:
             continue
-        und = {(min(u, v), max(u, v)) for u, v in pairs.tolist()}
-        if len(und) != len(pairs):
-            continue
-        edges = np.array(sorted(und), dtype=np.uint32)
-        if _connected(n, edges):
-            return edges
+        arr = np.array(sorted(edges), dtype=np.uint32)
+        if _connected(n, arr):
+            return arr
 
 
 def adjacency(n, edges):
