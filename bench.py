@@ -177,6 +177,18 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_pair_coordinate": per_pc},
     }
+    # Measured ceiling: a plain streaming copy kernel over one model matrix worth of bytes.
+    src, dst = s.models_view(swarm.COMM), s.models_view(swarm.LIVE)   # W is rebuilt by every step
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    swarm.stream_copy(dst, src)
+    ev0.record()
+    for _ in range(5):
+        swarm.stream_copy(dst, src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * src.numel() * 4 * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    out["roofline"]["copy_kernel_GBps"] = copy_gbs
+    out["roofline"]["frac_of_copy"] = achieved / copy_gbs
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, edges, a, c, eps)
     print(json.dumps(out))

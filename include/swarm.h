@@ -178,6 +178,10 @@ swarm_status swarm_timing_reset(swarm_t h);
 swarm_status swarm_kernel_times(swarm_t h, double *gossip_ms, uint32_t *gossip_calls,
                                 double *local_ms, uint32_t *local_calls);
 
+/* Measurement aid: plain streaming copy of nbytes (a multiple of 16, at most 2^36) between
+ * device buffers on the given stream -- the copy rate the gossip pass is compared with. */
+swarm_status swarm_stream_copy(void *dst_dev, const void *src_dev, uint64_t nbytes, void *hip_stream);
+
 const char *swarm_last_error(swarm_t h);
 
 #ifdef __cplusplus

@@ -23,7 +23,7 @@ EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set
            "swarm_gossip_round", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
            "swarm_potential", "swarm_pair_linf", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
-           "swarm_last_error"]
+           "swarm_stream_copy", "swarm_last_error"]
 
 
 class SwarmError(RuntimeError):
@@ -68,6 +68,7 @@ def load_library():
         "swarm_pair_linf": [vp, vp, u32, vp],
         "swarm_counters": [vp, P(u64), P(u64), P(u64), P(u64)],
         "swarm_timing_reset": [vp],
+        "swarm_stream_copy": [vp, vp, u64, vp],
         "swarm_kernel_times": [vp, P(ctypes.c_double), P(u32), P(ctypes.c_double), P(u32)],
     }
     for name, argtypes in sig.items():
@@ -286,3 +287,12 @@ def dequantize(codes, key, eps, bits, stream=None):
     if rc != OK:
         raise SwarmError(rc, lib().swarm_last_error(None).decode())
     return out
+
+
+def stream_copy(dst, src, stream=None):
+    """Plain streaming copy kernel between two device tensors of equal byte size."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    rc = lib().swarm_stream_copy(_dev_ptr(dst), _dev_ptr(src), nbytes, _stream_ptr(stream))
+    if rc != OK:
+        raise SwarmError(rc, lib().swarm_last_error(None).decode())

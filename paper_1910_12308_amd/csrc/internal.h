@@ -56,6 +56,9 @@ uint32_t potential_partials(uint64_t d);
 hipError_t launch_pair_linf(const float *X, uint64_t d, const uint32_t *pairs, uint32_t npairs,
                             uint32_t *linf_bits, hipStream_t st);
 
+// Streaming copy of nbytes (multiple of 16, below 2^36) from src to dst.
+hipError_t launch_stream_copy(const void *src, void *dst, uint64_t nbytes, hipStream_t st);
+
 // Matching: one workgroup; outputs pairs (increasing edge index), their count, the
 // unmatched nodes and their count.
 hipError_t launch_matching(const uint32_t *edges, uint32_t n_edges, uint32_t n, uint64_t seed, uint32_t round,

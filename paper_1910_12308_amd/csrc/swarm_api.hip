@@ -634,6 +634,13 @@ swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions,
     return SWARM_OK;
 }
 
+swarm_status swarm_stream_copy(void *dst_dev, const void *src_dev, uint64_t nbytes, void *hip_stream) {
+    if (!dst_dev || !src_dev || nbytes == 0 || nbytes % 16 != 0 || nbytes > (1ull << 36))
+        return fail(nullptr, SWARM_EINVAL, "stream copy: size must be a multiple of 16, at most 2^36");
+    const hipError_t e = launch_stream_copy(src_dev, dst_dev, nbytes, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SWARM_OK : fail(nullptr, SWARM_EDEVICE, hipGetErrorString(e));
+}
+
 swarm_status swarm_timing_reset(swarm_t h) {
     if (!h) return SWARM_EINVAL;
     h->timed_gossip = h->timed_local = 0;
