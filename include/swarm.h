@@ -12,8 +12,8 @@
  * Conventions
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
  *   - The handle OWNS the model matrices X (current / communicated), W (live copy with
- *     the pending local steps), Xhat (model at the node's last initiation, created on
- *     first use of swarm_interact), and the ring of packed code rows.  Objective data
+ *     the pending local steps), Xhat (model at the node's last initiation, created as a
+ *     copy of X on first use), and the ring of packed code rows.  Objective data
  *     passed to swarm_set_objective_* is BORROWED: it must outlive the handle.
  *   - Host arrays are only read (or written) during the call.
  *   - Kernels are enqueued on the HIP stream given at swarm_init.  Calls return after

@@ -112,6 +112,15 @@ swarm_status acquire_desc(swarm_t h, uint8_t **slot, unsigned *index) {
     return SWARM_OK;
 }
 
+// Snapshots (models at the last initiation) start equal to the current models.
+swarm_status ensure_snapshots(swarm_t h) {
+    if (h->Xhat) return SWARM_OK;
+    const size_t model_bytes = (size_t)h->cfg.n * h->cfg.d * sizeof(float);
+    SWARM_HIP(h, hipMalloc((void **)&h->Xhat, model_bytes));
+    SWARM_HIP(h, hipMemcpyAsync(h->Xhat, h->X, model_bytes, hipMemcpyDeviceToDevice, h->stream));
+    return SWARM_OK;
+}
+
 constexpr uint32_t MAX_TIMED_CALLS = 1024;
 
 // Record the start (which = 0) or stop (which = 1) event of timed call number `call`.
@@ -483,10 +492,9 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     if (i >= c.n || j >= c.n || i == j ||
         !std::binary_search(h->edge_keys.begin(), h->edge_keys.end(), edge_key(i, j)))
         return fail(h, SWARM_EINVAL, "responder is not a neighbour of the initiator");
-    const size_t model_bytes = (size_t)c.n * c.d * sizeof(float);
-    if (!h->Xhat) {   // snapshots start equal to the models
-        SWARM_HIP(h, hipMalloc((void **)&h->Xhat, model_bytes));
-        SWARM_HIP(h, hipMemcpyAsync(h->Xhat, h->X, model_bytes, hipMemcpyDeviceToDevice, h->stream));
+    {
+        const swarm_status rc = ensure_snapshots(h);
+        if (rc != SWARM_OK) return rc;
     }
     bool has_delta = h->pending[i] != 0;
     if (c.H > 0 && h->kind != OBJ_NONE) {
@@ -538,7 +546,10 @@ static float *matrix_of(swarm_t h, uint32_t which) {
 static swarm_status check_window(swarm_t h, uint32_t which, uint32_t node0, uint32_t count, uint64_t k0, uint64_t len,
                                  const void *host) {
     if (which > SWARM_MODELS_SNAP) return fail(h, SWARM_EINVAL, "unknown model matrix");
-    if (!matrix_of(h, which)) return fail(h, SWARM_ESTATE, "snapshots exist only after swarm_interact");
+    if (which == SWARM_MODELS_SNAP) {
+        const swarm_status rc = ensure_snapshots(h);
+        if (rc != SWARM_OK) return rc;
+    }
     if (!host || count == 0 || len == 0 || (uint64_t)node0 + count > h->cfg.n || k0 + len > h->cfg.d)
         return fail(h, SWARM_EINVAL, "window out of range");
     return SWARM_OK;
@@ -573,8 +584,12 @@ swarm_status swarm_write_models(swarm_t h, uint32_t which, uint32_t node0, uint3
 swarm_status swarm_models_ptr(swarm_t h, uint32_t which, float **ptr_dev) {
     if (!h) return SWARM_EINVAL;
     if (!ptr_dev || which > SWARM_MODELS_SNAP) return fail(h, SWARM_EINVAL, "unknown model matrix");
+    if (which == SWARM_MODELS_SNAP) {
+        const swarm_status rc = ensure_snapshots(h);
+        if (rc != SWARM_OK) return rc;
+    }
     *ptr_dev = matrix_of(h, which);
-    return *ptr_dev ? SWARM_OK : fail(h, SWARM_ESTATE, "snapshots exist only after swarm_interact");
+    return SWARM_OK;
 }
 
 swarm_status swarm_read_codes(swarm_t h, uint32_t age, uint32_t node, uint64_t byte0, uint64_t len,

@@ -254,3 +254,80 @@ def test_boundary_rejects_bad_arguments(gpu):
     assert g.counters()["rounds"] == 0                                 # rejected calls change nothing
     g.gossip_round([])                                                 # an empty round is legal
     assert g.counters()["rounds"] == 1
+
+
+# ------------------------------------------------------------------ Algorithm 1 with least-squares objectives
+def test_algorithm1_least_squares_teacher_forced(gpu):
+    """The sequential model on the small workload's shape: n=8, d=4096, 256x4096 least squares per
+    node, batch 32, H=2, 8-bit codes; every step starts from the oracle's state."""
+    from oracle.objectives import LeastSquares
+    from helpers import TOL_GEMM
+    n, d, m, batch, H, lr, bits, eps = 8, 4096, 256, 32, 2, 0.05, 8, 2.0 ** -6
+    edges = wl.complete_graph(n)
+    A, b, _ = wl.least_squares_data(n, d, m, 0)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, 0, seed=0)
+    c.objective = LeastSquares(A, b, batch)
+    g.set_objective_lsq(torch.from_numpy(A).cuda(), torch.from_numpy(b).cuda(), m, batch)
+    for t in range(25):
+        g.write_models(gpu.COMM, c.X)
+        g.write_models(gpu.SNAP, c.Xhat)
+        i, j = c.sample_pair()
+        assert g.sample_pair() == (i, j)
+        c.interact(i, j)
+        g.interact(i, j)
+        assert np.array_equal(g.read_codes(i), c.ring[0][i]) and np.array_equal(g.read_codes(j), c.ring[0][j])
+        assert_close(g.read_models(gpu.LIVE, i, 1), c.W[i:i + 1], TOL_GEMM, f"W_i after local steps, t={t}")
+        X = g.read_models(gpu.COMM)
+        assert_close(X[j], c.X[j], TOL_ELEMENTWISE, f"responder model, t={t}")
+        assert_close(X[i], c.X[i], TOL_GEMM, f"initiator model, t={t}")
+        assert_close(g.read_models(gpu.SNAP), c.Xhat, TOL_GEMM, f"snapshots, t={t}")
+        others = [k for k in range(n) if k not in (i, j)]
+        assert np.array_equal(X[others], c.X[others])
+    assert g.counters()["bits_communicated"] == c.bits_communicated
+
+
+def test_algorithm1_free_running_matches_statistically(gpu):
+    """200 sequential interactions without forcing: a last-bit difference can flip a rounding
+    decision, so the runs are compared through the potential and the distance to the optimum."""
+    from oracle.objectives import LeastSquares
+    n, d, m, batch, H, lr, bits, eps = 8, 4096, 256, 32, 2, 0.05, 8, 2.0 ** -6
+    edges = wl.complete_graph(n)
+    A, b, xstar = wl.least_squares_data(n, d, m, 1)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, 0, seed=0)
+    c.objective = LeastSquares(A, b, batch)
+    g.set_objective_lsq(torch.from_numpy(A).cuda(), torch.from_numpy(b).cuda(), m, batch)
+    for t in range(200):
+        pair = c.sample_pair()
+        assert g.sample_pair() == pair
+        c.interact(*pair)
+        g.interact(*pair)
+    X = g.read_models(gpu.COMM).astype(np.float64)
+    assert np.abs(X - c.X).max() <= 8 * eps
+    assert (np.abs(X - c.X) > 1e-4).mean() < 0.05
+    assert g.potential() == pytest.approx(c.potential(), rel=0.05)
+    assert g.counters()["decode_failures"] == c.decode_failures == 0
+    # both moved from 0 toward the least-squares solution's neighbourhood
+    d0, d1 = np.linalg.norm(xstar), np.linalg.norm(X.mean(axis=0) - xstar)
+    assert d1 < d0
+
+
+def test_round_mode_free_running_matches_statistically(gpu):
+    """40 rounds on a torus with noisy diagonal quadratics, matching sampled on the device."""
+    n, d, H, lr, bits, eps = 16, 8192, 3, 0.1, 8, 2.0 ** -4
+    edges = wl.torus_graph(4, 4)
+    a, cc = wl.diag_quadratic_data(n, d, 2)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, 0, seed=3)
+    c.objective = DiagQuadratic(a, cc, 0.1)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.1)
+    gam_g, gam_c = [], []
+    for r in range(40):
+        c.local_steps()
+        g.local_steps()
+        c.gossip_round(c.sample_matching())
+        g.gossip_round(None)
+        gam_g.append(g.potential())
+        gam_c.append(c.potential())
+    assert np.allclose(gam_g, gam_c, rtol=0.02)
+    assert g.counters()["interactions"] == c.interactions
+    X = g.read_models(gpu.COMM).astype(np.float64)
+    assert np.abs(X - c.X).max() <= 8 * eps
