@@ -19,6 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per pair-coordinate of the fused gossip pass from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs,
+# scaled by the stream-copy calibration (17.00 B fetched + 8.99 B written at 4-bit codes, stale reads).
+MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {(4, True): 25.99}
 
 
 def algorithmic_bytes_per_pair_coordinate(bits, stale, delta=True):
@@ -174,7 +177,12 @@ def main():
                    "local_steps_GBps": local_gbs},
         "roofline": {"kernel": "gossip_pairs_kernel (fused quantize/exchange/decode/average)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": (MEASURED_TRAFFIC_PER_PAIR_COORDINATE[(bits, stale)] * d * interactions
+                                 / max(1, times["gossip_calls"])
+                                 if (bits, stale) in MEASURED_TRAFFIC_PER_PAIR_COORDINATE else None),
+                     "traffic_unit": "bytes per launch (counters, calibrated on the stream copy)",
+                     "achieved_bytes_per_launch": gossip_bytes / max(1, times["gossip_calls"]),
                      "bytes_per_pair_coordinate": per_pc},
     }
     # Measured ceiling: a plain streaming copy kernel over one model matrix worth of bytes.
