@@ -1,9 +1,331 @@
+// Local SGD steps for the two-layer perceptron objective (in -> hid -> out, ReLU,
+// softmax cross-entropy averaged over the batch) on a synthetic Gaussian mixture.
+// Every node has its own weights, so each step is a *grouped* problem: one launch per
+// GEMM covers all nodes (grid.z), each workgroup computing a 128x128 tile of one node's
+// product on the matrix cores (v_mfma_f32_32x32x2f32, float32 in and out).
+//
+// Per step:  data (labels, features)  ->  hid = relu(x W1^T + b1)  ->  logits = hid W2^T + b2
+//   -> dlogits = (softmax - onehot)/batch -> dpre = (dlogits W2) * [hid > 0]
+//   -> W2 -= eta dlogits^T hid, b2 -= eta colsum(dlogits), W1 -= eta dpre^T x, b1 -= eta colsum(dpre).
+// The weight updates are fused into the epilogues of the two weight-gradient GEMMs, so
+// the gradients never reach memory.
+//
+// Tiling: 4 waves per workgroup, each wave a 64x64 sub-tile = 2x2 MFMA blocks; K is
+// consumed in slabs of 16 staged through LDS (double buffered, next slab prefetched into
+// registers during the MFMAs).  A 32x32x2 MFMA takes one A and one B value per lane; lanes
+// 0-31 carry one k index and lanes 32-63 another, and any pairing is valid as long as A and
+// B agree, so lanes 0-31 take k 0..7 of the slab and lanes 32-63 take k 8..15: operands
+// whose k runs contiguously in memory are fetched from LDS with two 128-bit reads.
 #include "objectives.h"
+#include "philox.hpp"
+
 namespace swarm {
-hipError_t alloc_mlp(MlpObjective &o, uint32_t n_nodes) { o.n_nodes = n_nodes; return hipErrorNotSupported; }
-void free_mlp(MlpObjective &o) { o = MlpObjective{}; }
-hipError_t launch_local_mlp(const float *, float *, const MlpObjective &, const uint32_t *, uint32_t, uint32_t,
-                            uint64_t, uint32_t, float, uint64_t, uint32_t, hipStream_t) {
-    return hipErrorNotSupported;
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr int TM = 128, TN = 128, TK = 16;
+constexpr int LDK = TK + 4;      // row length of a [row][k] LDS tile (keeps 16-byte alignment, spreads banks)
+constexpr int LDR = TM + 4;      // row length of a [k][row] LDS tile
+
+enum Epilogue { EPI_BIAS_RELU = 0, EPI_BIAS = 1, EPI_RELU_MASK = 2, EPI_SGD_UPDATE = 3 };
+
+struct GemmArgs {
+    const float *A, *B;          // operand bases
+    float *C;                    // output base
+    const float *aux;            // bias (per node), ReLU mask source (per slot) or weights to update (per node)
+    const uint32_t *nodes;       // slot -> node id, or null for identity
+    uint64_t strideA, strideB, strideC, strideAux;   // elements between consecutive nodes / slots
+    uint32_t a_by_node, b_by_node, c_by_node, aux_by_node;
+    uint32_t M, N, K, lda, ldb, ldc, ldaux;
+    float lr;
+};
+
+// Load a 128 x 16 slab of an operand whose k index is contiguous in memory: P[row * ld + k].
+__device__ __forceinline__ void fetch_kc(const float *P, uint32_t ld, uint32_t row0, uint32_t rows, uint32_t k0,
+                                         f4 r[2]) {
+    const uint32_t t = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t row = row0 + (t >> 2) + 64 * i;
+        r[i] = row < rows ? *(const f4 *)(P + (uint64_t)row * ld + k0 + 4 * (t & 3)) : f4{0.f, 0.f, 0.f, 0.f};
+    }
 }
+__device__ __forceinline__ void stash_kc(float *lds, const f4 r[2]) {
+    const uint32_t t = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *(f4 *)(lds + ((t >> 2) + 64 * i) * LDK + 4 * (t & 3)) = r[i];
+}
+// Load a 16 x 128 slab of an operand whose row (m or n) index is contiguous: P[k * ld + row].
+__device__ __forceinline__ void fetch_rc(const float *P, uint32_t ld, uint32_t row0, uint32_t rows, uint32_t k0,
+                                         f4 r[2]) {
+    const uint32_t t = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t k = k0 + (t >> 5) + 8 * i, row = row0 + 4 * (t & 31);
+        r[i] = row < rows ? *(const f4 *)(P + (uint64_t)k * ld + row) : f4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+__device__ __forceinline__ void stash_rc(float *lds, const f4 r[2]) {
+    const uint32_t t = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *(f4 *)(lds + ((t >> 5) + 8 * i) * LDR + 4 * (t & 31)) = r[i];
+}
+
+// The 8 operand values of this lane for one 32-row MFMA block: rows row0 + (lane % 32), k run (lane / 32) * 8 .. +7.
+template <bool KC>
+__device__ __forceinline__ void operand(const float *lds, uint32_t row, uint32_t half, float v[8]) {
+    if (KC) {
+        const f4 lo = *(const f4 *)(lds + row * LDK + 8 * half), hi = *(const f4 *)(lds + row * LDK + 8 * half + 4);
+        v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+    } else {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) v[kk] = lds[(8 * half + kk) * LDR + row];
+    }
+}
+
+// C (M x N) = op(A) op(B) with A_KC: A stored [m][k] else [k][m]; B_KC: B stored [n][k] else [k][n].
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
+    constexpr int A_TILE = A_KC ? TM * LDK : TK * LDR, B_TILE = B_KC ? TN * LDK : TK * LDR;
+    __shared__ __attribute__((aligned(16))) float lds_a[2][A_TILE];
+    __shared__ __attribute__((aligned(16))) float lds_b[2][B_TILE];
+    const uint32_t slot = blockIdx.z, node = g.nodes ? g.nodes[slot] : slot;
+    const float *A = g.A + (g.a_by_node ? node : slot) * g.strideA;
+    const float *B = g.B + (g.b_by_node ? node : slot) * g.strideB;
+    float *C = g.C + (g.c_by_node ? node : slot) * g.strideC;
+    const float *aux = g.aux + (g.aux_by_node ? node : slot) * g.strideAux;
+    const uint32_t m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, half = lane >> 5, r32 = lane & 31u;
+    const uint32_t wm = (wave >> 1) * 64, wn = (wave & 1u) * 64;
+
+    f16v acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+    f4 ra[2], rb[2];
+    auto fetch = [&](uint32_t k0) {
+        if (A_KC) fetch_kc(A, g.lda, m0, g.M, k0, ra); else fetch_rc(A, g.lda, m0, g.M, k0, ra);
+        if (B_KC) fetch_kc(B, g.ldb, n0, g.N, k0, rb); else fetch_rc(B, g.ldb, n0, g.N, k0, rb);
+    };
+    auto stash = [&](int buf) {
+        if (A_KC) stash_kc(lds_a[buf], ra); else stash_rc(lds_a[buf], ra);
+        if (B_KC) stash_kc(lds_b[buf], rb); else stash_rc(lds_b[buf], rb);
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    const uint32_t slabs = g.K / TK;
+    for (uint32_t s = 0; s < slabs; ++s) {
+        const int cur = s & 1;
+        if (s + 1 < slabs) fetch((s + 1) * TK);
+        float a[2][8], b[2][8];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) operand<A_KC>(lds_a[cur], wm + 32 * mi + r32, half, a[mi]);
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) operand<B_KC>(lds_b[cur], wn + 32 * ni + r32, half, b[ni]);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][kk], b[ni][kk], acc[mi][ni], 0, 0, 0);
+        if (s + 1 < slabs) stash(cur ^ 1);
+        __syncthreads();
+    }
+    // Accumulator layout of the 32x32 block: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const uint32_t n = n0 + wn + 32 * ni + r32;
+            if (n >= g.N) continue;
+            float bias = 0.f;
+            if (EPI == EPI_BIAS_RELU || EPI == EPI_BIAS) bias = aux[n];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const uint32_t m = m0 + wm + 32 * mi + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (m >= g.M) continue;
+                float c = acc[mi][ni][v];
+                if (EPI == EPI_BIAS_RELU) c = fmaxf(c + bias, 0.f);
+                if (EPI == EPI_BIAS) c = c + bias;
+                if (EPI == EPI_RELU_MASK) c = aux[(uint64_t)m * g.ldaux + n] > 0.f ? c : 0.f;
+                if (EPI == EPI_SGD_UPDATE) c = fmaf(-g.lr, c, aux[(uint64_t)m * g.ldaux + n]);
+                C[(uint64_t)m * g.ldc + n] = c;
+            }
+        }
+}
+
+// Labels by inverse CDF: y = #{c : cdf[c] <= u}, u = (word >> 8) 2^-24, limited to n_out - 1.
+__global__ void mlp_labels_kernel(const float *__restrict__ cdf, const uint32_t *__restrict__ nodes,
+                                  uint32_t *__restrict__ labels, uint32_t n_out, uint32_t batch, uint64_t seed,
+                                  uint32_t event, uint32_t q) {
+    const uint32_t slot = blockIdx.x, node = nodes ? nodes[slot] : slot;
+    for (uint32_t s = threadIdx.x; s < batch; s += blockDim.x) {
+        const Words4 w = stream(seed, TAG_LABEL, q, node, event, s >> 2);
+        const uint32_t word = (s & 3u) == 0 ? w.w0 : (s & 3u) == 1 ? w.w1 : (s & 3u) == 2 ? w.w2 : w.w3;
+        const float u = (float)(word >> 8) * 0x1p-24f;
+        const float *row = cdf + (uint64_t)node * n_out;
+        uint32_t lo = 0, hi = n_out;                      // first index with cdf > u
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (row[mid] <= u) lo = mid + 1; else hi = mid;
+        }
+        labels[(uint64_t)slot * batch + s] = lo < n_out ? lo : n_out - 1;
+    }
+}
+
+// Features: x[s] = means[y_s] + sigma N(0, I); one Philox call per float4.
+__global__ __launch_bounds__(256) void mlp_features_kernel(const float *__restrict__ means,
+                                                           const uint32_t *__restrict__ nodes,
+                                                           const uint32_t *__restrict__ labels, float *__restrict__ x,
+                                                           uint32_t n_in, uint32_t batch, float sigma, uint64_t seed,
+                                                           uint32_t event, uint32_t q) {
+    const uint32_t slot = blockIdx.y, node = nodes ? nodes[slot] : slot;
+    const uint64_t f = (uint64_t)blockIdx.x * 256 + threadIdx.x;       // float4 index within the batch
+    if (f * 4 >= (uint64_t)batch * n_in) return;
+    const uint32_t s = (uint32_t)(f * 4 / n_in), k = (uint32_t)(f * 4 % n_in);
+    const uint32_t y = labels[(uint64_t)slot * batch + s];
+    const Words4 w = stream(seed, TAG_DATA, q, node, event, f);
+    float z0, z1, z2, z3;
+    box_muller(w.w0, w.w1, z0, z1);
+    box_muller(w.w2, w.w3, z2, z3);
+    const f4 mu = *(const f4 *)(means + (uint64_t)y * n_in + k);
+    f4 out;
+    out.x = fmaf(sigma, z0, mu.x); out.y = fmaf(sigma, z1, mu.y);
+    out.z = fmaf(sigma, z2, mu.z); out.w = fmaf(sigma, z3, mu.w);
+    *(f4 *)(x + ((uint64_t)slot * batch + s) * n_in + k) = out;
+}
+
+__device__ __forceinline__ float block_reduce(float v, float *lds, bool is_max) {
+    for (int off = 32; off > 0; off >>= 1) {
+        const float o = __shfl_xor(v, off);
+        v = is_max ? fmaxf(v, o) : v + o;
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = lds[0];
+    for (uint32_t w = 1; w < blockDim.x / 64; ++w) r = is_max ? fmaxf(r, lds[w]) : r + lds[w];
+    return r;
+}
+
+// In place: logits row -> (softmax - onehot(y)) / batch.
+__global__ __launch_bounds__(256) void mlp_softmax_grad_kernel(float *__restrict__ logits,
+                                                               const uint32_t *__restrict__ labels, uint32_t n_out,
+                                                               uint32_t batch) {
+    __shared__ float lds[4];
+    const uint32_t slot = blockIdx.y, s = blockIdx.x;
+    float *row = logits + ((uint64_t)slot * batch + s) * n_out;
+    float mx = -INFINITY;
+    for (uint32_t c = threadIdx.x; c < n_out; c += 256) mx = fmaxf(mx, row[c]);
+    mx = block_reduce(mx, lds, true);
+    float sum = 0.f;
+    for (uint32_t c = threadIdx.x; c < n_out; c += 256) sum += expf(row[c] - mx);
+    sum = block_reduce(sum, lds, false);
+    const uint32_t y = labels[(uint64_t)slot * batch + s];
+    const float inv_b = 1.0f / (float)batch;
+    for (uint32_t c = threadIdx.x; c < n_out; c += 256)
+        row[c] = (expf(row[c] - mx) / sum - (c == y ? 1.f : 0.f)) * inv_b;
+}
+
+// b_dst = b_src - lr * column sums of G (batch x width).
+__global__ __launch_bounds__(256) void mlp_bias_kernel(const float *__restrict__ G, const float *__restrict__ src,
+                                                       float *__restrict__ dst, const uint32_t *__restrict__ nodes,
+                                                       uint32_t width, uint32_t batch, uint64_t d, uint64_t bias_off,
+                                                       float lr) {
+    const uint32_t slot = blockIdx.y, node = nodes ? nodes[slot] : slot;
+    const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= width) return;
+    const float *g = G + (uint64_t)slot * batch * width;
+    float sum = 0.f;
+    for (uint32_t s = 0; s < batch; ++s) sum += g[(uint64_t)s * width + c];
+    dst[(uint64_t)node * d + bias_off + c] = fmaf(-lr, sum, src[(uint64_t)node * d + bias_off + c]);
+}
+
+hipError_t alloc_mlp(MlpObjective &o, uint32_t n_nodes) {
+    o.n_nodes = n_nodes;
+    const size_t b = o.batch;
+    hipError_t e;
+    if ((e = hipMalloc((void **)&o.x, sizeof(float) * n_nodes * b * o.n_in)) != hipSuccess) return e;
+    if ((e = hipMalloc((void **)&o.hid, sizeof(float) * n_nodes * b * o.n_hid)) != hipSuccess) return e;
+    if ((e = hipMalloc((void **)&o.dlogits, sizeof(float) * n_nodes * b * o.n_out)) != hipSuccess) return e;
+    if ((e = hipMalloc((void **)&o.dhid, sizeof(float) * n_nodes * b * o.n_hid)) != hipSuccess) return e;
+    if ((e = hipMalloc((void **)&o.labels, sizeof(uint32_t) * n_nodes * b)) != hipSuccess) return e;
+    return hipSuccess;
+}
+
+void free_mlp(MlpObjective &o) {
+    void *p[] = {o.x, o.hid, o.dlogits, o.dhid, o.labels};
+    for (void *q : p) if (q) (void)hipFree(q);
+    o = MlpObjective{};
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+static void gemm(const GemmArgs &g, uint32_t count, hipStream_t st) {
+    const dim3 grid((g.N + TN - 1) / TN, (g.M + TM - 1) / TM, count);
+    mlp_gemm_kernel<A_KC, B_KC, EPI><<<grid, 256, 0, st>>>(g);
+}
+
+hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, const uint32_t *nodes,
+                            uint32_t count, uint32_t n, uint64_t d, uint32_t H, float lr, uint64_t seed,
+                            uint32_t event, hipStream_t st) {
+    (void)n;
+    if (count == 0) return hipSuccess;
+    const uint32_t I = o.n_in, Hd = o.n_hid, O = o.n_out, Bt = o.batch;
+    const uint64_t off_b1 = (uint64_t)Hd * I, off_w2 = off_b1 + Hd, off_b2 = off_w2 + (uint64_t)O * Hd;
+    for (uint32_t q = 0; q < H; ++q) {
+        const float *src = q == 0 ? base : W;
+        mlp_labels_kernel<<<count, 128, 0, st>>>(o.cdf, nodes, o.labels, O, Bt, seed, event, q);
+        mlp_features_kernel<<<dim3((unsigned)(((uint64_t)Bt * I / 4 + 255) / 256), count), 256, 0, st>>>(
+            o.means, nodes, o.labels, o.x, I, Bt, o.data_sigma, seed, event, q);
+        GemmArgs g{};
+        g.nodes = nodes; g.lr = lr;
+        // hid = relu(x W1^T + b1):  M = batch, N = hid, K = in
+        g.A = o.x; g.strideA = (uint64_t)Bt * I; g.a_by_node = 0; g.lda = I;
+        g.B = src; g.strideB = d; g.b_by_node = 1; g.ldb = I;
+        g.C = o.hid; g.strideC = (uint64_t)Bt * Hd; g.c_by_node = 0; g.ldc = Hd;
+        g.aux = src + off_b1; g.strideAux = d; g.aux_by_node = 1; g.ldaux = 0;
+        g.M = Bt; g.N = Hd; g.K = I;
+        gemm<true, true, EPI_BIAS_RELU>(g, count, st);
+        // logits = hid W2^T + b2:  M = batch, N = out, K = hid
+        g.A = o.hid; g.strideA = (uint64_t)Bt * Hd; g.lda = Hd;
+        g.B = src + off_w2; g.ldb = Hd;
+        g.C = o.dlogits; g.strideC = (uint64_t)Bt * O; g.ldc = O;
+        g.aux = src + off_b2;
+        g.M = Bt; g.N = O; g.K = Hd;
+        gemm<true, true, EPI_BIAS>(g, count, st);
+        mlp_softmax_grad_kernel<<<dim3(Bt, count), 256, 0, st>>>(o.dlogits, o.labels, O, Bt);
+        // dpre = (dlogits W2) * [hid > 0]:  M = batch, N = hid, K = out;  W2 stored [k][n]
+        g.A = o.dlogits; g.strideA = (uint64_t)Bt * O; g.lda = O;
+        g.B = src + off_w2; g.ldb = Hd;
+        g.C = o.dhid; g.strideC = (uint64_t)Bt * Hd; g.ldc = Hd;
+        g.aux = o.hid; g.strideAux = (uint64_t)Bt * Hd; g.aux_by_node = 0; g.ldaux = Hd;
+        g.M = Bt; g.N = Hd; g.K = O;
+        gemm<true, false, EPI_RELU_MASK>(g, count, st);
+        // W2 <- W2 - eta dlogits^T hid:  M = out, N = hid, K = batch;  both operands stored [k][row]
+        g.A = o.dlogits; g.strideA = (uint64_t)Bt * O; g.a_by_node = 0; g.lda = O;
+        g.B = o.hid; g.strideB = (uint64_t)Bt * Hd; g.b_by_node = 0; g.ldb = Hd;
+        g.C = W + off_w2; g.strideC = d; g.c_by_node = 1; g.ldc = Hd;
+        g.aux = src + off_w2; g.strideAux = d; g.aux_by_node = 1; g.ldaux = Hd;
+        g.M = O; g.N = Hd; g.K = Bt;
+        gemm<false, false, EPI_SGD_UPDATE>(g, count, st);
+        mlp_bias_kernel<<<dim3((O + 255) / 256, count), 256, 0, st>>>(o.dlogits, src, W, nodes, O, Bt, d, off_b2, lr);
+        // W1 <- W1 - eta dpre^T x:  M = hid, N = in, K = batch
+        g.A = o.dhid; g.strideA = (uint64_t)Bt * Hd; g.lda = Hd;
+        g.B = o.x; g.strideB = (uint64_t)Bt * I; g.ldb = I;
+        g.C = W; g.ldc = I;
+        g.aux = src; g.ldaux = I;
+        g.M = Hd; g.N = I; g.K = Bt;
+        gemm<false, false, EPI_SGD_UPDATE>(g, count, st);
+        mlp_bias_kernel<<<dim3((Hd + 255) / 256, count), 256, 0, st>>>(o.dhid, src, W, nodes, Hd, Bt, d, off_b1, lr);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace swarm

@@ -334,6 +334,7 @@ swarm_status swarm_set_objective_mlp(swarm_t h, uint32_t n_in, uint32_t n_hid, u
 swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count) {
     if (!h) return SWARM_EINVAL;
     if (h->kind == OBJ_NONE) return fail(h, SWARM_ESTATE, "no objective set");
+    if (h->cfg.H == 0) return SWARM_OK;          // no steps: nothing becomes pending
     const uint32_t n = h->cfg.n;
     const uint32_t *nodes_dev = nullptr;
     if (nodes) {

@@ -331,3 +331,40 @@ def test_round_mode_free_running_matches_statistically(gpu):
     assert g.counters()["interactions"] == c.interactions
     X = g.read_models(gpu.COMM).astype(np.float64)
     assert np.abs(X - c.X).max() <= 8 * eps
+
+
+# ------------------------------------------------------------------ MLP local steps (MFMA GEMMs)
+@pytest.mark.parametrize("shape", [(64, 96, 32, 32), (256, 384, 128, 128)])
+def test_local_steps_mlp(gpu, shape):
+    """Two local steps of the two-layer perceptron on the Gaussian mixture: data generation,
+    forward, softmax-CE gradient, backward GEMMs and fused SGD updates against the float64 oracle."""
+    from oracle.objectives import MixtureMLP
+    from helpers import TOL_GEMM
+    n_in, n_hid, n_out, batch = shape
+    n, H, lr = 5, 2, 0.02
+    d = n_hid * n_in + n_hid + n_out * n_hid + n_out
+    means, cdf = wl.mixture_data(n, n_in, n_out, 3)
+    g, c = make_both(gpu, n, d, wl.complete_graph(n), 8, 2.0 ** -8, H, lr, 0, seed=21)
+    c.objective = MixtureMLP(n_in, n_hid, n_out, means, cdf, 0.5, batch)
+    g.set_objective_mlp(n_in, n_hid, n_out, torch.from_numpy(means).cuda(), torch.from_numpy(cdf).cuda(), 0.5, batch)
+    gen = np.random.Generator(np.random.PCG64(5))
+    c.X[:] = models(gen, n, d, 0.1)
+    force_state(gpu, g, c)
+    c.local_steps()
+    g.local_steps()
+    W = g.read_models(gpu.LIVE)
+    assert_close(W, c.W, TOL_GEMM, "weights after two local steps")
+    # the summed gradient itself: -(W - X) / eta
+    grad_gpu = (c.X.astype(np.float64) - W) / lr
+    grad_cpu = (c.X.astype(np.float64) - c.W) / lr
+    assert_close(grad_gpu, grad_cpu, TOL_GEMM, "summed stochastic gradient")
+    assert np.abs(grad_cpu).max() > 1e-3                                   # the comparison is not vacuous
+    # subset of nodes, then a gossip round on top
+    force_state(gpu, g, c)
+    c.local_steps([3, 0])
+    g.local_steps([3, 0])
+    assert_close(g.read_models(gpu.LIVE)[[3, 0]], c.W[[3, 0]], TOL_GEMM, "subset")
+    pairs = [(0, 3), (1, 2)]
+    c.gossip_round(pairs)
+    g.gossip_round(pairs)
+    assert_close(g.read_models(gpu.COMM), c.X, TOL_GEMM, "models after the round")
