@@ -19,7 +19,10 @@ namespace swarm {
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int TILE = 512;          // coordinates per wave
-constexpr int WAVES = 4;           // waves per workgroup
+#ifndef SWARM_GOSSIP_WAVES
+#define SWARM_GOSSIP_WAVES 8
+#endif
+constexpr int WAVES = SWARM_GOSSIP_WAVES;   // waves per workgroup
 
 __device__ __forceinline__ f4 ldg_nt(const float *p) { return __builtin_nontemporal_load((const f4 *)p); }
 __device__ __forceinline__ void stg_nt(float *p, f4 v) { __builtin_nontemporal_store(v, (f4 *)p); }

@@ -49,6 +49,9 @@ struct swarm_ctx {
     hipEvent_t desc_free[DESC_SLOTS] = {nullptr, nullptr, nullptr, nullptr};
     unsigned desc_next = 0;
     uint32_t *match_host = nullptr;              // counts[2] | pairs | singles
+    uint32_t *mpairs_dev = nullptr, *msingles_dev = nullptr;   // outputs of the matching kernel
+    hipEvent_t match_ready = nullptr;            // the matching of round match_round has reached match_host
+    uint64_t match_round = ~0ull;
     double *scalar_host = nullptr;
 
     size_t off_pairs = 0, off_singles = 0, off_stale = 0, off_pending = 0, desc_bytes = 0;
@@ -236,6 +239,9 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         SWARM_HIP(h, hipMalloc((void **)&h->nodes_dev, sizeof(uint32_t) * n));
         SWARM_HIP(h, hipMalloc((void **)&h->linf_dev, sizeof(uint32_t) * (n / 2)));
         SWARM_HIP(h, hipMalloc((void **)&h->desc_dev, h->desc_bytes));
+        SWARM_HIP(h, hipMalloc((void **)&h->mpairs_dev, sizeof(uint32_t) * 2 * (n / 2)));
+        SWARM_HIP(h, hipMalloc((void **)&h->msingles_dev, sizeof(uint32_t) * n));
+        SWARM_HIP(h, hipEventCreateWithFlags(&h->match_ready, hipEventDisableTiming));
         SWARM_HIP(h, hipMalloc((void **)&h->counters_dev, sizeof(DeviceCounters)));
         SWARM_HIP(h, hipMalloc((void **)&h->partials_dev, sizeof(double) * potential_partials(cfg->d)));
         SWARM_HIP(h, hipMalloc((void **)&h->gamma_dev, sizeof(double)));
@@ -277,13 +283,15 @@ swarm_status swarm_destroy(swarm_t h) {
     free_lsq(h->lsq);
     free_mlp(h->mlp);
     void *dev[] = {h->X, h->W, h->Xhat, h->ring, h->edges_dev, h->prio_dev, h->counts_dev, h->nodes_dev,
-                   h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev};
+                   h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev, h->mpairs_dev,
+                   h->msingles_dev};
     for (void *p : dev) if (p) (void)hipFree(p);
     for (int s = 0; s < DESC_SLOTS; ++s) {
         if (h->desc_host[s]) (void)hipHostFree(h->desc_host[s]);
         if (h->desc_free[s]) (void)hipEventDestroy(h->desc_free[s]);
     }
     if (h->match_host) (void)hipHostFree(h->match_host);
+    if (h->match_ready) (void)hipEventDestroy(h->match_ready);
     if (h->scalar_host) (void)hipHostFree(h->scalar_host);
     for (hipEvent_t e : h->ev_gossip) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_local) (void)hipEventDestroy(e);
@@ -358,20 +366,31 @@ swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count)
     return SWARM_OK;
 }
 
+// Enqueue the matching of the current round and its copy to pinned host memory.  The matching
+// depends only on (seed, round, graph), so it can be issued a round ahead: the host then finds
+// it ready instead of draining the stream.
+static swarm_status enqueue_matching(swarm_t h) {
+    const swarm_config &c = h->cfg;
+    const uint32_t maxp = c.n / 2;
+    SWARM_HIP(h, launch_matching(h->edges_dev, c.n_edges, c.n, c.seed, (uint32_t)h->round, h->prio_dev,
+                                 h->mpairs_dev, h->msingles_dev, h->counts_dev, h->stream));
+    SWARM_HIP(h, hipMemcpyAsync(h->match_host, h->counts_dev, sizeof(uint32_t) * 2, hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2, h->mpairs_dev, sizeof(uint32_t) * 2 * maxp,
+                                hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2 + 2 * maxp, h->msingles_dev, sizeof(uint32_t) * c.n,
+                                hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipEventRecord(h->match_ready, h->stream));
+    h->match_round = h->round;
+    return SWARM_OK;
+}
+
 static swarm_status sample_matching_device(swarm_t h, uint32_t *npairs, uint32_t *nsingles) {
     const swarm_config &c = h->cfg;
-    SWARM_HIP(h, launch_matching(h->edges_dev, c.n_edges, c.n, c.seed, (uint32_t)h->round, h->prio_dev,
-                                 h->pairs_dev(), h->singles_dev(), h->counts_dev, h->stream));
-    const uint32_t maxp = c.n / 2;
-    SWARM_HIP(h, hipMemcpyAsync(h->match_host, h->counts_dev, sizeof(uint32_t) * 2, hipMemcpyDeviceToHost, h->stream));
-    SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2, h->pairs_dev(), sizeof(uint32_t) * 2 * maxp,
-                                hipMemcpyDeviceToHost, h->stream));
-    SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2 + 2 * maxp, h->singles_dev(), sizeof(uint32_t) * c.n,
-                                hipMemcpyDeviceToHost, h->stream));
-    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    if (h->match_round != h->round) SWARM_TRY(enqueue_matching(h));
+    SWARM_HIP(h, hipEventSynchronize(h->match_ready));
     *npairs = h->match_host[0];
     *nsingles = h->match_host[1];
-    if (*npairs > maxp || *nsingles > c.n || 2 * *npairs + *nsingles != c.n)
+    if (*npairs > c.n / 2 || *nsingles > c.n || 2 * *npairs + *nsingles != c.n)
         return fail(h, SWARM_EDEVICE, "matching kernel returned inconsistent counts");
     return SWARM_OK;
 }
@@ -469,7 +488,8 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
     }
     SWARM_HIP(h, hipEventRecord(h->desc_free[slot_index], h->stream));
 
-    const GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
+    GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
+    if (device_pairs) { a.pairs = h->mpairs_dev; a.singles = h->msingles_dev; }
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
     SWARM_HIP(h, launch_gossip_pairs(a, c.bits, delta_mode, stale_mode, npairs, h->stream));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
@@ -483,6 +503,7 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
     h->round += 1;
     h->interactions += npairs;
     h->bits_communicated += 2ull * npairs * c.d * (c.bits ? c.bits : 32);
+    if (device_pairs) SWARM_TRY(enqueue_matching(h));   // next round's matching, one round ahead
     return SWARM_OK;
 }
 
