@@ -40,12 +40,17 @@ def build_workload(cfg_id, scale_d=None):
     n, d = cfg["n"], cfg["d"]
     if cfg["graph"] == "regular4":
         edges = wl.random_regular_graph(n, 4, 0)
+    elif cfg["graph"] == "regular8":
+        edges = wl.random_regular_graph(n, 8, 0)
     elif cfg["graph"] == "torus8x8":
         edges = wl.torus_graph(8, 8)
     elif cfg["graph"] == "complete":
         edges = wl.complete_graph(n)
     else:
         raise SystemExit(f"bench: graph {cfg['graph']} not supported here")
+    if cfg["objective"] == "mlp":
+        means, cdf = wl.mixture_data(n, cfg["n_in"], cfg["n_out"], 0, cfg["alpha"])
+        return cfg, edges, torch.from_numpy(means).cuda(), torch.from_numpy(cdf).cuda()
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0)
     # a ~ U[lo, hi] (or log-uniform), c ~ N(mu_i, 1), mu_i ~ N(0, shift^2): generated on the device, row by row
@@ -66,6 +71,10 @@ def build_workload(cfg_id, scale_d=None):
 
 def eps_for(cfg):
     # power of two so that the decoding radius (2^(b-1) - 5/2) eps covers the usual disagreement
+    if cfg["objective"] == "mlp":
+        return 2.0 ** -10          # weights of order 0.02: radius 125 eps = 0.12
+    if cfg["shift_sigma"] >= 2.0:
+        return 0.25                # strongly heterogeneous nodes sit several units apart
     return 0.5 if cfg["bits"] == 4 else 2.0 ** -4
 
 
@@ -85,6 +94,8 @@ def cpu_baseline(cfg, edges, a, c, eps, seconds_target=15.0):
     from oracle.objectives import DiagQuadratic
     from oracle.swarm import SwarmOracle
     n, d = cfg["n"], cfg["d"]
+    if cfg["objective"] == "mlp":
+        return cpu_baseline_mlp(cfg, edges, a, c, eps)
     width = 1 << 14
     result = None
     while True:
@@ -107,12 +118,34 @@ def cpu_baseline(cfg, edges, a, c, eps, seconds_target=15.0):
         width *= 4
 
 
+def cpu_baseline_mlp(cfg, edges, means, cdf, eps):
+    """The MLP objective needs whole models: time the oracle's local steps on two nodes and one
+    pairwise gossip of full rows, and scale to the whole swarm (n nodes, n/2 pairs)."""
+    import numpy as np
+    from oracle.objectives import MixtureMLP
+    from oracle.swarm import SwarmOracle
+    n, d = cfg["n"], cfg["d"]
+    sub = 2
+    o = SwarmOracle(sub, d, [(0, 1)], cfg["bits"], eps, cfg["H"], cfg["lr"], 0, 0)
+    o.objective = MixtureMLP(cfg["n_in"], cfg["n_hid"], cfg["n_out"], means.cpu().numpy(), cdf.cpu().numpy()[:sub],
+                             cfg["data_sigma"], cfg["batch"])
+    o.X[:] = 0.02 * np.random.Generator(np.random.PCG64(0)).standard_normal(d).astype(np.float32)
+    t0 = time.perf_counter()
+    o.local_steps()
+    o.gossip_round([(0, 1)])
+    dt = time.perf_counter() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return dict(value=1.0 / dt, unit="interactions/s", cores=threads, kind="oracle",
+                sample=f"2 of {n} nodes: H local MLP steps each (numpy float64 GEMMs, BLAS threads) + 1 pairwise "
+                       f"gossip of full rows, {dt:.2f} s; a round of the whole swarm is {n // 2} such units")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=4, help="workload configuration (2, 4 or 5)")
+    ap.add_argument("--config", type=int, default=4, help="workload configuration (2, 3, 4 or 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
     args = ap.parse_args()
@@ -128,7 +161,13 @@ def main():
     n, d, bits = cfg["n"], cfg["d"], cfg["bits"]
     eps = eps_for(cfg)
     s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0)
-    s.set_objective_diag(a, c, cfg["sigma"])
+    if cfg["objective"] == "mlp":
+        x0 = 0.02 * torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
+        s.close()
+        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0, x0=x0)
+        s.set_objective_mlp(cfg["n_in"], cfg["n_hid"], cfg["n_out"], a, c, cfg["data_sigma"], cfg["batch"])
+    else:
+        s.set_objective_diag(a, c, cfg["sigma"])
 
     def step():
         s.local_steps()
@@ -158,6 +197,11 @@ def main():
     achieved = gossip_bytes / gossip_s / 1e9 if gossip_s > 0 else 0.0
     local_bytes = 16.0 * d * n * times["local_calls"]
     local_gbs = local_bytes / (times["local_ms"] * 1e-3) / 1e9 if times["local_ms"] > 0 else 0.0
+    mlp = None
+    if cfg["objective"] == "mlp":
+        # 5 GEMMs of 2*batch*in*hid (= 2*batch*hid*out here) flops per node and local step
+        flops = 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"] * n * cfg["H"] * times["local_calls"]
+        mlp = flops / (times["local_ms"] * 1e-3) / 1e12
 
     out = {
         "metric": "node-interactions/sec + gossip-avg HBM GB/s (% of peak), n=64 d=25.6M",
@@ -167,14 +211,16 @@ def main():
         "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config {args.config}: n={n} d={d} graph={cfg['graph']} diag-quadratic "
-                               f"sigma={cfg['sigma']} H={cfg['H']} lr={cfg['lr']} bits={bits} "
+        "config": {"workload": f"config {args.config}: n={n} d={d} graph={cfg['graph']} {cfg['objective']} "
+                               f"sigma={cfg.get('sigma', cfg.get('data_sigma'))} H={cfg['H']} lr={cfg['lr']} bits={bits} "
                                f"stale_max={cfg['stale_max']} ({cfg.get('stale', 'fresh')}) eps={eps}",
                    "pairs_per_round": interactions / args.steps,
                    "decode_failures": after["decode_failures"] - before["decode_failures"],
                    "gossip_ms_per_round": times["gossip_ms"] / max(1, times["gossip_calls"]),
                    "local_steps_ms_per_round": times["local_ms"] / max(1, times["local_calls"]),
-                   "local_steps_GBps": local_gbs},
+                   "local_steps_GBps": None if mlp is not None else local_gbs,
+                   "local_steps_mfma_f32_TFLOPs": mlp,
+                   "local_steps_mfma_frac_of_157.3": None if mlp is None else mlp / 157.3},
         "roofline": {"kernel": "gossip_pairs_kernel (fused quantize/exchange/decode/average)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,

@@ -258,8 +258,9 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         SWARM_HIP(h, hipMemsetAsync(h->counters_dev, 0, sizeof(DeviceCounters), h->stream));
         SWARM_HIP(h, hipMemsetAsync(h->desc_dev, 0, h->desc_bytes, h->stream));
         if (x0_dev) {
-            SWARM_HIP(h, hipMemcpy2DAsync(h->X, cfg->d * sizeof(float), x0_dev, 0, cfg->d * sizeof(float), n,
-                                          hipMemcpyDeviceToDevice, h->stream));
+            for (uint32_t i = 0; i < n; ++i)     // every node starts from the same model
+                SWARM_HIP(h, hipMemcpyAsync(h->X + (uint64_t)i * cfg->d, x0_dev, cfg->d * sizeof(float),
+                                            hipMemcpyDeviceToDevice, h->stream));
         } else {
             SWARM_HIP(h, hipMemsetAsync(h->X, 0, model_bytes, h->stream));
         }

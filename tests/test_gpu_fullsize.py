@@ -1,59 +1,113 @@
-"""Parity at the benchmark's full size and launch configuration (n = 64, d = 25.6 M, 4-bit
-codes, reads one round stale): the oracle evaluates column windows (every step is
-per-coordinate and the random streams are counter-based), the GPU runs the whole rows."""
+"""Parity at the full sizes of the workload configurations, in the launch configuration the
+benchmark times.  For the per-coordinate objectives the oracle evaluates column windows (every
+step is per-coordinate and the random streams are counter-based) while the GPU runs whole rows;
+for the MLP the oracle evaluates a few whole nodes."""
 import numpy as np
 import pytest
 import torch
 
 import workloads as wl
-from oracle.objectives import DiagQuadratic
+from oracle.objectives import DiagQuadratic, MixtureMLP
 from oracle.swarm import SwarmOracle
-from helpers import TOL_ELEMENTWISE, assert_close
+from helpers import TOL_ELEMENTWISE, TOL_GEMM, assert_close
 
 pytestmark = pytest.mark.gpu
 
 
-def test_config4_full_size_sampled_windows(gpu):
-    cfg = wl.CONFIGS[4]
+def graph_of(cfg):
+    n = cfg["n"]
+    return {"regular4": lambda: wl.random_regular_graph(n, 4, 0), "regular8": lambda: wl.random_regular_graph(n, 8, 0),
+            "torus8x8": lambda: wl.torus_graph(8, 8), "complete": lambda: wl.complete_graph(n)}[cfg["graph"]]()
+
+
+@pytest.mark.parametrize("cfg_id,eps", [(2, 2.0 ** -4), (4, 0.5), (5, 0.25)])
+def test_diag_configs_full_size_sampled_windows(gpu, cfg_id, eps):
+    cfg = wl.CONFIGS[cfg_id]
     n, d, bits, H, lr, S, sigma = cfg["n"], cfg["d"], cfg["bits"], cfg["H"], cfg["lr"], cfg["stale_max"], cfg["sigma"]
-    eps, seed = 0.5, 0
-    edges = wl.random_regular_graph(n, 4, 0)
+    seed = cfg_id
+    edges = graph_of(cfg)
     gen = torch.Generator(device="cuda")
-    gen.manual_seed(1)
-    a = torch.empty((n, d), dtype=torch.float32, device="cuda").uniform_(0.5, 2.0, generator=gen)
+    gen.manual_seed(cfg_id)
+    a = torch.empty((n, d), dtype=torch.float32, device="cuda").uniform_(0.0, 1.0, generator=gen)
+    if cfg["a_law"] == "uniform":
+        a.mul_(cfg["a_hi"] - cfg["a_lo"]).add_(cfg["a_lo"])
+    else:
+        a.mul_(float(np.log(cfg["a_hi"] / cfg["a_lo"]))).add_(float(np.log(cfg["a_lo"]))).exp_()
     c = torch.empty((n, d), dtype=torch.float32, device="cuda").normal_(0.0, 1.0, generator=gen)
-    c += torch.randn(n, 1, generator=gen, device="cuda")
+    c += cfg["shift_sigma"] * torch.randn(n, 1, generator=gen, device="cuda")
     g = gpu.Swarm(n, d, edges, bits, eps, H, lr, S, seed)
     g.set_objective_diag(a, c, sigma)
     g.models_view(gpu.COMM).normal_(0.0, 0.7, generator=gen)        # any state: start away from zero
     torch.cuda.synchronize()
     width = 6 * 512 + 8                                             # several tiles and a ragged edge
-    starts = [0, 8 * 1234567, d - width]                            # first, an unaligned middle, last columns
+    starts = [0, 8 * (d // 24) + 8, d - width]                      # first, an unaligned middle, last columns
     oracles = []
     for k0 in starts:
         o = SwarmOracle(n, d, edges, bits, eps, H, lr, S, seed, k0=k0, k1=k0 + width)
         o.objective = DiagQuadratic(a[:, k0:k0 + width].cpu().numpy(), c[:, k0:k0 + width].cpu().numpy(), sigma, k0=k0)
         oracles.append(o)
-    for r in range(3):
+    for r in range(4):
         for o, k0 in zip(oracles, starts):                           # same state on both sides
             o.X[:] = g.read_models(gpu.COMM, k0=k0, length=width)
         pairs = g.sample_matching()
         assert np.array_equal(pairs, oracles[0].sample_matching().astype(np.uint32))
-        stale = np.full(n, 1, dtype=np.uint8)
+        if cfg.get("stale") == "fixed1":
+            stale = np.full(n, 1, dtype=np.uint8)
+        elif cfg.get("stale") == "uniform":
+            stale = g.sample_stale()
+            assert np.array_equal(stale, oracles[0].sample_stale().astype(np.uint8))
+        else:
+            stale = None
         g.local_steps()
         g.gossip_round(None, stale)                                  # the launch configuration bench.py times
         for o, k0 in zip(oracles, starts):
             o.local_steps()
             assert_close(g.read_models(gpu.LIVE, k0=k0, length=width), o.W, TOL_ELEMENTWISE, f"W window {k0} round {r}")
             o.gossip_round(pairs, stale)
-            for node in (0, 17, n - 1):
+            for node in (0, n // 3, n - 1):
                 got = g.read_codes(node, byte0=k0 * bits // 8, length=width * bits // 8)
                 assert np.array_equal(got, o.ring[r % (S + 1)][node]), f"codes window {k0} node {node} round {r}"
             assert_close(g.read_models(gpu.COMM, k0=k0, length=width), o.X, 2 * TOL_ELEMENTWISE,
                          f"X window {k0} round {r}")
     cnt = g.counters()
-    assert cnt["rounds"] == 3 and cnt["interactions"] == oracles[0].interactions
+    assert cnt["rounds"] == 4 and cnt["interactions"] == oracles[0].interactions
     assert cnt["bits_communicated"] == oracles[0].bits_communicated
-    # a property that holds at any size: the mean model moves only by the applied updates and the
-    # quantization error, so after the rounds it stays finite and the potential is positive
     assert np.isfinite(g.potential()) and g.potential() > 0
+
+
+def test_mlp_config_full_size_sampled_nodes(gpu):
+    """n = 256 nodes, 1024-4096-1024 perceptron (d = 8.4 M), batch 128, H = 2, 8-bit codes: the oracle
+    recomputes the local steps of two whole nodes and one matched pair of the gossip round."""
+    cfg = wl.CONFIGS[3]
+    n, d, bits, H, lr = cfg["n"], cfg["d"], cfg["bits"], cfg["H"], cfg["lr"]
+    eps, seed = 2.0 ** -10, 3
+    edges = graph_of(cfg)
+    means, cdf = wl.mixture_data(n, cfg["n_in"], cfg["n_out"], 0, cfg["alpha"])
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    g = gpu.Swarm(n, d, edges, bits, eps, H, lr, 0, seed)
+    g.set_objective_mlp(cfg["n_in"], cfg["n_hid"], cfg["n_out"], torch.from_numpy(means).cuda(),
+                        torch.from_numpy(cdf).cuda(), cfg["data_sigma"], cfg["batch"])
+    g.models_view(gpu.COMM).normal_(0.0, 0.02, generator=gen)
+    torch.cuda.synchronize()
+    pairs = g.sample_matching()
+    i, j = (int(v) for v in pairs[len(pairs) // 2])                 # one matched pair in the middle of the list
+    obj = MixtureMLP(cfg["n_in"], cfg["n_hid"], cfg["n_out"], means, cdf, cfg["data_sigma"], cfg["batch"])
+    X = {u: g.read_models(gpu.COMM, node0=u, count=1)[0] for u in (i, j)}
+    g.local_steps()
+    g.gossip_round(None)
+    W = {}
+    for u in (i, j):
+        w = X[u].astype(np.float64)
+        for q in range(H):
+            w = w - float(np.float32(lr)) * obj.gradient(u, w, seed, 0, q)
+        W[u] = w
+        assert_close(g.read_models(gpu.LIVE, node0=u, count=1)[0], w, TOL_GEMM, f"W of node {u}")
+    # the pair's gossip step written with the oracle's quantizer, from the same X and the oracle's own W
+    from oracle import quantizer as qz, rng
+    z = {u: qz.stochastic_round(X[u], eps, rng.sr_halves(seed, u, 0, 0, d)) for u in (i, j)}
+    for u, v in ((i, j), (j, i)):
+        seen = qz.decode(qz.code(z[v], bits), X[u], eps, bits)
+        want = (z[u] + seen) * (0.5 * eps) + (W[u] - X[u].astype(np.float64))
+        assert np.array_equal(g.read_codes(u), qz.pack(qz.code(z[u], bits), bits)), f"codes of node {u}"
+        assert_close(g.read_models(gpu.COMM, node0=u, count=1)[0], want, TOL_GEMM, f"X of node {u}")
