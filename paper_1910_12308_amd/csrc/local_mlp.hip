@@ -107,6 +107,25 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
+    // Epilogues that need a tile of another matrix (the weights to update, the ReLU mask source)
+    // request it before the K loop, so that its HBM latency hides behind the MFMAs instead of
+    // serialising compute phase and memory phase.
+    constexpr bool PREFETCH_AUX = EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE;
+    float pre[2][2][16];
+    if (PREFETCH_AUX) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const uint32_t n = n0 + wn + 32 * ni + r32;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t m = m0 + wm + 32 * mi + 8 * (v >> 2) + 4 * half + (v & 3);
+                    pre[mi][ni][v] = (n < g.N && m < g.M) ? aux[(uint64_t)m * g.ldaux + n] : 0.f;
+                }
+            }
+    }
+
     f4 ra[2], rb[2];
     auto fetch = [&](uint32_t k0) {
         if (A_KC) fetch_kc(A, g.lda, m0, g.M, k0, ra); else fetch_rc(A, g.lda, m0, g.M, k0, ra);
@@ -154,8 +173,8 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
                 float c = acc[mi][ni][v];
                 if (EPI == EPI_BIAS_RELU) c = fmaxf(c + bias, 0.f);
                 if (EPI == EPI_BIAS) c = c + bias;
-                if (EPI == EPI_RELU_MASK) c = aux[(uint64_t)m * g.ldaux + n] > 0.f ? c : 0.f;
-                if (EPI == EPI_SGD_UPDATE) c = fmaf(-g.lr, c, aux[(uint64_t)m * g.ldaux + n]);
+                if (EPI == EPI_RELU_MASK) c = pre[mi][ni][v] > 0.f ? c : 0.f;
+                if (EPI == EPI_SGD_UPDATE) c = fmaf(-g.lr, c, pre[mi][ni][v]);
                 C[(uint64_t)m * g.ldc + n] = c;
             }
         }
