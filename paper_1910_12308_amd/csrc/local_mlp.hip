@@ -47,8 +47,9 @@ __device__ __forceinline__ void fetch_kc(const float *P, uint32_t ld, uint32_t r
     const uint32_t t = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const uint32_t row = row0 + (t >> 2) + 64 * i;
-        r[i] = row < rows ? *(const f4 *)(P + (uint64_t)row * ld + k0 + 4 * (t & 3)) : f4{0.f, 0.f, 0.f, 0.f};
+        // rows past the matrix edge re-read its last row: they only feed outputs that are never stored
+        const uint32_t row = min(row0 + (t >> 2) + 64 * i, rows - 1);
+        r[i] = *(const f4 *)(P + (uint64_t)row * ld + k0 + 4 * (t & 3));
     }
 }
 __device__ __forceinline__ void stash_kc(float *lds, const f4 r[2]) {
@@ -62,8 +63,8 @@ __device__ __forceinline__ void fetch_rc(const float *P, uint32_t ld, uint32_t r
     const uint32_t t = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const uint32_t k = k0 + (t >> 5) + 8 * i, row = row0 + 4 * (t & 31);
-        r[i] = row < rows ? *(const f4 *)(P + (uint64_t)k * ld + row) : f4{0.f, 0.f, 0.f, 0.f};
+        const uint32_t k = k0 + (t >> 5) + 8 * i, row = min(row0 + 4 * (t & 31), rows - 4);
+        r[i] = *(const f4 *)(P + (uint64_t)k * ld + row);
     }
 }
 __device__ __forceinline__ void stash_rc(float *lds, const f4 r[2]) {
@@ -111,6 +112,9 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
     // request it before the K loop, so that its HBM latency hides behind the MFMAs instead of
     // serialising compute phase and memory phase.
     constexpr bool PREFETCH_AUX = EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE;
+    // Tiles that lie wholly inside the matrix (all of them when M and N are multiples of 128)
+    // take straight-line loads and stores; the guarded path serves ragged edges.
+    const bool full_tile = m0 + TM <= g.M && n0 + TN <= g.N;
     float pre[2][2][16];
     if (PREFETCH_AUX) {
 #pragma unroll
@@ -118,10 +122,17 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
 #pragma unroll
             for (int ni = 0; ni < 2; ++ni) {
                 const uint32_t n = n0 + wn + 32 * ni + r32;
+                const uint32_t mb = m0 + wm + 32 * mi + 4 * half;
+                if (full_tile) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const uint32_t m = m0 + wm + 32 * mi + 8 * (v >> 2) + 4 * half + (v & 3);
-                    pre[mi][ni][v] = (n < g.N && m < g.M) ? aux[(uint64_t)m * g.ldaux + n] : 0.f;
+                    for (int v = 0; v < 16; ++v)
+                        pre[mi][ni][v] = aux[(uint64_t)(mb + 8 * (v >> 2) + (v & 3)) * g.ldaux + n];
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const uint32_t m = mb + 8 * (v >> 2) + (v & 3);
+                        pre[mi][ni][v] = (n < g.N && m < g.M) ? aux[(uint64_t)m * g.ldaux + n] : 0.f;
+                    }
                 }
             }
     }
@@ -163,19 +174,28 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni) {
             const uint32_t n = n0 + wn + 32 * ni + r32;
-            if (n >= g.N) continue;
+            const uint32_t mb = m0 + wm + 32 * mi + 4 * half;
             float bias = 0.f;
-            if (EPI == EPI_BIAS_RELU || EPI == EPI_BIAS) bias = aux[n];
+            if ((EPI == EPI_BIAS_RELU || EPI == EPI_BIAS) && n < g.N) bias = aux[n];
+            float out[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const uint32_t m = m0 + wm + 32 * mi + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (m >= g.M) continue;
                 float c = acc[mi][ni][v];
                 if (EPI == EPI_BIAS_RELU) c = fmaxf(c + bias, 0.f);
                 if (EPI == EPI_BIAS) c = c + bias;
                 if (EPI == EPI_RELU_MASK) c = pre[mi][ni][v] > 0.f ? c : 0.f;
                 if (EPI == EPI_SGD_UPDATE) c = fmaf(-g.lr, c, pre[mi][ni][v]);
-                C[(uint64_t)m * g.ldc + n] = c;
+                out[v] = c;
+            }
+            if (full_tile) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) C[(uint64_t)(mb + 8 * (v >> 2) + (v & 3)) * g.ldc + n] = out[v];
+            } else if (n < g.N) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t m = mb + 8 * (v >> 2) + (v & 3);
+                    if (m < g.M) C[(uint64_t)m * g.ldc + n] = out[v];
+                }
             }
         }
 }
