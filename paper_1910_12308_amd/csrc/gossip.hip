@@ -107,30 +107,30 @@ __device__ __forceinline__ void report(DeviceCounters *c, int fails, bool clampe
     }
 }
 
-template <int BITS, int DELTA, int STALE>
-__global__ __launch_bounds__(WAVES * 64) void gossip_pairs_kernel(const GossipArgs a) {
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+// One wave's tile of one pair.  FULL: the tile lies wholly inside the row, so no lane needs a
+// guard and every load is issued before the first use; the ragged last tile of a row takes the
+// guarded variant.
+template <int BITS, int DELTA, int STALE, bool FULL>
+__device__ __forceinline__ void gossip_pair_tile(const GossipArgs &a, const PairDesc pd, uint64_t tile, uint32_t lane) {
     const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
-    const bool inA = kA < a.d, inB = kB < a.d;
-    if (tile * TILE >= a.d) return;
-    const uint32_t ni = a.pairs[2 * blockIdx.y], nj = a.pairs[2 * blockIdx.y + 1];
+    const bool inA = FULL || kA < a.d, inB = FULL || kB < a.d;
+    // Lanes past the end of the row load the row's last float4 instead (never stored).
+    const uint64_t lA = inA ? kA : a.d - 4, lB = inB ? kB : a.d - 4;
+    const uint32_t ni = pd.ni, nj = pd.nj;
     float *xi = a.X + (uint64_t)ni * a.d, *xj = a.X + (uint64_t)nj * a.d;
     const float *wi = a.W + (uint64_t)ni * a.d, *wj = a.W + (uint64_t)nj * a.d;
 
-    const bool di = DELTA == 1 || (DELTA == 2 && a.pending[ni]);
-    const bool dj = DELTA == 1 || (DELTA == 2 && a.pending[nj]);
-    const uint32_t si = STALE == 0 ? 0u : (uint32_t)a.stale[ni];   // age of the code i reads from j
-    const uint32_t sj = STALE == 0 ? 0u : (uint32_t)a.stale[nj];
+    const bool di = DELTA == 1 || (DELTA == 2 && (pd.flags & (1u << 16)));
+    const bool dj = DELTA == 1 || (DELTA == 2 && (pd.flags & (1u << 17)));
+    const uint32_t si = STALE == 0 ? 0u : (pd.flags & 0xFFu);          // age of the code i reads from j
+    const uint32_t sj = STALE == 0 ? 0u : ((pd.flags >> 8) & 0xFFu);
     const bool stale_i = STALE == 1 || (STALE == 2 && si != 0), stale_j = STALE == 1 || (STALE == 2 && sj != 0);
 
+    const f4 xiA = ldg_nt(xi + lA), xjA = ldg_nt(xj + lA), xiB = ldg_nt(xi + lB), xjB = ldg_nt(xj + lB);
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    f4 xiA = zero, xiB = zero, xjA = zero, xjB = zero, wiA, wiB, wjA, wjB;
-    if (inA) { xiA = ldg_nt(xi + kA); xjA = ldg_nt(xj + kA); }
-    if (inB) { xiB = ldg_nt(xi + kB); xjB = ldg_nt(xj + kB); }
-    wiA = xiA; wiB = xiB; wjA = xjA; wjB = xjB;
-    if (di) { if (inA) wiA = ldg_nt(wi + kA); if (inB) wiB = ldg_nt(wi + kB); }
-    if (dj) { if (inA) wjA = ldg_nt(wj + kA); if (inB) wjB = ldg_nt(wj + kB); }
+    f4 wiA = zero, wiB = zero, wjA = zero, wjB = zero;
+    if (di) { wiA = ldg_nt(wi + lA); wiB = ldg_nt(wi + lB); }
+    if (dj) { wjA = ldg_nt(wj + lA); wjB = ldg_nt(wj + lB); }
 
     const uint64_t slot_bytes = (uint64_t)a.n * a.row_bytes;
     uint8_t *pub_i = a.ring + a.slot_now * slot_bytes + ni * a.row_bytes;
@@ -138,35 +138,35 @@ __global__ __launch_bounds__(WAVES * 64) void gossip_pairs_kernel(const GossipAr
     uint64_t seenjA = 0, seenjB = 0, seeniA = 0, seeniB = 0;       // partner codes as read
     if (stale_i) {   // i reads what j published si rounds ago
         const uint8_t *src = a.ring + ((a.slot_now + a.ring_depth - si) % a.ring_depth) * slot_bytes + nj * a.row_bytes;
-        if (inA) seenjA = load_code<BITS>(src, kA / 4);
-        if (inB) seenjB = load_code<BITS>(src, kB / 4);
+        seenjA = load_code<BITS>(src, lA / 4);
+        seenjB = load_code<BITS>(src, lB / 4);
     }
     if (stale_j) {
         const uint8_t *src = a.ring + ((a.slot_now + a.ring_depth - sj) % a.ring_depth) * slot_bytes + ni * a.row_bytes;
-        if (inA) seeniA = load_code<BITS>(src, kA / 4);
-        if (inB) seeniB = load_code<BITS>(src, kB / 4);
+        seeniA = load_code<BITS>(src, lA / 4);
+        seeniB = load_code<BITS>(src, lB / 4);
     }
 
     const LaneRandom ri = row_random(a.seed, ni, a.event, tile, lane);
     const LaneRandom rj = row_random(a.seed, nj, a.event, tile, lane);
 
-    bool clamped = false;
-    int fails = 0;
+    bool clampedA = false, clampedB = false;     // counted per half: lanes past the row end hold a duplicate
+    int failsA = 0, failsB = 0;
     int ziA[4], ziB[4], zjA[4], zjB[4];
-    const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, a.inv_eps, ziA, clamped);
-    const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, a.inv_eps, ziB, clamped);
-    const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, a.inv_eps, zjA, clamped);
-    const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, a.inv_eps, zjB, clamped);
+    const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, a.inv_eps, ziA, clampedA);
+    const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, a.inv_eps, ziB, clampedB);
+    const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, a.inv_eps, zjA, clampedA);
+    const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, a.inv_eps, zjB, clampedB);
     const float half_eps = 0.5f * a.eps;
 
-    const f4 oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, xiA, wiA - xiA, a.inv_eps, half_eps,
-                                  stale_i ? nullptr : zjA, fails, clamped);
-    const f4 oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, xiB, wiB - xiB, a.inv_eps, half_eps,
-                                  stale_i ? nullptr : zjB, fails, clamped);
-    const f4 ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, xjA, wjA - xjA, a.inv_eps, half_eps,
-                                  stale_j ? nullptr : ziA, fails, clamped);
-    const f4 ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, xjB, wjB - xjB, a.inv_eps, half_eps,
-                                  stale_j ? nullptr : ziB, fails, clamped);
+    const f4 oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, xiA, di ? wiA - xiA : zero, a.inv_eps, half_eps,
+                                  stale_i ? nullptr : zjA, failsA, clampedA);
+    const f4 oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, xiB, di ? wiB - xiB : zero, a.inv_eps, half_eps,
+                                  stale_i ? nullptr : zjB, failsB, clampedB);
+    const f4 ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, xjA, dj ? wjA - xjA : zero, a.inv_eps, half_eps,
+                                  stale_j ? nullptr : ziA, failsA, clampedA);
+    const f4 ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, xjB, dj ? wjB - xjB : zero, a.inv_eps, half_eps,
+                                  stale_j ? nullptr : ziB, failsB, clampedB);
     if (inA) {
         stg_nt(xi + kA, oiA); stg_nt(xj + kA, ojA);
         store_code<BITS>(pub_i, kA / 4, ciA); store_code<BITS>(pub_j, kA / 4, cjA);
@@ -175,8 +175,17 @@ __global__ __launch_bounds__(WAVES * 64) void gossip_pairs_kernel(const GossipAr
         stg_nt(xi + kB, oiB); stg_nt(xj + kB, ojB);
         store_code<BITS>(pub_i, kB / 4, ciB); store_code<BITS>(pub_j, kB / 4, cjB);
     }
-    if (!inA) { fails = 0; clamped = false; }    // lanes past the row end hold zeros only
-    report(a.counters, fails, clamped);
+    report(a.counters, (inA ? failsA : 0) + (inB ? failsB : 0), (inA && clampedA) || (inB && clampedB));
+}
+
+template <int BITS, int DELTA, int STALE>
+__global__ __launch_bounds__(WAVES * 64) void gossip_pairs_kernel(const GossipArgs a) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    if (tile * TILE >= a.d) return;
+    const PairDesc pd = a.pairs[blockIdx.y];                       // uniform: one scalar load
+    if (tile * TILE + TILE <= a.d) gossip_pair_tile<BITS, DELTA, STALE, true>(a, pd, tile, lane);
+    else gossip_pair_tile<BITS, DELTA, STALE, false>(a, pd, tile, lane);
 }
 
 // Q = identity (Corollary 4.2): plain pairwise averaging plus the pending update.
@@ -184,12 +193,13 @@ template <int DELTA>
 __global__ __launch_bounds__(WAVES * 64) void average_pairs_kernel(const GossipArgs a) {
     const uint64_t k = ((uint64_t)blockIdx.x * (WAVES * 64) + threadIdx.x) * 4;
     if (k >= a.d) return;
-    const uint32_t ni = a.pairs[2 * blockIdx.y], nj = a.pairs[2 * blockIdx.y + 1];
+    const PairDesc pd = a.pairs[blockIdx.y];
+    const uint32_t ni = pd.ni, nj = pd.nj;
     float *xi = a.X + (uint64_t)ni * a.d + k, *xj = a.X + (uint64_t)nj * a.d + k;
     const f4 vi = ldg_nt(xi), vj = ldg_nt(xj);
     f4 di = {0.f, 0.f, 0.f, 0.f}, dj = di;
-    if (DELTA == 1 || (DELTA == 2 && a.pending[ni])) di = ldg_nt(a.W + (uint64_t)ni * a.d + k) - vi;
-    if (DELTA == 1 || (DELTA == 2 && a.pending[nj])) dj = ldg_nt(a.W + (uint64_t)nj * a.d + k) - vj;
+    if (DELTA == 1 || (DELTA == 2 && (pd.flags & (1u << 16)))) di = ldg_nt(a.W + (uint64_t)ni * a.d + k) - vi;
+    if (DELTA == 1 || (DELTA == 2 && (pd.flags & (1u << 17)))) dj = ldg_nt(a.W + (uint64_t)nj * a.d + k) - vj;
     const f4 avg = 0.5f * (vi + vj);
     stg_nt(xi, avg + di);
     stg_nt(xj, avg + dj);
@@ -203,10 +213,11 @@ __global__ __launch_bounds__(WAVES * 64) void gossip_singles_kernel(const Gossip
     const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
     const bool inA = kA < a.d, inB = kB < a.d;
     if (tile * TILE >= a.d) return;
-    const uint32_t u = a.singles[blockIdx.y];
+    const uint32_t entry = a.singles[blockIdx.y];
+    const uint32_t u = entry & ~SINGLE_PENDING;
     float *xu = a.X + (uint64_t)u * a.d;
     const float *wu = a.W + (uint64_t)u * a.d;
-    const bool pend = a.pending[u];
+    const bool pend = entry & SINGLE_PENDING;
     if constexpr (BITS > 0) {
         const f4 zero = {0.f, 0.f, 0.f, 0.f};
         const f4 xA = inA ? ldg_nt(xu + kA) : zero, xB = inB ? ldg_nt(xu + kB) : zero;

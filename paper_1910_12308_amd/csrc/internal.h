@@ -12,15 +12,21 @@ struct DeviceCounters {
     unsigned int pad;
 };
 
+// One matched pair of a round.  flags: bits 0-7 = age (in rounds) of the code i reads from j,
+// bits 8-15 = age of the code j reads from i, bit 16 / 17 = W_i / W_j carries unapplied steps.
+// 16 bytes so that a workgroup fetches its pair with one scalar load.
+struct PairDesc {
+    uint32_t ni, nj, flags, pad;
+};
+constexpr uint32_t SINGLE_PENDING = 0x80000000u;   // unmatched-node entry: node id | pending flag
+
 struct GossipArgs {
     float *X;                 // n x d current models (updated in place)
     const float *W;           // n x d live copies
     float *Xhat;              // n x d snapshots (Algorithm 1 only), may be null
     uint8_t *ring;            // (S+1) x n x row_bytes packed codes
-    const uint32_t *pairs;    // device: 2 per pair
-    const uint32_t *singles;  // device: unmatched nodes
-    const uint8_t *pending;   // device: n flags, W_i carries unapplied steps
-    const uint8_t *stale;     // device: n, rounds of staleness of node's read
+    const PairDesc *pairs;    // device: one per matched pair
+    const uint32_t *singles;  // device: unmatched nodes (node id | SINGLE_PENDING)
     DeviceCounters *counters;
     uint64_t d;
     uint64_t row_bytes;       // d * bits / 8

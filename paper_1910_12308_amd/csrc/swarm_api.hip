@@ -40,7 +40,7 @@ struct swarm_ctx {
     uint8_t *ring = nullptr;
     uint32_t *edges_dev = nullptr, *prio_dev = nullptr, *counts_dev = nullptr, *nodes_dev = nullptr;
     uint32_t *linf_dev = nullptr;
-    uint8_t *desc_dev = nullptr;                 // pairs | singles | stale | pending
+    uint8_t *desc_dev = nullptr;                 // PairDesc[n/2] | singles[n]
     DeviceCounters *counters_dev = nullptr;
     double *partials_dev = nullptr, *gamma_dev = nullptr;
 
@@ -54,7 +54,7 @@ struct swarm_ctx {
     uint64_t match_round = ~0ull;
     double *scalar_host = nullptr;
 
-    size_t off_pairs = 0, off_singles = 0, off_stale = 0, off_pending = 0, desc_bytes = 0;
+    size_t off_pairs = 0, off_singles = 0, desc_bytes = 0;
 
     std::vector<uint8_t> pending;                // host mirror: W_i carries unapplied steps
     ObjectiveKind kind = OBJ_NONE;
@@ -67,10 +67,8 @@ struct swarm_ctx {
     uint32_t timed_gossip = 0, timed_local = 0;    // recorded calls since the last reset
     std::string err;
 
-    uint32_t *pairs_dev() const { return (uint32_t *)(desc_dev + off_pairs); }
+    PairDesc *pairs_dev() const { return (PairDesc *)(desc_dev + off_pairs); }
     uint32_t *singles_dev() const { return (uint32_t *)(desc_dev + off_singles); }
-    uint8_t *stale_dev() const { return desc_dev + off_stale; }
-    uint8_t *pending_dev() const { return desc_dev + off_pending; }
 };
 
 namespace {
@@ -98,7 +96,6 @@ GossipArgs gossip_args(swarm_t h, uint32_t event, uint32_t slot) {
     GossipArgs a{};
     a.X = h->X; a.W = h->W; a.Xhat = h->Xhat; a.ring = h->ring;
     a.pairs = h->pairs_dev(); a.singles = h->singles_dev();
-    a.pending = h->pending_dev(); a.stale = h->stale_dev();
     a.counters = h->counters_dev;
     a.d = h->cfg.d; a.row_bytes = h->row_bytes; a.seed = h->cfg.seed;
     a.n = h->cfg.n; a.event = event; a.slot_now = slot; a.ring_depth = h->cfg.stale_max + 1;
@@ -217,10 +214,8 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
 
     const uint32_t n = cfg->n;
     h->off_pairs = 0;
-    h->off_singles = h->off_pairs + sizeof(uint32_t) * 2 * (n / 2);
-    h->off_stale = h->off_singles + sizeof(uint32_t) * n;
-    h->off_pending = h->off_stale + n;
-    h->desc_bytes = h->off_pending + n;
+    h->off_singles = h->off_pairs + sizeof(PairDesc) * (n / 2);
+    h->desc_bytes = h->off_singles + sizeof(uint32_t) * n;
 
     swarm_status rc = SWARM_OK;
     auto body = [&]() -> swarm_status {
@@ -473,24 +468,24 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
     const int delta_mode = with_delta == 0 ? 0 : (with_delta == 2 * npairs ? 1 : 2);
     const int stale_mode = with_stale == 0 ? 0 : (with_stale == 2 * npairs ? 1 : 2);
 
+    // Per-round metadata: one descriptor per pair (nodes, staleness, pending flags) and the
+    // unmatched nodes, staged in pinned memory and copied with one transfer.
     uint8_t *slot = nullptr;
     unsigned slot_index = 0;
     const swarm_status rc = acquire_desc(h, &slot, &slot_index);
     if (rc != SWARM_OK) return rc;
-    std::memcpy(slot + h->off_stale, stale.data(), n);
-    std::memcpy(slot + h->off_pending, h->pending.data(), n);
-    if (!device_pairs) {
-        if (npairs) std::memcpy(slot + h->off_pairs, pairs.data(), sizeof(uint32_t) * 2 * npairs);
-        if (nsingles) std::memcpy(slot + h->off_singles, singles.data(), sizeof(uint32_t) * nsingles);
-        SWARM_HIP(h, hipMemcpyAsync(h->desc_dev, slot, h->desc_bytes, hipMemcpyHostToDevice, h->stream));
-    } else {
-        SWARM_HIP(h, hipMemcpyAsync(h->desc_dev + h->off_stale, slot + h->off_stale, 2 * (size_t)n,
-                                    hipMemcpyHostToDevice, h->stream));
+    PairDesc *pd = (PairDesc *)(slot + h->off_pairs);
+    for (uint32_t p = 0; p < npairs; ++p) {
+        const uint32_t u = pairs[2 * p], v = pairs[2 * p + 1];
+        pd[p] = PairDesc{u, v, (uint32_t)stale[u] | ((uint32_t)stale[v] << 8) |
+                               (h->pending[u] ? 1u << 16 : 0u) | (h->pending[v] ? 1u << 17 : 0u), 0u};
     }
+    uint32_t *sg = (uint32_t *)(slot + h->off_singles);
+    for (uint32_t k = 0; k < nsingles; ++k) sg[k] = singles[k] | (h->pending[singles[k]] ? SINGLE_PENDING : 0u);
+    SWARM_HIP(h, hipMemcpyAsync(h->desc_dev, slot, h->desc_bytes, hipMemcpyHostToDevice, h->stream));
     SWARM_HIP(h, hipEventRecord(h->desc_free[slot_index], h->stream));
 
-    GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
-    if (device_pairs) { a.pairs = h->mpairs_dev; a.singles = h->msingles_dev; }
+    const GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
     SWARM_HIP(h, launch_gossip_pairs(a, c.bits, delta_mode, stale_mode, npairs, h->stream));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
@@ -649,10 +644,10 @@ swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npa
         return fail(h, SWARM_EINVAL, "pair list out of range");
     for (uint32_t k = 0; k < 2 * npairs; ++k)
         if (pairs_host[k] >= h->cfg.n) return fail(h, SWARM_EINVAL, "pair endpoint out of range");
-    SWARM_HIP(h, hipMemcpyAsync(h->pairs_dev(), pairs_host, sizeof(uint32_t) * 2 * npairs, hipMemcpyHostToDevice,
+    SWARM_HIP(h, hipMemcpyAsync(h->nodes_dev, pairs_host, sizeof(uint32_t) * 2 * npairs, hipMemcpyHostToDevice,
                                 h->stream));
     SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * npairs, h->stream));
-    SWARM_HIP(h, launch_pair_linf(h->X, h->cfg.d, h->pairs_dev(), npairs, h->linf_dev, h->stream));
+    SWARM_HIP(h, launch_pair_linf(h->X, h->cfg.d, h->nodes_dev, npairs, h->linf_dev, h->stream));
     SWARM_HIP(h, hipMemcpyAsync(linf_host, h->linf_dev, sizeof(uint32_t) * npairs, hipMemcpyDeviceToHost, h->stream));
     SWARM_HIP(h, hipStreamSynchronize(h->stream));
     return SWARM_OK;
