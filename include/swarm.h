@@ -42,6 +42,13 @@ typedef enum {
     SWARM_ERANGE = 5    /* reported by swarm_counters: |x/eps| reached the clamp 2^29     */
 } swarm_status;
 
+/* When the local steps reach the exchanged model.  DEFERRED (the paper: the node computes its
+ * local gradients, "which it does not yet apply", averages the quantized models, then adds the
+ * summed update to the average): X is exchanged, W = X - eta h~ lives in a second matrix.
+ * INPLACE: the local steps update the exchanged model directly and the averaging acts on the
+ * updated models; one matrix, no pending update (W is an alias of X). */
+enum { SWARM_APPLY_DEFERRED = 0, SWARM_APPLY_INPLACE = 1 };
+
 enum { SWARM_MODELS_COMM = 0,  /* X: current / communicated models                        */
        SWARM_MODELS_LIVE = 1,  /* W: live copies carrying the pending local steps         */
        SWARM_MODELS_SNAP = 2   /* Xhat: models at the last initiation (Algorithm 1)       */ };
@@ -61,12 +68,14 @@ typedef struct {
     uint32_t stale_max;     /* S: a read may use the partner's code from up to S rounds
                                ago; the ring keeps S+1 slots. Must be 0 when bits = 0.     */
     uint64_t seed;          /* key of every random stream                                  */
+    uint32_t apply_mode;    /* SWARM_APPLY_DEFERRED (default) or SWARM_APPLY_INPLACE           */
 } swarm_config;
 
 /* Create a handle.  x0_dev: d floats (device) copied into every node's model, or NULL
  * for zeros (all nodes start from the same model: Algorithm 1, initial models; the
  * registers initially hold zero vectors).  hip_stream: a hipStream_t (NULL = default
- * stream).  Allocates (2 n d) floats + (S+1) n d b/8 bytes of device memory.
+ * stream).  Allocates (2 n d) floats (n d in INPLACE mode) + (S+1) n d b/8 bytes of device
+ * memory.
  * Synchronises the stream. */
 swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_stream,
                         swarm_t *out);
@@ -121,7 +130,7 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
 /* One step of Algorithm 1 (sequential model), initiator i, responder j adjacent to i:
  * i runs its H local steps from its snapshot Xhat_i, then
  *     X_i <- (Q(X_i) + Q(X_j)) / 2 + (W_i - Xhat_i),   X_j <- (Q(X_i) + Q(X_j)) / 2,
- * Xhat_i <- X_i.  Requires stale_max = 0. */
+ * Xhat_i <- X_i.  Requires stale_max = 0 and DEFERRED apply mode. */
 swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j);
 
 /* Algorithm 1's sampling: initiator uniform over nodes, responder uniform over its

@@ -16,7 +16,7 @@ from . import rng
 
 class SwarmOracle:
     def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None,
-                 k0=0, k1=None, state_dtype=np.float32):
+                 k0=0, k1=None, state_dtype=np.float32, apply_mode="deferred"):
         self.n, self.d = int(n), int(d)
         self.k0 = int(k0)
         self.k1 = self.d if k1 is None else int(k1)
@@ -26,6 +26,10 @@ class SwarmOracle:
         self.H, self.lr = int(H), float(np.float32(lr))
         self.S, self.seed = int(stale_max), int(seed)
         assert self.bits in (0,) + qz.SUPPORTED_BITS and (self.bits > 0 or self.S == 0)
+        # "deferred": the paper's rule (steps computed, averaged model adopted, steps added on top);
+        # "inplace": the steps update the exchanged model itself before the averaging.
+        assert apply_mode in ("deferred", "inplace")
+        self.apply_mode = apply_mode
         self.dtype = state_dtype
         dw = self.k1 - self.k0
         self.X = np.zeros((self.n, dw), dtype=state_dtype)
@@ -53,8 +57,13 @@ class SwarmOracle:
             w = base.astype(np.float64)
             for q in range(self.H):
                 w = w - self.lr * self.objective.gradient(i, w, self.seed, event, q)
-            self.W[i] = w
-            self.pending[i] = True
+            if self.apply_mode == "inplace":
+                assert not sequential
+                self.X[i] = w
+                self.W[i] = self.X[i]
+            else:
+                self.W[i] = w
+                self.pending[i] = True
 
     def _delta(self, i, base):
         """Pending update -eta h~_i = W_i - base (zero if no local steps are pending)."""

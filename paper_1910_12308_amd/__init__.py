@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libswarm.so")
 
 OK, EINVAL, ENOMEM, EDEVICE, ESTATE, ERANGE = range(6)
 COMM, LIVE, SNAP = 0, 1, 2
+DEFERRED, INPLACE = 0, 1
 _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_ESTATE", 5: "SWARM_ERANGE"}
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
@@ -36,7 +37,7 @@ class _Config(ctypes.Structure):
     _fields_ = [("n", ctypes.c_uint32), ("d", ctypes.c_uint64), ("n_edges", ctypes.c_uint32),
                 ("edges", ctypes.POINTER(ctypes.c_uint32)), ("bits", ctypes.c_uint32), ("eps", ctypes.c_float),
                 ("H", ctypes.c_uint32), ("lr", ctypes.c_float), ("stale_max", ctypes.c_uint32),
-                ("seed", ctypes.c_uint64)]
+                ("seed", ctypes.c_uint64), ("apply_mode", ctypes.c_uint32)]
 
 
 def load_library():
@@ -120,13 +121,15 @@ class _DeviceView:
 class Swarm:
     """One simulated swarm: n node models of dimension d on one GPU."""
 
-    def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None, stream=None):
+    def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None, stream=None,
+                 apply_mode=DEFERRED):
         self._h = ctypes.c_void_p()
         self._lib = lib()
         edges = _host_u32(edges)
         self.n, self.d, self.bits, self.stale_max = int(n), int(d), int(bits), int(stale_max)
         cfg = _Config(self.n, self.d, edges.size // 2, edges.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
-                      self.bits, float(eps), int(H), float(lr), self.stale_max, int(seed) & 0xFFFFFFFFFFFFFFFF)
+                      self.bits, float(eps), int(H), float(lr), self.stale_max, int(seed) & 0xFFFFFFFFFFFFFFFF,
+                      int(apply_mode))
         self._keep = []          # borrowed objective tensors must outlive the handle
         rc = self._lib.swarm_init(ctypes.byref(cfg), _dev_ptr(x0, torch.float32), _stream_ptr(stream),
                                   ctypes.byref(self._h))

@@ -124,7 +124,9 @@ __device__ __forceinline__ void gossip_pair_tile(const GossipArgs &a, const Pair
     const bool dj = DELTA == 1 || (DELTA == 2 && (pd.flags & (1u << 17)));
     const uint32_t si = STALE == 0 ? 0u : (pd.flags & 0xFFu);          // age of the code i reads from j
     const uint32_t sj = STALE == 0 ? 0u : ((pd.flags >> 8) & 0xFFu);
-    const bool stale_i = STALE == 1 || (STALE == 2 && si != 0), stale_j = STALE == 1 || (STALE == 2 && sj != 0);
+    // STALE: 0 = both reads fresh, 1 = both stale, 2 = per-pair flags, 3 = only i's read is stale
+    const bool stale_i = STALE == 1 || STALE == 3 || (STALE == 2 && si != 0);
+    const bool stale_j = STALE == 1 || (STALE == 2 && sj != 0);
 
     const f4 xiA = ldg_nt(xi + lA), xjA = ldg_nt(xj + lA), xiB = ldg_nt(xi + lB), xjB = ldg_nt(xj + lB);
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -331,9 +333,9 @@ static void launch_pairs_bits(const GossipArgs &a, int delta_mode, int stale_mod
         gossip_pairs_kernel<BITS, D, S><<<grid, WAVES * 64, 0, st>>>(a);                      \
         return;                                                                               \
     }
-    SWARM_CASE(0, 0) SWARM_CASE(0, 1) SWARM_CASE(0, 2)
-    SWARM_CASE(1, 0) SWARM_CASE(1, 1) SWARM_CASE(1, 2)
-    SWARM_CASE(2, 0) SWARM_CASE(2, 1) SWARM_CASE(2, 2)
+    SWARM_CASE(0, 0) SWARM_CASE(0, 1) SWARM_CASE(0, 2) SWARM_CASE(0, 3)
+    SWARM_CASE(1, 0) SWARM_CASE(1, 1) SWARM_CASE(1, 2) SWARM_CASE(1, 3)
+    SWARM_CASE(2, 0) SWARM_CASE(2, 1) SWARM_CASE(2, 2) SWARM_CASE(2, 3)
 #undef SWARM_CASE
 }
 

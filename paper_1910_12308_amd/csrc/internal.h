@@ -38,7 +38,9 @@ struct GossipArgs {
     float eps, inv_eps;
 };
 
-// delta_mode / stale_mode: 0 = none of the nodes, 1 = all of them, 2 = per-node flags.
+// delta_mode: 0 = no node of these pairs has pending steps, 1 = all have, 2 = per-pair flags.
+// stale_mode: 0 = all reads fresh, 1 = all stale, 2 = per-pair flags, 3 = in every pair only the
+// first node's read is stale.
 hipError_t launch_gossip_pairs(const GossipArgs &a, uint32_t bits, int delta_mode, int stale_mode,
                                uint32_t npairs, hipStream_t st);
 hipError_t launch_gossip_singles(const GossipArgs &a, uint32_t bits, uint32_t nsingles, hipStream_t st);

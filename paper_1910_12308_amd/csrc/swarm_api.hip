@@ -182,6 +182,7 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     if (cfg->bits == 0 && cfg->stale_max != 0) return fail(nullptr, SWARM_EINVAL, "stale reads need quantized codes");
     if (cfg->stale_max > 254) return fail(nullptr, SWARM_EINVAL, "stale_max exceeds 254");
     if (cfg->H > 255) return fail(nullptr, SWARM_EINVAL, "H exceeds 255");
+    if (cfg->apply_mode > SWARM_APPLY_INPLACE) return fail(nullptr, SWARM_EINVAL, "unknown apply mode");
     if (cfg->n_edges == 0 || !cfg->edges) return fail(nullptr, SWARM_EINVAL, "graph has no edges");
     if (cfg->n_edges > MATCHING_MAX_EDGES) return fail(nullptr, SWARM_EINVAL, "too many edges");
 
@@ -222,7 +223,8 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         SWARM_HIP(h, hipGetDevice(&h->device));
         const size_t model_bytes = (size_t)n * cfg->d * sizeof(float);
         SWARM_HIP(h, hipMalloc((void **)&h->X, model_bytes));
-        SWARM_HIP(h, hipMalloc((void **)&h->W, model_bytes));
+        if (cfg->apply_mode == SWARM_APPLY_INPLACE) h->W = h->X;     // one matrix: local steps update X itself
+        else SWARM_HIP(h, hipMalloc((void **)&h->W, model_bytes));
         if (cfg->bits) {
             const size_t ring_bytes = (size_t)(cfg->stale_max + 1) * n * h->row_bytes;
             SWARM_HIP(h, hipMalloc((void **)&h->ring, ring_bytes));
@@ -259,7 +261,8 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         } else {
             SWARM_HIP(h, hipMemsetAsync(h->X, 0, model_bytes, h->stream));
         }
-        SWARM_HIP(h, hipMemcpyAsync(h->W, h->X, model_bytes, hipMemcpyDeviceToDevice, h->stream));
+        if (h->W != h->X)
+            SWARM_HIP(h, hipMemcpyAsync(h->W, h->X, model_bytes, hipMemcpyDeviceToDevice, h->stream));
         SWARM_HIP(h, hipStreamSynchronize(h->stream));
         return SWARM_OK;
     };
@@ -278,6 +281,7 @@ swarm_status swarm_destroy(swarm_t h) {
     (void)hipStreamSynchronize(h->stream);
     free_lsq(h->lsq);
     free_mlp(h->mlp);
+    if (h->W == h->X) h->W = nullptr;
     void *dev[] = {h->X, h->W, h->Xhat, h->ring, h->edges_dev, h->prio_dev, h->counts_dev, h->nodes_dev,
                    h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev, h->mpairs_dev,
                    h->msingles_dev};
@@ -357,6 +361,7 @@ swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count)
     SWARM_TRY(run_local_steps(h, h->X, nodes_dev, count, 0, (uint32_t)h->round));
     SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 1));
     h->timed_local += 1;
+    if (h->cfg.apply_mode == SWARM_APPLY_INPLACE) return SWARM_OK;   // already applied: nothing is pending
     if (nodes) for (uint32_t k = 0; k < count; ++k) h->pending[nodes[k]] = 1;
     else std::fill(h->pending.begin(), h->pending.end(), 1);
     return SWARM_OK;
@@ -459,14 +464,26 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
             stale[u] = (uint8_t)std::min<uint64_t>(stale_host[u], h->round);   // only rounds that exist
         }
     }
-    // Which kernel specialisation serves all pairs?
-    uint32_t with_delta = 0, with_stale = 0;
-    for (uint32_t k = 0; k < 2 * npairs; ++k) {
-        with_delta += h->pending[pairs[k]] != 0;
-        with_stale += stale[pairs[k]] != 0;
-    }
+    // Which kernel specialisations serve the pairs?  Pending marks: all / none / mixed.  Staleness:
+    // pairs are grouped into both-fresh, both-stale and one-stale (stale reader listed first), and
+    // each group gets the kernel compiled for it; with mixed pending marks one generic launch is used.
+    uint32_t with_delta = 0;
+    for (uint32_t k = 0; k < 2 * npairs; ++k) with_delta += h->pending[pairs[k]] != 0;
     const int delta_mode = with_delta == 0 ? 0 : (with_delta == 2 * npairs ? 1 : 2);
-    const int stale_mode = with_stale == 0 ? 0 : (with_stale == 2 * npairs ? 1 : 2);
+    std::vector<PairDesc> groups[3];          // 0: fresh/fresh, 1: stale/stale, 2: first stale only
+    auto describe = [&](uint32_t u, uint32_t v) {
+        return PairDesc{u, v, (uint32_t)stale[u] | ((uint32_t)stale[v] << 8) |
+                                  (h->pending[u] ? 1u << 16 : 0u) | (h->pending[v] ? 1u << 17 : 0u), 0u};
+    };
+    for (uint32_t p = 0; p < npairs; ++p) {
+        const uint32_t u = pairs[2 * p], v = pairs[2 * p + 1];
+        if (delta_mode == 2) groups[0].push_back(describe(u, v));
+        else if (!stale[u] && !stale[v]) groups[0].push_back(describe(u, v));
+        else if (stale[u] && stale[v]) groups[1].push_back(describe(u, v));
+        else if (stale[u]) groups[2].push_back(describe(u, v));
+        else groups[2].push_back(describe(v, u));
+    }
+    const int group_mode[3] = {delta_mode == 2 ? 2 : 0, 1, 3};
 
     // Per-round metadata: one descriptor per pair (nodes, staleness, pending flags) and the
     // unmatched nodes, staged in pinned memory and copied with one transfer.
@@ -475,11 +492,8 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
     const swarm_status rc = acquire_desc(h, &slot, &slot_index);
     if (rc != SWARM_OK) return rc;
     PairDesc *pd = (PairDesc *)(slot + h->off_pairs);
-    for (uint32_t p = 0; p < npairs; ++p) {
-        const uint32_t u = pairs[2 * p], v = pairs[2 * p + 1];
-        pd[p] = PairDesc{u, v, (uint32_t)stale[u] | ((uint32_t)stale[v] << 8) |
-                               (h->pending[u] ? 1u << 16 : 0u) | (h->pending[v] ? 1u << 17 : 0u), 0u};
-    }
+    for (int gidx = 0; gidx < 3; ++gidx)
+        for (const PairDesc &desc : groups[gidx]) *pd++ = desc;
     uint32_t *sg = (uint32_t *)(slot + h->off_singles);
     for (uint32_t k = 0; k < nsingles; ++k) sg[k] = singles[k] | (h->pending[singles[k]] ? SINGLE_PENDING : 0u);
     SWARM_HIP(h, hipMemcpyAsync(h->desc_dev, slot, h->desc_bytes, hipMemcpyHostToDevice, h->stream));
@@ -487,7 +501,14 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
 
     const GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
-    SWARM_HIP(h, launch_gossip_pairs(a, c.bits, delta_mode, stale_mode, npairs, h->stream));
+    {
+        GossipArgs ga = a;
+        for (int gidx = 0; gidx < 3; ++gidx) {
+            const uint32_t count = (uint32_t)groups[gidx].size();
+            SWARM_HIP(h, launch_gossip_pairs(ga, c.bits, delta_mode, group_mode[gidx], count, h->stream));
+            ga.pairs += count;
+        }
+    }
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
     h->timed_gossip += 1;
     // unmatched nodes: publish their code (needed by later stale reads) and apply their own steps
@@ -507,6 +528,7 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     if (!h) return SWARM_EINVAL;
     const swarm_config &c = h->cfg;
     if (c.stale_max != 0) return fail(h, SWARM_EINVAL, "Algorithm 1 steps need stale_max = 0");
+    if (c.apply_mode != SWARM_APPLY_DEFERRED) return fail(h, SWARM_EINVAL, "Algorithm 1 defers the local steps");
     if (i >= c.n || j >= c.n || i == j ||
         !std::binary_search(h->edge_keys.begin(), h->edge_keys.end(), edge_key(i, j)))
         return fail(h, SWARM_EINVAL, "responder is not a neighbour of the initiator");
@@ -594,7 +616,8 @@ swarm_status swarm_write_models(swarm_t h, uint32_t which, uint32_t node0, uint3
     SWARM_HIP(h, hipMemcpy2DAsync(dst, h->cfg.d * sizeof(float), src_host, len * sizeof(float), len * sizeof(float),
                                   count, hipMemcpyHostToDevice, h->stream));
     SWARM_HIP(h, hipStreamSynchronize(h->stream));
-    if (which == SWARM_MODELS_LIVE) for (uint32_t u = node0; u < node0 + count; ++u) h->pending[u] = 1;
+    if (which == SWARM_MODELS_LIVE && h->cfg.apply_mode == SWARM_APPLY_DEFERRED)
+        for (uint32_t u = node0; u < node0 + count; ++u) h->pending[u] = 1;
     if (which == SWARM_MODELS_COMM) for (uint32_t u = node0; u < node0 + count; ++u) h->pending[u] = 0;
     return SWARM_OK;
 }

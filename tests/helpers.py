@@ -24,9 +24,11 @@ def assert_close(gpu, cpu, tol, what=""):
                              f"gpu={np.asarray(gpu)[idx]!r} cpu={np.asarray(cpu)[idx]!r}")
 
 
-def make_both(swarm_mod, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0):
-    gpu = swarm_mod.Swarm(n, d, edges, bits, eps, H, lr, stale_max, seed)
-    cpu = SwarmOracle(n, d, edges, bits, eps, H, lr, stale_max, seed)
+def make_both(swarm_mod, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, inplace=False):
+    gpu = swarm_mod.Swarm(n, d, edges, bits, eps, H, lr, stale_max, seed,
+                          apply_mode=swarm_mod.INPLACE if inplace else swarm_mod.DEFERRED)
+    cpu = SwarmOracle(n, d, edges, bits, eps, H, lr, stale_max, seed,
+                      apply_mode="inplace" if inplace else "deferred")
     return gpu, cpu
 
 

@@ -368,3 +368,31 @@ def test_local_steps_mlp(gpu, shape):
     c.gossip_round(pairs)
     g.gossip_round(pairs)
     assert_close(g.read_models(gpu.COMM), c.X, TOL_GEMM, "models after the round")
+
+
+# ------------------------------------------------------------------ in-place apply mode
+def test_inplace_apply_mode_rounds(gpu):
+    """One matrix: the local steps update the exchanged model, the averaging acts on the result."""
+    n, d, H, lr, bits, eps, S = 8, D_RAGGED, 3, 0.1, 8, 2.0 ** -4, 1
+    edges = wl.torus_graph(2, 4)
+    a, cc = wl.diag_quadratic_data(n, d, 7)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=31, inplace=True)
+    c.objective = DiagQuadratic(a, cc, 0.05)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
+    gen = np.random.Generator(np.random.PCG64(31))
+    c.X[:] = models(gen, n, d)
+    for r in range(4):
+        g.write_models(gpu.COMM, c.X)
+        c.local_steps()
+        g.local_steps()
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"X after local steps, round {r}")
+        g.write_models(gpu.COMM, c.X)                      # same input to the gossip pass on both sides
+        pairs = c.sample_matching()
+        stale = [min(r, 1)] * n
+        c.gossip_round(pairs, stale)
+        g.gossip_round(None, stale)
+        for i in range(n):
+            assert np.array_equal(g.read_codes(i), ring_row(c, i)), (r, i)
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"X after round {r}")
+    with pytest.raises(gpu.SwarmError):
+        g.interact(0, 1)

@@ -392,3 +392,18 @@ def test_swarm_converges_to_the_global_minimiser_neighbourhood():
     assert o.decode_failures == 0
     assert np.sqrt(((o.mean() - xstar) ** 2).mean()) < 0.25
     assert np.mean(gam[100:]) < 1.5 * np.mean(gam[50:100]) + 1e-9
+
+
+def test_oracle_inplace_mode_is_average_of_updated_models():
+    """CPU pin of the in-place rule: with Q = identity, X_i' = (w_i + w_j)/2 where w = X - eta h~(X)."""
+    n, d, H, lr = 4, 16, 2, 0.1
+    a, cc = wl.diag_quadratic_data(n, d, 1)
+    o = SwarmOracle(n, d, wl.complete_graph(n), 0, 0.0, H, lr, 0, 0, state_dtype=np.float64, apply_mode="inplace")
+    o.objective = DiagQuadratic(a, cc, 0.0)
+    X = np.random.Generator(np.random.PCG64(0)).standard_normal((n, d))
+    o.X[:] = X
+    o.local_steps()
+    w = cc + (1 - np.float64(np.float32(lr)) * a.astype(np.float64)) ** H * (X - cc)
+    assert np.allclose(o.X, w, atol=1e-13) and not o.pending.any()
+    o.gossip_round([(0, 1)])
+    assert np.allclose(o.X[0], (w[0] + w[1]) / 2) and np.array_equal(o.X[0], o.X[1])
