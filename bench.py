@@ -19,15 +19,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per pair-coordinate of the fused gossip pass from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs,
-# scaled by the stream-copy calibration (17.00 B fetched + 8.99 B written at 4-bit codes, stale reads).
-MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {(4, True): 25.99}
+# HBM bytes per pair-coordinate from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by the stream-copy
+# calibration (see profiles/), at 4-bit codes with stale reads: key = (kernel, bits, stale).
+MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {("gossip", 4, True): 25.99, ("round", 4, True): 33.99}
 
 
-def algorithmic_bytes_per_pair_coordinate(bits, stale, delta=True):
-    """Fused gossip pass: read X_i, X_j (+ W_i, W_j when local steps are pending), write
-    X_i', X_j', write two b-bit codes, read two b-bit stale codes when the reads are stale."""
-    return 8 + (8 if delta else 0) + 8 + 2 * bits / 8 + (2 * bits / 8 if stale else 0)
+def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction):
+    """Gossip pass: read X_i, X_j, W_i, W_j (16 B), write X_i', X_j' (8 B), write two b-bit codes, read
+    two b-bit partner codes when the reads are stale.  One-pass round (local steps inside the gossip
+    pass): read X, a, c of both nodes (24 B) instead of X and W; W never moves."""
+    reads = 16 if kernel == "gossip" else 24
+    return reads + 8 + 2 * bits / 8 + stale_fraction * 2 * bits / 8
 
 
 def build_workload(cfg_id, scale_d=None):
@@ -140,6 +142,41 @@ def cpu_baseline_mlp(cfg, edges, means, cdf, eps):
                        f"gossip of full rows, {dt:.2f} s; a round of the whole swarm is {n // 2} such units")
 
 
+def measure(torch, s, step, steps, warmup):
+    """W untimed steps, then exactly `steps` timed ones between two device synchronisations."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    before = s.counters(raise_on_range=False)
+    s.timing_reset()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    after = s.counters(raise_on_range=False)
+    return dict(dt=dt, times=s.kernel_times(), interactions=after["interactions"] - before["interactions"],
+                decode_failures=after["decode_failures"] - before["decode_failures"])
+
+
+def roofline(kernel, name, cfg, m, d):
+    """Algorithmic bytes of the timed launches / their summed HIP-event duration, against 8 TB/s."""
+    bits, S = cfg["bits"], cfg["stale_max"]
+    stale_fraction = {"fixed1": 1.0, "uniform": S / (S + 1.0)}.get(cfg.get("stale"), 0.0)
+    per_pc = algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction)
+    launches = max(1, m["times"]["gossip_calls"])
+    total = per_pc * d * m["interactions"]
+    seconds = m["times"]["gossip_ms"] * 1e-3
+    achieved = total / seconds / 1e9 if seconds > 0 else 0.0
+    measured = MEASURED_TRAFFIC_PER_PAIR_COORDINATE.get((kernel, bits, stale_fraction == 1.0))
+    return {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None if measured is None else measured * d * m["interactions"] / launches,
+            "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE counters, calibrated on the stream copy)",
+            "achieved_bytes_per_launch": total / launches, "bytes_per_pair_coordinate": per_pc,
+            "ms_per_launch": m["times"]["gossip_ms"] / launches}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -147,12 +184,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload configuration (2, 3, 4 or 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-call", action="store_true",
+                    help="time swarm_local_steps + swarm_gossip_round as the step instead of the one-pass round")
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build simulates the whole swarm on ONE GPU; --gpus must be 1 "
                          "(no collectives or sharding across GPUs are part of it)")
-    import numpy as np
     import torch
     import paper_1910_12308_amd as swarm
 
@@ -160,79 +198,79 @@ def main():
     cfg, edges, a, c = build_workload(args.config, args.d)
     n, d, bits = cfg["n"], cfg["d"], cfg["bits"]
     eps = eps_for(cfg)
-    s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0)
     if cfg["objective"] == "mlp":
         x0 = 0.02 * torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
-        s.close()
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0, x0=x0)
         s.set_objective_mlp(cfg["n_in"], cfg["n_hid"], cfg["n_out"], a, c, cfg["data_sigma"], cfg["batch"])
     else:
+        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0)
         s.set_objective_diag(a, c, cfg["sigma"])
 
-    def step():
+    def step_two_calls():
         s.local_steps()
         s.gossip_round(None, stale_plan(cfg, s))
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    before = s.counters(raise_on_range=False)
-    s.timing_reset()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    after = s.counters(raise_on_range=False)
-    times = s.kernel_times()
-    interactions = after["interactions"] - before["interactions"]
+    def step_one_pass():
+        s.round_fused(None, stale_plan(cfg, s))
 
-    # Roofline of the dominant kernel (the fused gossip pass): algorithmic bytes / measured kernel time.
-    stale = cfg["stale_max"] > 0 and cfg.get("stale") == "fixed1"
-    per_pc = algorithmic_bytes_per_pair_coordinate(bits, stale)
-    if cfg.get("stale") == "uniform":                 # each read is stale with probability S/(S+1) after warm-up
-        per_pc = algorithmic_bytes_per_pair_coordinate(bits, False) + (2 * bits / 8) * cfg["stale_max"] / (cfg["stale_max"] + 1)
-    gossip_bytes = per_pc * d * interactions
-    gossip_s = times["gossip_ms"] * 1e-3
-    achieved = gossip_bytes / gossip_s / 1e9 if gossip_s > 0 else 0.0
-    local_bytes = 16.0 * d * n * times["local_calls"]
-    local_gbs = local_bytes / (times["local_ms"] * 1e-3) / 1e9 if times["local_ms"] > 0 else 0.0
-    mlp = None
-    if cfg["objective"] == "mlp":
-        # 5 GEMMs of 2*batch*in*hid (= 2*batch*hid*out here) flops per node and local step
-        flops = 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"] * n * cfg["H"] * times["local_calls"]
-        mlp = flops / (times["local_ms"] * 1e-3) / 1e12
+    # The step is one pass of the whole hot path.  For per-coordinate objectives the library offers it as
+    # one kernel pass (local steps inside the gossip pass, bit-identical to the two calls); that is the
+    # timed step unless --two-call is given.  The other variant is measured after the timed region and
+    # reported beside it.
+    one_pass_ok = cfg["objective"] == "diag"
+    use_one_pass = one_pass_ok and not args.two_call
+    main_m = measure(torch, s, step_one_pass if use_one_pass else step_two_calls, args.steps, args.warmup)
+    other_m = None
+    if one_pass_ok:
+        other_m = measure(torch, s, step_two_calls if use_one_pass else step_one_pass, args.steps, 2)
+    one_m, two_m = (main_m, other_m) if use_one_pass else (other_m, main_m)
 
+    def two_call_report(m):
+        t = m["times"]
+        rep = {"interactions_per_s": m["interactions"] / m["dt"], "ms_per_step": m["dt"] / args.steps * 1e3,
+               "gossip_pass": roofline("gossip", "gossip_pairs_kernel (quantize/exchange/decode/average)", cfg, m, d),
+               "local_steps_ms_per_round": t["local_ms"] / max(1, t["local_calls"])}
+        if cfg["objective"] == "mlp":
+            # 5 GEMMs of 2*batch*in*hid (= 2*batch*hid*out here) flops per node and local step
+            flops = 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"] * n * cfg["H"] * t["local_calls"]
+            rep["local_steps_mfma_f32_TFLOPs"] = flops / (t["local_ms"] * 1e-3) / 1e12
+            rep["local_steps_mfma_frac_of_157.3"] = rep["local_steps_mfma_f32_TFLOPs"] / 157.3
+        elif t["local_ms"] > 0:
+            rep["local_steps_GBps"] = 16.0 * d * n * t["local_calls"] / (t["local_ms"] * 1e-3) / 1e9
+            rep["local_steps_frac_of_hbm_peak"] = rep["local_steps_GBps"] / HBM_PEAK_GBS
+        return rep
+
+    if use_one_pass:
+        roof = roofline("round", "fused_pairs_kernel (H local steps + quantize/exchange/decode/average, one pass)",
+                        cfg, main_m, d)
+    else:
+        roof = roofline("gossip", "gossip_pairs_kernel (quantize/exchange/decode/average)", cfg, main_m, d)
     out = {
         "metric": "node-interactions/sec + gossip-avg HBM GB/s (% of peak), n=64 d=25.6M",
-        "value": interactions / dt,
+        "value": main_m["interactions"] / main_m["dt"],
         "unit": "interactions/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": dt / args.steps * 1e3,
+        "ms_per_step": main_m["dt"] / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config}: n={n} d={d} graph={cfg['graph']} {cfg['objective']} "
                                f"sigma={cfg.get('sigma', cfg.get('data_sigma'))} H={cfg['H']} lr={cfg['lr']} bits={bits} "
                                f"stale_max={cfg['stale_max']} ({cfg.get('stale', 'fresh')}) eps={eps}",
-                   "pairs_per_round": interactions / args.steps,
-                   "decode_failures": after["decode_failures"] - before["decode_failures"],
-                   "gossip_ms_per_round": times["gossip_ms"] / max(1, times["gossip_calls"]),
-                   "local_steps_ms_per_round": times["local_ms"] / max(1, times["local_calls"]),
-                   "local_steps_GBps": None if mlp is not None else local_gbs,
-                   "local_steps_mfma_f32_TFLOPs": mlp,
-                   "local_steps_mfma_frac_of_157.3": None if mlp is None else mlp / 157.3},
-        "roofline": {"kernel": "gossip_pairs_kernel (fused quantize/exchange/decode/average)",
-                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (MEASURED_TRAFFIC_PER_PAIR_COORDINATE[(bits, stale)] * d * interactions
-                                 / max(1, times["gossip_calls"])
-                                 if (bits, stale) in MEASURED_TRAFFIC_PER_PAIR_COORDINATE else None),
-                     "traffic_unit": "bytes per launch (counters, calibrated on the stream copy)",
-                     "achieved_bytes_per_launch": gossip_bytes / max(1, times["gossip_calls"]),
-                     "bytes_per_pair_coordinate": per_pc},
+                   "step": ("one-pass round (swarm_round_fused)" if use_one_pass
+                            else "swarm_local_steps + swarm_gossip_round"),
+                   "pairs_per_round": main_m["interactions"] / args.steps,
+                   "decode_failures": main_m["decode_failures"]},
+        "roofline": roof,
     }
+    if two_m is not None:
+        out["two_call_round"] = two_call_report(two_m)
+    if one_m is not None and not use_one_pass:
+        out["one_pass_round"] = {"interactions_per_s": one_m["interactions"] / one_m["dt"],
+                                 "ms_per_step": one_m["dt"] / args.steps * 1e3,
+                                 "roofline": roofline("round", "fused_pairs_kernel", cfg, one_m, d)}
     # Measured ceiling: a plain streaming copy kernel over one model matrix worth of bytes.
-    src, dst = s.models_view(swarm.COMM), s.models_view(swarm.LIVE)   # W is rebuilt by every step
+    src = s.models_view(swarm.COMM)
+    dst = torch.empty_like(src)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     swarm.stream_copy(dst, src)
     ev0.record()
@@ -241,8 +279,9 @@ def main():
     ev1.record()
     torch.cuda.synchronize()
     copy_gbs = 2.0 * src.numel() * 4 * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del dst
     out["roofline"]["copy_kernel_GBps"] = copy_gbs
-    out["roofline"]["frac_of_copy"] = achieved / copy_gbs
+    out["roofline"]["frac_of_copy"] = out["roofline"]["achieved"] / copy_gbs
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, edges, a, c, eps)
     print(json.dumps(out))

@@ -127,6 +127,15 @@ swarm_status swarm_sample_stale(swarm_t h, uint8_t *stale_host);
 swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t npairs,
                                 const uint8_t *stale_host);
 
+/* The same round in one pass, for objectives whose gradient is per-coordinate (the diagonal
+ * quadratic): equivalent, bit for bit, to swarm_local_steps(all nodes) followed by
+ * swarm_gossip_round(pairs, stale), but the H local steps of each node are taken in registers
+ * inside the gossip pass and the live copies W are neither written nor read (W keeps its old
+ * contents).  Needs bits > 0, H > 0, the diagonal objective and no pending local steps
+ * (SWARM_ESTATE otherwise). */
+swarm_status swarm_round_fused(swarm_t h, const uint32_t *pairs_host, uint32_t npairs,
+                               const uint8_t *stale_host);
+
 /* One step of Algorithm 1 (sequential model), initiator i, responder j adjacent to i:
  * i runs its H local steps from its snapshot Xhat_i, then
  *     X_i <- (Q(X_i) + Q(X_j)) / 2 + (W_i - Xhat_i),   X_j <- (Q(X_i) + Q(X_j)) / 2,

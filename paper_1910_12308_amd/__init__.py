@@ -21,7 +21,7 @@ _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_E
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
            "swarm_set_objective_mlp", "swarm_local_steps", "swarm_sample_matching", "swarm_sample_stale",
-           "swarm_gossip_round", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
+           "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
            "swarm_potential", "swarm_pair_linf", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
            "swarm_stream_copy", "swarm_last_error"]
@@ -57,6 +57,7 @@ def load_library():
         "swarm_sample_matching": [vp, vp, P(u32)],
         "swarm_sample_stale": [vp, vp],
         "swarm_gossip_round": [vp, vp, u32, vp],
+        "swarm_round_fused": [vp, vp, u32, vp],
         "swarm_interact": [vp, u32, u32],
         "swarm_sample_pair": [vp, P(u32), P(u32)],
         "swarm_quantize": [vp, u64, f32, u32, u64, u32, u32, vp, vp],
@@ -189,18 +190,24 @@ class Swarm:
         self._check(self._lib.swarm_sample_stale(self._h, out.ctypes.data_as(ctypes.c_void_p)))
         return out
 
+    def round_fused(self, pairs=None, stale=None):
+        """Local steps + gossip round in one pass (diagonal objective only)."""
+        self._round(self._lib.swarm_round_fused, pairs, stale)
+
     def gossip_round(self, pairs=None, stale=None):
+        self._round(self._lib.swarm_gossip_round, pairs, stale)
+
+    def _round(self, fn, pairs, stale):
         sp = None
         if stale is not None:
             stale = np.ascontiguousarray(np.asarray(stale, dtype=np.uint8))
             assert stale.size == self.n
             sp = stale.ctypes.data_as(ctypes.c_void_p)
         if pairs is None:
-            self._check(self._lib.swarm_gossip_round(self._h, None, 0, sp))
+            self._check(fn(self._h, None, 0, sp))
         else:
             pairs = _host_u32(pairs)
-            self._check(self._lib.swarm_gossip_round(self._h, pairs.ctypes.data_as(ctypes.c_void_p),
-                                                     pairs.size // 2, sp))
+            self._check(fn(self._h, pairs.ctypes.data_as(ctypes.c_void_p), pairs.size // 2, sp))
 
     def interact(self, i, j):
         self._check(self._lib.swarm_interact(self._h, int(i), int(j)))

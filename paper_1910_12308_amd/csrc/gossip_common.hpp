@@ -1,0 +1,102 @@
+// Device helpers shared by the gossip kernels: tile geometry, non-temporal 128-bit accesses,
+// packed code words, the per-lane random words of a row (one Philox call per 8 coordinates,
+// halves swapped between neighbouring lanes), rounding of a float4 and the averaging rule.
+#pragma once
+#include "internal.h"
+#include "philox.hpp"
+#include "quant.hpp"
+
+namespace swarm {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int TILE = 512;          // coordinates per wave
+#ifndef SWARM_GOSSIP_WAVES
+#define SWARM_GOSSIP_WAVES 8
+#endif
+constexpr int WAVES = SWARM_GOSSIP_WAVES;   // waves per workgroup
+
+__device__ __forceinline__ f4 ldg_nt(const float *p) { return __builtin_nontemporal_load((const f4 *)p); }
+__device__ __forceinline__ void stg_nt(float *p, f4 v) { __builtin_nontemporal_store(v, (f4 *)p); }
+__device__ __forceinline__ uint32_t swap_with_neighbour(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+}
+
+// Packed code of one float4 (4 coordinates, 4*BITS bits, coordinate m at bit m*BITS).
+template <int BITS> struct CodeWord;
+template <> struct CodeWord<2>  { typedef uint8_t  type; };
+template <> struct CodeWord<4>  { typedef uint16_t type; };
+template <> struct CodeWord<8>  { typedef uint32_t type; };
+template <> struct CodeWord<16> { typedef uint64_t type; };
+
+template <int BITS>
+__device__ __forceinline__ uint64_t load_code(const uint8_t *row, uint64_t f) {
+    return (uint64_t)__builtin_nontemporal_load((const typename CodeWord<BITS>::type *)(row + f * (BITS / 2)));
+}
+template <int BITS>
+__device__ __forceinline__ void store_code(uint8_t *row, uint64_t f, uint64_t c) {
+    __builtin_nontemporal_store((typename CodeWord<BITS>::type)c,
+                                (typename CodeWord<BITS>::type *)(row + f * (BITS / 2)));
+}
+
+// The two random words of the float4 this lane holds in the tile's first half (lo*)
+// and second half (hi*), for one row.
+struct LaneRandom { uint32_t a0, a1, b0, b1; };
+
+__device__ __forceinline__ LaneRandom row_random(uint64_t seed, uint32_t node, uint32_t event,
+                                                 uint64_t tile, uint32_t lane) {
+    const bool odd = lane & 1u;
+    const uint64_t group = tile * (TILE / 8) + (lane >> 1) + (odd ? 32u : 0u);
+    const Words4 w = stream(seed, TAG_SR, 0, node, event, group);
+    // even lane keeps words 0,1 of group A and needs words 0,1 of group B (made by the odd lane);
+    // odd lane keeps words 2,3 of group B and needs words 2,3 of group A (made by the even lane).
+    const uint32_t r0 = swap_with_neighbour(odd ? w.w0 : w.w2);
+    const uint32_t r1 = swap_with_neighbour(odd ? w.w1 : w.w3);
+    LaneRandom out;
+    out.a0 = odd ? r0 : w.w0;  out.a1 = odd ? r1 : w.w1;
+    out.b0 = odd ? w.w2 : r0;  out.b1 = odd ? w.w3 : r1;
+    return out;
+}
+
+template <int BITS>
+__device__ __forceinline__ uint64_t round_float4(f4 x, uint32_t w_lo, uint32_t w_hi, float inv_eps,
+                                                 int z[4], bool &clamped) {
+    z[0] = stochastic_round(x.x, inv_eps, w_lo & 0xFFFFu, clamped);
+    z[1] = stochastic_round(x.y, inv_eps, w_lo >> 16, clamped);
+    z[2] = stochastic_round(x.z, inv_eps, w_hi & 0xFFFFu, clamped);
+    z[3] = stochastic_round(x.w, inv_eps, w_hi >> 16, clamped);
+    constexpr uint64_t MASK = (1ull << BITS) - 1;
+    return ((uint64_t)z[0] & MASK) | (((uint64_t)z[1] & MASK) << BITS) |
+           (((uint64_t)z[2] & MASK) << (2 * BITS)) | (((uint64_t)z[3] & MASK) << (3 * BITS));
+}
+
+// Average of own lattice point and the partner's decoded one, plus the pending update.
+template <int BITS>
+__device__ __forceinline__ f4 averaged(const int z_own[4], uint64_t partner_code, f4 key, f4 delta,
+                                       float inv_eps, float half_eps, const int *z_true, int &fails,
+                                       bool &clamped) {
+    constexpr uint32_t MASK = (uint32_t)((1ull << BITS) - 1);
+    const float k[4] = {key.x, key.y, key.z, key.w};
+    const float dl[4] = {delta.x, delta.y, delta.z, delta.w};
+    float o[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int zp = decode_near<BITS>((uint32_t)(partner_code >> (m * BITS)) & MASK,
+                                         key_cell(k[m], inv_eps, clamped));
+        if (z_true) fails += (zp != z_true[m]);
+        o[m] = (float)(z_own[m] + zp) * half_eps + dl[m];
+    }
+    return f4{o[0], o[1], o[2], o[3]};
+}
+
+__device__ __forceinline__ void report(DeviceCounters *c, int fails, bool clamped) {
+    if (__builtin_expect(__any(fails != 0), 0)) {
+        for (int off = 32; off > 0; off >>= 1) fails += __shfl_xor(fails, off);
+        if ((threadIdx.x & 63) == 0) atomicAdd(&c->decode_failures, (unsigned long long)fails);
+    }
+    if (__builtin_expect(__any(clamped), 0)) {
+        if ((threadIdx.x & 63) == 0) atomicOr(&c->range_clamped, 1u);
+    }
+}
+
+}  // namespace swarm

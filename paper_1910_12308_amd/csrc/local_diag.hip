@@ -5,12 +5,9 @@
 // steps of a coordinate stay in registers: one read of the base model, a and c, one
 // write of the live copy W.  One thread owns one float4; one Philox call per step
 // gives its four normals.
-#include "internal.h"
-#include "philox.hpp"
+#include "diag_steps.hpp"
 
 namespace swarm {
-
-typedef float f4 __attribute__((ext_vector_type(4)));
 
 template <bool NOISE>
 __global__ __launch_bounds__(256) void local_diag_kernel(const float *__restrict__ X, float *__restrict__ W,
@@ -24,22 +21,7 @@ __global__ __launch_bounds__(256) void local_diag_kernel(const float *__restrict
     f4 w = __builtin_nontemporal_load((const f4 *)(X + off));
     const f4 a = __builtin_nontemporal_load((const f4 *)(A + off));
     const f4 c = __builtin_nontemporal_load((const f4 *)(C + off));
-    for (uint32_t q = 0; q < H; ++q) {
-        f4 noise = {0.f, 0.f, 0.f, 0.f};
-        if (NOISE) {
-            const Words4 r = stream(seed, TAG_NOISE, q, node, event, f);
-            float n0, n1, n2, n3;
-            box_muller(r.w0, r.w1, n0, n1);
-            box_muller(r.w2, r.w3, n2, n3);
-            noise = f4{n0, n1, n2, n3} * sigma;
-        }
-        const f4 t = w - c;
-        f4 g;
-        g.x = fmaf(a.x, t.x, noise.x); g.y = fmaf(a.y, t.y, noise.y);
-        g.z = fmaf(a.z, t.z, noise.z); g.w = fmaf(a.w, t.w, noise.w);
-        w.x = fmaf(-lr, g.x, w.x); w.y = fmaf(-lr, g.y, w.y);
-        w.z = fmaf(-lr, g.z, w.z); w.w = fmaf(-lr, g.w, w.w);
-    }
+    w = diag_steps<NOISE>(w, a, c, node, f, H, lr, sigma, seed, event);
     __builtin_nontemporal_store(w, (f4 *)(W + off));
 }
 

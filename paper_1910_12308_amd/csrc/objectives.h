@@ -25,6 +25,13 @@ struct MlpObjective {
     uint32_t n_nodes = 0;
 };
 
+// Whole round in one pass (local steps + quantized gossip) for the diagonal objective; bits in {2,4,8,16}.
+struct GossipArgs;
+hipError_t launch_fused_pairs(const GossipArgs &g, const DiagObjective &o, uint32_t bits, bool inplace, uint32_t H,
+                              float lr, int stale_mode, uint32_t npairs, hipStream_t st);
+hipError_t launch_fused_singles(const GossipArgs &g, const DiagObjective &o, uint32_t bits, bool inplace, uint32_t H,
+                                float lr, uint32_t nsingles, hipStream_t st);
+
 hipError_t launch_local_lsq(const float *base, float *W, const LsqObjective &o, const uint32_t *nodes,
                             uint32_t count, uint64_t d, uint32_t H, float lr, uint64_t seed, uint32_t event,
                             hipStream_t st);

@@ -429,9 +429,15 @@ swarm_status swarm_sample_pair(swarm_t h, uint32_t *i, uint32_t *j) {
     return SWARM_OK;
 }
 
-swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t npairs, const uint8_t *stale_host) {
-    if (!h) return SWARM_EINVAL;
+static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t npairs, const uint8_t *stale_host,
+                               bool fused) {
     const swarm_config &c = h->cfg;
+    if (fused) {
+        if (h->kind != OBJ_DIAG) return fail(h, SWARM_ESTATE, "the fused round needs the diagonal-quadratic objective");
+        if (c.bits == 0 || c.H == 0) return fail(h, SWARM_ESTATE, "the fused round needs quantized codes and H > 0");
+        for (uint8_t p : h->pending)
+            if (p) return fail(h, SWARM_ESTATE, "local steps are already pending: use swarm_gossip_round");
+    }
     const uint32_t n = c.n;
     std::vector<uint32_t> pairs, singles;
     uint32_t nsingles = 0;
@@ -501,20 +507,28 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
 
     const GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
+    const bool inplace = c.apply_mode == SWARM_APPLY_INPLACE;
     {
         GossipArgs ga = a;
         for (int gidx = 0; gidx < 3; ++gidx) {
             const uint32_t count = (uint32_t)groups[gidx].size();
-            SWARM_HIP(h, launch_gossip_pairs(ga, c.bits, delta_mode, group_mode[gidx], count, h->stream));
+            if (fused)
+                SWARM_HIP(h, launch_fused_pairs(ga, h->diag, c.bits, inplace, c.H, c.lr, group_mode[gidx], count, h->stream));
+            else
+                SWARM_HIP(h, launch_gossip_pairs(ga, c.bits, delta_mode, group_mode[gidx], count, h->stream));
             ga.pairs += count;
         }
     }
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
     h->timed_gossip += 1;
     // unmatched nodes: publish their code (needed by later stale reads) and apply their own steps
-    bool singles_work = c.bits != 0;
-    for (uint32_t u : singles) singles_work |= h->pending[u] != 0;
-    if (singles_work) SWARM_HIP(h, launch_gossip_singles(a, c.bits, nsingles, h->stream));
+    if (fused) {
+        SWARM_HIP(h, launch_fused_singles(a, h->diag, c.bits, inplace, c.H, c.lr, nsingles, h->stream));
+    } else {
+        bool singles_work = c.bits != 0;
+        for (uint32_t u : singles) singles_work |= h->pending[u] != 0;
+        if (singles_work) SWARM_HIP(h, launch_gossip_singles(a, c.bits, nsingles, h->stream));
+    }
 
     std::fill(h->pending.begin(), h->pending.end(), 0);
     h->round += 1;
@@ -522,6 +536,16 @@ swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t 
     h->bits_communicated += 2ull * npairs * c.d * (c.bits ? c.bits : 32);
     if (device_pairs) SWARM_TRY(enqueue_matching(h));   // next round's matching, one round ahead
     return SWARM_OK;
+}
+
+swarm_status swarm_gossip_round(swarm_t h, const uint32_t *pairs_host, uint32_t npairs, const uint8_t *stale_host) {
+    if (!h) return SWARM_EINVAL;
+    return round_impl(h, pairs_host, npairs, stale_host, false);
+}
+
+swarm_status swarm_round_fused(swarm_t h, const uint32_t *pairs_host, uint32_t npairs, const uint8_t *stale_host) {
+    if (!h) return SWARM_EINVAL;
+    return round_impl(h, pairs_host, npairs, stale_host, true);
 }
 
 swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {

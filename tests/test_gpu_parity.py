@@ -396,3 +396,42 @@ def test_inplace_apply_mode_rounds(gpu):
         assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"X after round {r}")
     with pytest.raises(gpu.SwarmError):
         g.interact(0, 1)
+
+
+# ------------------------------------------------------------------ fused round (local steps inside the gossip pass)
+@pytest.mark.parametrize("inplace", [False, True])
+@pytest.mark.parametrize("bits,S", [(4, 1), (8, 2)])
+def test_fused_round_equals_two_calls_and_oracle(gpu, inplace, bits, S):
+    n, d, H, lr, eps, sigma = 10, D_RAGGED, 3, 0.1, 2.0 ** -3, 0.05
+    edges = wl.random_regular_graph(n, 3, 1)
+    a, cc = wl.diag_quadratic_data(n, d, 11)
+    ad, cd = torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda()
+    fused, c = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=17, inplace=inplace)
+    split, _ = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=17, inplace=inplace)
+    c.objective = DiagQuadratic(a, cc, sigma)
+    fused.set_objective_diag(ad, cd, sigma)
+    split.set_objective_diag(ad, cd, sigma)
+    gen = np.random.Generator(np.random.PCG64(17))
+    c.X[:] = models(gen, n, d, 0.3)
+    for r in range(5):
+        fused.write_models(gpu.COMM, c.X)
+        split.write_models(gpu.COMM, c.X)
+        pairs = c.sample_matching()
+        stale = fused.sample_stale()
+        assert np.array_equal(stale, c.sample_stale().astype(np.uint8))
+        c.local_steps()
+        c.gossip_round(pairs, stale)
+        split.local_steps()
+        split.gossip_round(None, stale)
+        fused.round_fused(None, stale)
+        Xf, Xs = fused.read_models(gpu.COMM), split.read_models(gpu.COMM)
+        assert np.array_equal(Xf, Xs), f"fused and two-call rounds differ, round {r}"
+        for i in range(n):
+            assert np.array_equal(fused.read_codes(i), ring_row(c, i)), (r, i)
+        assert_close(Xf, c.X, 2 * TOL_ELEMENTWISE, f"X after fused round {r}")
+    assert fused.counters() == split.counters()
+    fused.local_steps()
+    if not inplace:
+        with pytest.raises(gpu.SwarmError) as err:
+            fused.round_fused(None)                        # steps already pending
+        assert err.value.status == gpu.ESTATE
