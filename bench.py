@@ -5,8 +5,11 @@ A step is one pass of the whole hot path over the synthetic swarm of the headlin
 workload (n = 64 nodes on a random 4-regular graph, d = 25.6 M float32 parameters,
 diagonal-quadratic objectives with gradient noise 0.05, H = 3 local steps, 4-bit codes,
 every read one round stale): H local steps on every node, the round's random maximal
-matching, the fused quantized gossip pass over the matched pairs, and the unmatched
-nodes' own updates.  Prints ONE JSON line.
+matching, the quantized gossip pass over the matched pairs, and the unmatched nodes' own
+updates.  For per-coordinate objectives the library runs all of it in one kernel pass
+(swarm_round_fused, bit-identical to swarm_local_steps + swarm_gossip_round); that is the
+timed step, and the two-call variant is measured after it and reported in the same line.
+Prints ONE JSON line.
 """
 import argparse
 import json
