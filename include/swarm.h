@@ -49,6 +49,12 @@ typedef enum {
  * updated models; one matrix, no pending update (W is an alias of X). */
 enum { SWARM_APPLY_DEFERRED = 0, SWARM_APPLY_INPLACE = 1 };
 
+/* Number of local steps per interaction.  CONSTANT: H for every node (the paper's experiments).
+ * GEOMETRIC: each node draws H_i >= 1 afresh for every interaction from a geometric law of mean H
+ * (Section 3 "Sequential model": approximates activation by independent Poisson clocks), capped
+ * at 255; H_i = 1 + number of failures before the first 32-bit word below floor(2^32 / H). */
+enum { SWARM_STEPS_CONSTANT = 0, SWARM_STEPS_GEOMETRIC = 1 };
+
 enum { SWARM_MODELS_COMM = 0,  /* X: current / communicated models                        */
        SWARM_MODELS_LIVE = 1,  /* W: live copies carrying the pending local steps         */
        SWARM_MODELS_SNAP = 2   /* Xhat: models at the last initiation (Algorithm 1)       */ };
@@ -69,6 +75,8 @@ typedef struct {
                                ago; the ring keeps S+1 slots. Must be 0 when bits = 0.     */
     uint64_t seed;          /* key of every random stream                                  */
     uint32_t apply_mode;    /* SWARM_APPLY_DEFERRED (default) or SWARM_APPLY_INPLACE           */
+    uint32_t steps_law;     /* SWARM_STEPS_CONSTANT (default) or SWARM_STEPS_GEOMETRIC (H >= 1;
+                               not available with the MLP objective)                           */
 } swarm_config;
 
 /* Create a handle.  x0_dev: d floats (device) copied into every node's model, or NULL
@@ -115,6 +123,10 @@ swarm_status swarm_sample_matching(swarm_t h, uint32_t *pairs_host, uint32_t *np
 /* Draws, for every node, the staleness of its next read: uniform on {0..S}, limited to
  * the number of rounds done.  stale_host: n bytes.  Does not touch the device. */
 swarm_status swarm_sample_stale(swarm_t h, uint8_t *stale_host);
+
+/* The numbers of local steps H_i the nodes take for the current round (n bytes): H for every
+ * node under SWARM_STEPS_CONSTANT, else this round's geometric draws.  Does not touch the device. */
+swarm_status swarm_sample_steps(swarm_t h, uint8_t *steps_host);
 
 /* One gossip round (Section 3 "Parallel Execution"): every node publishes the code of
  * its model X_i into ring slot r mod (S+1); for every pair (i, j), i decodes the code j

@@ -24,7 +24,8 @@ TAG_MATCH = 3   # edge priorities of the round's matching, c2 = edge id
 TAG_PICK = 4    # sequential model: initiator and responder
 TAG_BATCH = 5   # least squares: minibatch rows, index = draw // 4
 TAG_STALE = 6   # staleness of a node's read of its partner
-TAG_DATA = 7    # MLP: labels (q' = 0) and features of the synthetic mixture
+TAG_DATA = 7    # MLP: features of the synthetic mixture (labels use tag 8)
+TAG_STEPS = 9   # geometric number of local steps: Bernoulli trials, index = trial // 4
 
 
 def seed_key(seed):

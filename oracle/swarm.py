@@ -16,7 +16,7 @@ from . import rng
 
 class SwarmOracle:
     def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None,
-                 k0=0, k1=None, state_dtype=np.float32, apply_mode="deferred"):
+                 k0=0, k1=None, state_dtype=np.float32, apply_mode="deferred", steps_law="constant"):
         self.n, self.d = int(n), int(d)
         self.k0 = int(k0)
         self.k1 = self.d if k1 is None else int(k1)
@@ -30,6 +30,10 @@ class SwarmOracle:
         # "inplace": the steps update the exchanged model itself before the averaging.
         assert apply_mode in ("deferred", "inplace")
         self.apply_mode = apply_mode
+        # "constant": H steps (the paper's experiments); "geometric": H_i ~ geometric of mean H, the
+        # paper's stand-in for activation by Poisson clocks (Section 3, "Sequential model").
+        assert steps_law in ("constant", "geometric") and (steps_law == "constant" or self.H >= 1)
+        self.steps_law = steps_law
         self.dtype = state_dtype
         dw = self.k1 - self.k0
         self.X = np.zeros((self.n, dw), dtype=state_dtype)
@@ -49,13 +53,31 @@ class SwarmOracle:
                            set(self.edges[self.edges[:, 1] == i, 0])) for i in range(self.n)]
 
     # ---- local steps: h~_i^q = g~_i(base - eta sum_{s<q} h~_i^s), fresh sample each q ----
+    def steps_of(self, node, event):
+        """H, or 1 + the number of failed Bernoulli(p) trials before the first success, p =
+        floor(2^32 / H) / 2^32, one trial per 32-bit word of the node's STEPS stream, capped at 255.
+        Mean H and second moment 2H^2 - H (appendix, properties of the local steps)."""
+        if self.steps_law == "constant" or self.H == 1:
+            return self.H
+        threshold = (1 << 32) // self.H
+        k = 1
+        for call in range(64):
+            for word in rng.stream(self.seed, rng.TAG_STEPS, 0, node, event, np.array([call])):
+                if int(word[0]) < threshold or k >= 255:
+                    return k
+                k += 1
+        return k
+
+    def sample_steps(self):
+        return np.array([self.steps_of(i, self.round) for i in range(self.n)], dtype=np.int64)
+
     def local_steps(self, nodes=None, sequential=False):
         nodes = range(self.n) if nodes is None else nodes
         event = self.interactions if sequential else self.round
         for i in nodes:
             base = self.Xhat[i] if sequential else self.X[i]
             w = base.astype(np.float64)
-            for q in range(self.H):
+            for q in range(self.steps_of(i, event)):
                 w = w - self.lr * self.objective.gradient(i, w, self.seed, event, q)
             if self.apply_mode == "inplace":
                 assert not sequential

@@ -17,10 +17,11 @@ LIB_PATH = os.path.join(_HERE, "libswarm.so")
 OK, EINVAL, ENOMEM, EDEVICE, ESTATE, ERANGE = range(6)
 COMM, LIVE, SNAP = 0, 1, 2
 DEFERRED, INPLACE = 0, 1
+CONSTANT, GEOMETRIC = 0, 1
 _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_ESTATE", 5: "SWARM_ERANGE"}
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
-           "swarm_set_objective_mlp", "swarm_local_steps", "swarm_sample_matching", "swarm_sample_stale",
+           "swarm_set_objective_mlp", "swarm_local_steps", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
            "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
            "swarm_potential", "swarm_pair_linf", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
@@ -37,7 +38,7 @@ class _Config(ctypes.Structure):
     _fields_ = [("n", ctypes.c_uint32), ("d", ctypes.c_uint64), ("n_edges", ctypes.c_uint32),
                 ("edges", ctypes.POINTER(ctypes.c_uint32)), ("bits", ctypes.c_uint32), ("eps", ctypes.c_float),
                 ("H", ctypes.c_uint32), ("lr", ctypes.c_float), ("stale_max", ctypes.c_uint32),
-                ("seed", ctypes.c_uint64), ("apply_mode", ctypes.c_uint32)]
+                ("seed", ctypes.c_uint64), ("apply_mode", ctypes.c_uint32), ("steps_law", ctypes.c_uint32)]
 
 
 def load_library():
@@ -56,6 +57,7 @@ def load_library():
         "swarm_local_steps": [vp, vp, u32],
         "swarm_sample_matching": [vp, vp, P(u32)],
         "swarm_sample_stale": [vp, vp],
+        "swarm_sample_steps": [vp, vp],
         "swarm_gossip_round": [vp, vp, u32, vp],
         "swarm_round_fused": [vp, vp, u32, vp],
         "swarm_interact": [vp, u32, u32],
@@ -123,14 +125,14 @@ class Swarm:
     """One simulated swarm: n node models of dimension d on one GPU."""
 
     def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None, stream=None,
-                 apply_mode=DEFERRED):
+                 apply_mode=DEFERRED, steps_law=CONSTANT):
         self._h = ctypes.c_void_p()
         self._lib = lib()
         edges = _host_u32(edges)
         self.n, self.d, self.bits, self.stale_max = int(n), int(d), int(bits), int(stale_max)
         cfg = _Config(self.n, self.d, edges.size // 2, edges.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
                       self.bits, float(eps), int(H), float(lr), self.stale_max, int(seed) & 0xFFFFFFFFFFFFFFFF,
-                      int(apply_mode))
+                      int(apply_mode), int(steps_law))
         self._keep = []          # borrowed objective tensors must outlive the handle
         rc = self._lib.swarm_init(ctypes.byref(cfg), _dev_ptr(x0, torch.float32), _stream_ptr(stream),
                                   ctypes.byref(self._h))
@@ -193,6 +195,11 @@ class Swarm:
     def round_fused(self, pairs=None, stale=None):
         """Local steps + gossip round in one pass (diagonal objective only)."""
         self._round(self._lib.swarm_round_fused, pairs, stale)
+
+    def sample_steps(self):
+        out = np.zeros(self.n, dtype=np.uint8)
+        self._check(self._lib.swarm_sample_steps(self._h, out.ctypes.data_as(ctypes.c_void_p)))
+        return out
 
     def gossip_round(self, pairs=None, stale=None):
         self._round(self._lib.swarm_gossip_round, pairs, stale)

@@ -16,7 +16,6 @@ struct FusedArgs {
     GossipArgs g;
     const float *A, *C;       // n x d objective data
     float sigma, lr;
-    uint32_t H;
 };
 
 template <int BITS, int STALE, bool INPLACE, bool NOISE, bool FULL>
@@ -51,11 +50,12 @@ __device__ __forceinline__ void fused_pair_tile(const FusedArgs &fa, const PairD
         seeniB = load_code<BITS>(src, lB / 4);
     }
 
-    // local steps of both nodes on this lane's four float4
-    const f4 wiA = diag_steps<NOISE>(xiA, aiA, ciA_, ni, lA / 4, fa.H, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wiB = diag_steps<NOISE>(xiB, aiB, ciB_, ni, lB / 4, fa.H, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wjA = diag_steps<NOISE>(xjA, ajA, cjA_, nj, lA / 4, fa.H, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wjB = diag_steps<NOISE>(xjB, ajB, cjB_, nj, lB / 4, fa.H, fa.lr, fa.sigma, a.seed, a.event);
+    // local steps of both nodes on this lane's four float4 (step counts travel in the descriptor)
+    const uint32_t Hi = pd.steps & 0xFFu, Hj = (pd.steps >> 8) & 0xFFu;
+    const f4 wiA = diag_steps<NOISE>(xiA, aiA, ciA_, ni, lA / 4, Hi, fa.lr, fa.sigma, a.seed, a.event);
+    const f4 wiB = diag_steps<NOISE>(xiB, aiB, ciB_, ni, lB / 4, Hi, fa.lr, fa.sigma, a.seed, a.event);
+    const f4 wjA = diag_steps<NOISE>(xjA, ajA, cjA_, nj, lA / 4, Hj, fa.lr, fa.sigma, a.seed, a.event);
+    const f4 wjB = diag_steps<NOISE>(xjB, ajB, cjB_, nj, lB / 4, Hj, fa.lr, fa.sigma, a.seed, a.event);
     // what is quantized / used as decoding key, and what is added to the average
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     const f4 qiA = INPLACE ? wiA : xiA, qiB = INPLACE ? wiB : xiB, qjA = INPLACE ? wjA : xjA, qjB = INPLACE ? wjB : xjB;
@@ -108,12 +108,13 @@ __global__ __launch_bounds__(WAVES * 64) void fused_singles_kernel(const FusedAr
     const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
     const bool inA = kA < a.d, inB = kB < a.d;
     const uint64_t lA = inA ? kA : a.d - 4, lB = inB ? kB : a.d - 4;
-    const uint32_t u = a.singles[blockIdx.y] & ~SINGLE_PENDING;
+    const uint32_t entry = a.singles[blockIdx.y];
+    const uint32_t u = entry & SINGLE_NODE_MASK, Hu = (entry >> 16) & 0xFFu;
     const uint64_t ou = (uint64_t)u * a.d;
     float *xu = a.X + ou;
     const f4 xA = ldg_nt(xu + lA), xB = ldg_nt(xu + lB);
-    const f4 wA = diag_steps<NOISE>(xA, ldg_nt(fa.A + ou + lA), ldg_nt(fa.C + ou + lA), u, lA / 4, fa.H, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wB = diag_steps<NOISE>(xB, ldg_nt(fa.A + ou + lB), ldg_nt(fa.C + ou + lB), u, lB / 4, fa.H, fa.lr, fa.sigma, a.seed, a.event);
+    const f4 wA = diag_steps<NOISE>(xA, ldg_nt(fa.A + ou + lA), ldg_nt(fa.C + ou + lA), u, lA / 4, Hu, fa.lr, fa.sigma, a.seed, a.event);
+    const f4 wB = diag_steps<NOISE>(xB, ldg_nt(fa.A + ou + lB), ldg_nt(fa.C + ou + lB), u, lB / 4, Hu, fa.lr, fa.sigma, a.seed, a.event);
     if constexpr (BITS > 0) {
         const LaneRandom r = row_random(a.seed, u, a.event, tile, lane);
         bool clampedA = false, clampedB = false;
@@ -157,7 +158,8 @@ static void launch_bits(const FusedArgs &fa, bool inplace, bool noise, int stale
 
 static hipError_t dispatch(const GossipArgs &g, const DiagObjective &o, uint32_t bits, bool inplace, uint32_t H,
                            float lr, int stale_mode, uint32_t npairs, uint32_t nsingles, bool singles, hipStream_t st) {
-    FusedArgs fa{g, o.a, o.c, o.sigma, lr, H};
+    (void)H;
+    FusedArgs fa{g, o.a, o.c, o.sigma, lr};
     const bool noise = o.sigma != 0.f;
     switch (bits) {
         case 2: launch_bits<2>(fa, inplace, noise, stale_mode, npairs, nsingles, singles, st); break;

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(WAVES * 64) void gossip_singles_kernel(const Gossip
     const bool inA = kA < a.d, inB = kB < a.d;
     if (tile * TILE >= a.d) return;
     const uint32_t entry = a.singles[blockIdx.y];
-    const uint32_t u = entry & ~SINGLE_PENDING;
+    const uint32_t u = entry & SINGLE_NODE_MASK;
     float *xu = a.X + (uint64_t)u * a.d;
     const float *wu = a.W + (uint64_t)u * a.d;
     const bool pend = entry & SINGLE_PENDING;

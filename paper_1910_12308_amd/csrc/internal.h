@@ -14,11 +14,14 @@ struct DeviceCounters {
 
 // One matched pair of a round.  flags: bits 0-7 = age (in rounds) of the code i reads from j,
 // bits 8-15 = age of the code j reads from i, bit 16 / 17 = W_i / W_j carries unapplied steps.
+// steps: bits 0-7 / 8-15 = number of local steps of i / j (used by the one-pass round).
 // 16 bytes so that a workgroup fetches its pair with one scalar load.
 struct PairDesc {
-    uint32_t ni, nj, flags, pad;
+    uint32_t ni, nj, flags, steps;
 };
-constexpr uint32_t SINGLE_PENDING = 0x80000000u;   // unmatched-node entry: node id | pending flag
+// Unmatched-node entry: node id (bits 0-15) | number of local steps (bits 16-23) | pending flag.
+constexpr uint32_t SINGLE_PENDING = 0x80000000u;
+constexpr uint32_t SINGLE_NODE_MASK = 0xFFFFu;
 
 struct GossipArgs {
     float *X;                 // n x d current models (updated in place)
@@ -52,9 +55,10 @@ hipError_t launch_quantize(const float *x, uint64_t d, float eps, float inv_eps,
 hipError_t launch_dequantize(const uint8_t *codes, const float *key, uint64_t d, float eps, float inv_eps,
                              uint32_t bits, float *out, hipStream_t st);
 
-// Local steps, diagonal quadratics: nodes == nullptr means rows 0..count-1.
+// Local steps, diagonal quadratics: nodes == nullptr means rows 0..count-1; steps (device, one
+// word per node id) overrides H when not null.
 hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const uint32_t *nodes,
-                             uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
+                             const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
                              uint32_t event, hipStream_t st);
 
 // Reductions.

@@ -12,7 +12,8 @@ namespace swarm {
 template <bool NOISE>
 __global__ __launch_bounds__(256) void local_diag_kernel(const float *__restrict__ X, float *__restrict__ W,
                                                          const float *__restrict__ A, const float *__restrict__ C,
-                                                         const uint32_t *__restrict__ nodes, uint64_t d, uint32_t H,
+                                                         const uint32_t *__restrict__ nodes,
+                                                         const uint32_t *__restrict__ steps, uint64_t d, uint32_t H,
                                                          float lr, float sigma, uint64_t seed, uint32_t event) {
     const uint64_t f = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     if (f * 4 >= d) return;
@@ -21,19 +22,19 @@ __global__ __launch_bounds__(256) void local_diag_kernel(const float *__restrict
     f4 w = __builtin_nontemporal_load((const f4 *)(X + off));
     const f4 a = __builtin_nontemporal_load((const f4 *)(A + off));
     const f4 c = __builtin_nontemporal_load((const f4 *)(C + off));
-    w = diag_steps<NOISE>(w, a, c, node, f, H, lr, sigma, seed, event);
+    w = diag_steps<NOISE>(w, a, c, node, f, steps ? steps[node] : H, lr, sigma, seed, event);
     __builtin_nontemporal_store(w, (f4 *)(W + off));
 }
 
 hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const uint32_t *nodes,
-                             uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
+                             const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
                              uint32_t event, hipStream_t st) {
     if (count == 0) return hipSuccess;
     const dim3 grid((unsigned)((d / 4 + 255) / 256), count, 1);
     if (sigma != 0.0f)
-        local_diag_kernel<true><<<grid, 256, 0, st>>>(X, W, a, c, nodes, d, H, lr, sigma, seed, event);
+        local_diag_kernel<true><<<grid, 256, 0, st>>>(X, W, a, c, nodes, steps, d, H, lr, sigma, seed, event);
     else
-        local_diag_kernel<false><<<grid, 256, 0, st>>>(X, W, a, c, nodes, d, H, lr, sigma, seed, event);
+        local_diag_kernel<false><<<grid, 256, 0, st>>>(X, W, a, c, nodes, steps, d, H, lr, sigma, seed, event);
     return hipGetLastError();
 }
 

@@ -15,12 +15,14 @@ constexpr int LB = 1024;
 
 __global__ __launch_bounds__(LB) void local_lsq_kernel(const float *__restrict__ base, float *__restrict__ W,
                                                        const float *__restrict__ A, const float *__restrict__ b,
-                                                       const uint32_t *__restrict__ nodes, uint64_t d, uint32_t H,
+                                                       const uint32_t *__restrict__ nodes,
+                                                       const uint32_t *__restrict__ steps, uint64_t d, uint32_t H,
                                                        float lr, uint32_t m_rows, uint32_t batch, uint64_t seed,
                                                        uint32_t event) {
     __shared__ uint32_t rows[LSQ_MAX_BATCH];
     __shared__ float resid[LSQ_MAX_BATCH];
     const uint32_t node = nodes ? nodes[blockIdx.x] : blockIdx.x;
+    if (steps) H = steps[node];
     const float *An = A + (uint64_t)node * m_rows * d;
     const float *bn = b + (uint64_t)node * m_rows;
     float *wrow = W + (uint64_t)node * d;
@@ -69,10 +71,10 @@ __global__ __launch_bounds__(LB) void local_lsq_kernel(const float *__restrict__
 }
 
 hipError_t launch_local_lsq(const float *base, float *W, const LsqObjective &o, const uint32_t *nodes,
-                            uint32_t count, uint64_t d, uint32_t H, float lr, uint64_t seed, uint32_t event,
+                            const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, uint64_t seed, uint32_t event,
                             hipStream_t st) {
     if (count == 0) return hipSuccess;
-    local_lsq_kernel<<<count, LB, 0, st>>>(base, W, o.A, o.b, nodes, d, H, lr, o.m_rows, o.batch, seed, event);
+    local_lsq_kernel<<<count, LB, 0, st>>>(base, W, o.A, o.b, nodes, steps, d, H, lr, o.m_rows, o.batch, seed, event);
     return hipGetLastError();
 }
 

@@ -33,7 +33,7 @@ hipError_t launch_fused_singles(const GossipArgs &g, const DiagObjective &o, uin
                                 float lr, uint32_t nsingles, hipStream_t st);
 
 hipError_t launch_local_lsq(const float *base, float *W, const LsqObjective &o, const uint32_t *nodes,
-                            uint32_t count, uint64_t d, uint32_t H, float lr, uint64_t seed, uint32_t event,
+                            const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, uint64_t seed, uint32_t event,
                             hipStream_t st);
 void free_lsq(LsqObjective &o);
 

@@ -9,7 +9,7 @@
 namespace swarm {
 
 enum : uint32_t { TAG_SR = 1, TAG_NOISE = 2, TAG_MATCH = 3, TAG_PICK = 4, TAG_BATCH = 5,
-                  TAG_STALE = 6, TAG_DATA = 7, TAG_LABEL = 8 };
+                  TAG_STALE = 6, TAG_DATA = 7, TAG_LABEL = 8, TAG_STEPS = 9 };
 
 struct Words4 { uint32_t w0, w1, w2, w3; };
 

@@ -39,7 +39,7 @@ struct swarm_ctx {
     float *X = nullptr, *W = nullptr, *Xhat = nullptr;
     uint8_t *ring = nullptr;
     uint32_t *edges_dev = nullptr, *prio_dev = nullptr, *counts_dev = nullptr, *nodes_dev = nullptr;
-    uint32_t *linf_dev = nullptr;
+    uint32_t *linf_dev = nullptr, *steps_dev = nullptr;   // steps_dev: local steps per node id (geometric law)
     uint8_t *desc_dev = nullptr;                 // PairDesc[n/2] | singles[n]
     DeviceCounters *counters_dev = nullptr;
     double *partials_dev = nullptr, *gamma_dev = nullptr;
@@ -141,17 +141,68 @@ swarm_status record_timing(swarm_t h, std::vector<hipEvent_t> &events, uint32_t 
         if (rc_ != SWARM_OK) return rc_;    \
     } while (0)
 
+// Stage a small host array of node ids in pinned memory and copy it to nodes_dev on the stream
+// (the caller's array may be reused as soon as the call returns).
+swarm_status upload_nodes(swarm_t h, const uint32_t *ids, uint32_t count) {
+    uint8_t *slot = nullptr;
+    unsigned slot_index = 0;
+    SWARM_TRY(acquire_desc(h, &slot, &slot_index));
+    std::memcpy(slot, ids, sizeof(uint32_t) * count);
+    SWARM_HIP(h, hipMemcpyAsync(h->nodes_dev, slot, sizeof(uint32_t) * count, hipMemcpyHostToDevice, h->stream));
+    SWARM_HIP(h, hipEventRecord(h->desc_free[slot_index], h->stream));
+    return SWARM_OK;
+}
+
+// Number of local steps of `node` for interaction `event`: H, or a geometric draw of mean H
+// (1 + failures before the first word below floor(2^32 / H), words taken in order from the
+// node's STEPS stream), capped at 255.
+uint32_t draw_steps(const swarm_config &c, uint32_t node, uint32_t event) {
+    if (c.steps_law == SWARM_STEPS_CONSTANT) return c.H;
+    const uint32_t threshold = (uint32_t)((1ull << 32) / c.H);   // H = 1 -> 2^32 wraps to 0: handled below
+    if (c.H == 1) return 1;
+    uint32_t k = 1;
+    for (uint32_t call = 0; k < 255; ++call) {
+        const Words4 w = stream(c.seed, TAG_STEPS, 0, node, event, call);
+        const uint32_t words[4] = {w.w0, w.w1, w.w2, w.w3};
+        for (int t = 0; t < 4 && k < 255; ++t) {
+            if (words[t] < threshold) return k;
+            ++k;
+        }
+    }
+    return k;
+}
+
+// Per-node step counts of this event on the device (one word per node id), or null when constant.
+swarm_status upload_steps(swarm_t h, uint32_t event, const uint32_t **steps_dev) {
+    *steps_dev = nullptr;
+    if (h->cfg.steps_law == SWARM_STEPS_CONSTANT) return SWARM_OK;
+    uint8_t *slot = nullptr;
+    unsigned slot_index = 0;
+    SWARM_TRY(acquire_desc(h, &slot, &slot_index));
+    uint32_t *dst = (uint32_t *)slot;
+    for (uint32_t i = 0; i < h->cfg.n; ++i) dst[i] = draw_steps(h->cfg, i, event);
+    SWARM_HIP(h, hipMemcpyAsync(h->steps_dev, slot, sizeof(uint32_t) * h->cfg.n, hipMemcpyHostToDevice, h->stream));
+    SWARM_HIP(h, hipEventRecord(h->desc_free[slot_index], h->stream));
+    *steps_dev = h->steps_dev;
+    return SWARM_OK;
+}
+
 swarm_status run_local_steps(swarm_t h, const float *base, const uint32_t *nodes_dev, uint32_t count,
-                             uint32_t single_node, uint32_t event) {
+                             uint32_t event) {
     const swarm_config &c = h->cfg;
     hipError_t e = hipSuccess;
+    const uint32_t *steps = nullptr;
+    if (h->kind == OBJ_MLP && c.steps_law != SWARM_STEPS_CONSTANT)
+        return fail(h, SWARM_ESTATE, "the MLP objective takes a constant number of local steps");
+    SWARM_TRY(upload_steps(h, event, &steps));
     switch (h->kind) {
         case OBJ_DIAG:
-            e = launch_local_diag(base, h->W, h->diag.a, h->diag.c, nodes_dev, count, c.d, c.H, c.lr,
+            e = launch_local_diag(base, h->W, h->diag.a, h->diag.c, nodes_dev, steps, count, c.d, c.H, c.lr,
                                   h->diag.sigma, c.seed, event, h->stream);
             break;
         case OBJ_LSQ:
-            e = launch_local_lsq(base, h->W, h->lsq, nodes_dev, count, c.d, c.H, c.lr, c.seed, event, h->stream);
+            e = launch_local_lsq(base, h->W, h->lsq, nodes_dev, steps, count, c.d, c.H, c.lr, c.seed, event,
+                                 h->stream);
             break;
         case OBJ_MLP:
             e = launch_local_mlp(base, h->W, h->mlp, nodes_dev, count, c.n, c.d, c.H, c.lr, c.seed, event,
@@ -160,7 +211,6 @@ swarm_status run_local_steps(swarm_t h, const float *base, const uint32_t *nodes
         default:
             return fail(h, SWARM_ESTATE, "no objective set");
     }
-    (void)single_node;
     SWARM_HIP(h, e);
     return SWARM_OK;
 }
@@ -183,6 +233,10 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     if (cfg->stale_max > 254) return fail(nullptr, SWARM_EINVAL, "stale_max exceeds 254");
     if (cfg->H > 255) return fail(nullptr, SWARM_EINVAL, "H exceeds 255");
     if (cfg->apply_mode > SWARM_APPLY_INPLACE) return fail(nullptr, SWARM_EINVAL, "unknown apply mode");
+    if (cfg->steps_law > SWARM_STEPS_GEOMETRIC) return fail(nullptr, SWARM_EINVAL, "unknown law of the local steps");
+    if (cfg->steps_law == SWARM_STEPS_GEOMETRIC && cfg->H == 0)
+        return fail(nullptr, SWARM_EINVAL, "a geometric number of local steps needs mean H >= 1");
+    if (cfg->n > SINGLE_NODE_MASK) return fail(nullptr, SWARM_EINVAL, "n exceeds 65535");
     if (cfg->n_edges == 0 || !cfg->edges) return fail(nullptr, SWARM_EINVAL, "graph has no edges");
     if (cfg->n_edges > MATCHING_MAX_EDGES) return fail(nullptr, SWARM_EINVAL, "too many edges");
 
@@ -235,6 +289,7 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         SWARM_HIP(h, hipMalloc((void **)&h->counts_dev, sizeof(uint32_t) * 2));
         SWARM_HIP(h, hipMalloc((void **)&h->nodes_dev, sizeof(uint32_t) * n));
         SWARM_HIP(h, hipMalloc((void **)&h->linf_dev, sizeof(uint32_t) * (n / 2)));
+        SWARM_HIP(h, hipMalloc((void **)&h->steps_dev, sizeof(uint32_t) * n));
         SWARM_HIP(h, hipMalloc((void **)&h->desc_dev, h->desc_bytes));
         SWARM_HIP(h, hipMalloc((void **)&h->mpairs_dev, sizeof(uint32_t) * 2 * (n / 2)));
         SWARM_HIP(h, hipMalloc((void **)&h->msingles_dev, sizeof(uint32_t) * n));
@@ -284,7 +339,7 @@ swarm_status swarm_destroy(swarm_t h) {
     if (h->W == h->X) h->W = nullptr;
     void *dev[] = {h->X, h->W, h->Xhat, h->ring, h->edges_dev, h->prio_dev, h->counts_dev, h->nodes_dev,
                    h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev, h->mpairs_dev,
-                   h->msingles_dev};
+                   h->msingles_dev, h->steps_dev};
     for (void *p : dev) if (p) (void)hipFree(p);
     for (int s = 0; s < DESC_SLOTS; ++s) {
         if (h->desc_host[s]) (void)hipHostFree(h->desc_host[s]);
@@ -352,13 +407,13 @@ swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count)
             if (nodes[k] >= n || seen[nodes[k]]) return fail(h, SWARM_EINVAL, "node id out of range or repeated");
             seen[nodes[k]] = 1;
         }
-        SWARM_HIP(h, hipMemcpyAsync(h->nodes_dev, nodes, sizeof(uint32_t) * count, hipMemcpyHostToDevice, h->stream));
+        SWARM_TRY(upload_nodes(h, nodes, count));
         nodes_dev = h->nodes_dev;
     } else {
         count = n;
     }
     SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 0));
-    SWARM_TRY(run_local_steps(h, h->X, nodes_dev, count, 0, (uint32_t)h->round));
+    SWARM_TRY(run_local_steps(h, h->X, nodes_dev, count, (uint32_t)h->round));
     SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 1));
     h->timed_local += 1;
     if (h->cfg.apply_mode == SWARM_APPLY_INPLACE) return SWARM_OK;   // already applied: nothing is pending
@@ -415,6 +470,13 @@ swarm_status swarm_sample_stale(swarm_t h, uint8_t *stale_host) {
                                         h->cfg.stale_max + 1);
         stale_host[i] = (uint8_t)std::min<uint64_t>(s, h->round);
     }
+    return SWARM_OK;
+}
+
+swarm_status swarm_sample_steps(swarm_t h, uint8_t *steps_host) {
+    if (!h) return SWARM_EINVAL;
+    if (!steps_host) return fail(h, SWARM_EINVAL, "null output");
+    for (uint32_t i = 0; i < h->cfg.n; ++i) steps_host[i] = (uint8_t)draw_steps(h->cfg, i, (uint32_t)h->round);
     return SWARM_OK;
 }
 
@@ -479,7 +541,8 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     std::vector<PairDesc> groups[3];          // 0: fresh/fresh, 1: stale/stale, 2: first stale only
     auto describe = [&](uint32_t u, uint32_t v) {
         return PairDesc{u, v, (uint32_t)stale[u] | ((uint32_t)stale[v] << 8) |
-                                  (h->pending[u] ? 1u << 16 : 0u) | (h->pending[v] ? 1u << 17 : 0u), 0u};
+                                  (h->pending[u] ? 1u << 16 : 0u) | (h->pending[v] ? 1u << 17 : 0u),
+                        fused ? draw_steps(c, u, (uint32_t)h->round) | (draw_steps(c, v, (uint32_t)h->round) << 8) : 0u};
     };
     for (uint32_t p = 0; p < npairs; ++p) {
         const uint32_t u = pairs[2 * p], v = pairs[2 * p + 1];
@@ -501,7 +564,9 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     for (int gidx = 0; gidx < 3; ++gidx)
         for (const PairDesc &desc : groups[gidx]) *pd++ = desc;
     uint32_t *sg = (uint32_t *)(slot + h->off_singles);
-    for (uint32_t k = 0; k < nsingles; ++k) sg[k] = singles[k] | (h->pending[singles[k]] ? SINGLE_PENDING : 0u);
+    for (uint32_t k = 0; k < nsingles; ++k)
+        sg[k] = singles[k] | (fused ? draw_steps(c, singles[k], (uint32_t)h->round) << 16 : 0u) |
+                (h->pending[singles[k]] ? SINGLE_PENDING : 0u);
     SWARM_HIP(h, hipMemcpyAsync(h->desc_dev, slot, h->desc_bytes, hipMemcpyHostToDevice, h->stream));
     SWARM_HIP(h, hipEventRecord(h->desc_free[slot_index], h->stream));
 
@@ -562,9 +627,9 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     }
     bool has_delta = h->pending[i] != 0;
     if (c.H > 0 && h->kind != OBJ_NONE) {
-        SWARM_HIP(h, hipMemcpyAsync(h->nodes_dev, &i, sizeof(uint32_t), hipMemcpyHostToDevice, h->stream));
+        SWARM_TRY(upload_nodes(h, &i, 1));
         SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 0));
-        SWARM_TRY(run_local_steps(h, h->Xhat, h->nodes_dev, 1, i, (uint32_t)h->interactions));
+        SWARM_TRY(run_local_steps(h, h->Xhat, h->nodes_dev, 1, (uint32_t)h->interactions));
         SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 1));
         h->timed_local += 1;
         has_delta = true;
@@ -691,8 +756,7 @@ swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npa
         return fail(h, SWARM_EINVAL, "pair list out of range");
     for (uint32_t k = 0; k < 2 * npairs; ++k)
         if (pairs_host[k] >= h->cfg.n) return fail(h, SWARM_EINVAL, "pair endpoint out of range");
-    SWARM_HIP(h, hipMemcpyAsync(h->nodes_dev, pairs_host, sizeof(uint32_t) * 2 * npairs, hipMemcpyHostToDevice,
-                                h->stream));
+    SWARM_TRY(upload_nodes(h, pairs_host, 2 * npairs));
     SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * npairs, h->stream));
     SWARM_HIP(h, launch_pair_linf(h->X, h->cfg.d, h->nodes_dev, npairs, h->linf_dev, h->stream));
     SWARM_HIP(h, hipMemcpyAsync(linf_host, h->linf_dev, sizeof(uint32_t) * npairs, hipMemcpyDeviceToHost, h->stream));

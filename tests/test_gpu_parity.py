@@ -435,3 +435,52 @@ def test_fused_round_equals_two_calls_and_oracle(gpu, inplace, bits, S):
         with pytest.raises(gpu.SwarmError) as err:
             fused.round_fused(None)                        # steps already pending
         assert err.value.status == gpu.ESTATE
+
+
+# ------------------------------------------------------------------ geometric number of local steps
+def test_geometric_local_steps(gpu):
+    """H_i drawn per node and interaction: identical draws on both sides, used by the stand-alone
+    local steps, by the one-pass round and by Algorithm 1's initiator."""
+    n, d, H, lr, bits, eps = 12, D_RAGGED, 3, 0.05, 8, 2.0 ** -4
+    edges = wl.random_regular_graph(n, 3, 2)
+    a, cc = wl.diag_quadratic_data(n, d, 13)
+    ad, cd = torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda()
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, 0, seed=23, geometric=True)
+    f, _ = make_both(gpu, n, d, edges, bits, eps, H, lr, 0, seed=23, geometric=True)
+    c.objective = DiagQuadratic(a, cc, 0.02)
+    g.set_objective_diag(ad, cd, 0.02)
+    f.set_objective_diag(ad, cd, 0.02)
+    gen = np.random.Generator(np.random.PCG64(23))
+    c.X[:] = models(gen, n, d, 0.5)
+    seen = set()
+    for r in range(4):
+        g.write_models(gpu.COMM, c.X)
+        f.write_models(gpu.COMM, c.X)
+        steps = g.sample_steps()
+        assert np.array_equal(steps, c.sample_steps().astype(np.uint8))
+        seen |= set(steps.tolist())
+        pairs = c.sample_matching()
+        c.local_steps()
+        g.local_steps()
+        assert_close(g.read_models(gpu.LIVE), c.W, TOL_ELEMENTWISE, f"W, round {r}")
+        c.gossip_round(pairs)
+        g.gossip_round(None)
+        f.round_fused(None)
+        assert np.array_equal(f.read_models(gpu.COMM), g.read_models(gpu.COMM))
+        assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"X, round {r}")
+    assert len(seen) > 1
+    # sequential model: the initiator's H_i is drawn for the interaction number
+    g2, c2 = make_both(gpu, n, d, edges, bits, eps, H, lr, 0, seed=29, geometric=True)
+    c2.objective = DiagQuadratic(a, cc, 0.0)
+    g2.set_objective_diag(ad, cd, 0.0)
+    c2.X[:] = models(gen, n, d, 0.5)
+    c2.Xhat[:] = c2.X
+    g2.write_models(gpu.COMM, c2.X)
+    g2.write_models(gpu.SNAP, c2.Xhat)
+    for t in range(6):
+        pair = c2.sample_pair()
+        c2.interact(*pair)
+        g2.interact(*pair)
+        g2.write_models(gpu.COMM, c2.X)
+        g2.write_models(gpu.SNAP, c2.Xhat)
+        assert_close(g2.read_models(gpu.LIVE, pair[0], 1), c2.W[pair[0]:pair[0] + 1], TOL_ELEMENTWISE, f"W_i, t={t}")

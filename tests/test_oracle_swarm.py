@@ -407,3 +407,39 @@ def test_oracle_inplace_mode_is_average_of_updated_models():
     assert np.allclose(o.X, w, atol=1e-13) and not o.pending.any()
     o.gossip_round([(0, 1)])
     assert np.allclose(o.X[0], (w[0] + w[1]) / 2) and np.array_equal(o.X[0], o.X[1])
+
+
+def test_geometric_steps_have_the_stated_moments():
+    """Geometric H_i of mean H: E[H_i] = H and E[H_i^2] = 2H^2 - H (appendix, properties of the
+    local steps); draws are >= 1, fresh per node and per interaction."""
+    for H in (2, 3, 5):
+        o = SwarmOracle(64, 8, wl.complete_graph(64), 0, 0.0, H, 0.1, 0, 5, steps_law="geometric")
+        draws = []
+        for r in range(150):
+            o.round = r
+            draws.append(o.sample_steps())
+        k = np.concatenate(draws).astype(np.float64)
+        assert k.min() >= 1
+        se1 = math.sqrt((H * H - H) / k.size)
+        assert abs(k.mean() - H) < 5 * se1 + 1e-3
+        assert (k ** 2).mean() == pytest.approx(2 * H * H - H, rel=0.08)
+        assert not np.array_equal(draws[0], draws[1])
+    one = SwarmOracle(4, 8, wl.complete_graph(4), 0, 0.0, 1, 0.1, 0, 5, steps_law="geometric")
+    assert one.sample_steps().tolist() == [1, 1, 1, 1]
+    const = SwarmOracle(4, 8, wl.complete_graph(4), 0, 0.0, 3, 0.1, 0, 5)
+    assert const.sample_steps().tolist() == [3, 3, 3, 3]
+
+
+def test_geometric_steps_are_used_by_the_local_steps():
+    n, d, H, lr = 6, 16, 3, 0.1
+    a, cc = wl.diag_quadratic_data(n, d, 2)
+    o = SwarmOracle(n, d, wl.complete_graph(n), 0, 0.0, H, lr, 0, 9, state_dtype=np.float64, steps_law="geometric")
+    o.objective = DiagQuadratic(a, cc, 0.0)
+    X = np.random.Generator(np.random.PCG64(1)).standard_normal((n, d))
+    o.X[:] = X
+    o.local_steps()
+    steps = o.sample_steps()
+    assert len(set(steps.tolist())) > 1
+    for i in range(n):
+        closed = cc[i] + (1 - np.float64(np.float32(lr)) * a[i].astype(np.float64)) ** int(steps[i]) * (X[i] - cc[i])
+        assert np.allclose(o.W[i], closed, atol=1e-13)
