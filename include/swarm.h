@@ -49,6 +49,15 @@ typedef enum {
  * updated models; one matrix, no pending update (W is an alias of X). */
 enum { SWARM_APPLY_DEFERRED = 0, SWARM_APPLY_INPLACE = 1 };
 
+/* How the lattice scale eps is chosen.  FIXED: cfg.eps for every exchange (Corollary 2.1 fixes
+ * eps up front).  PAIR_LINF: the case where the writer knows its distance to the decoding key
+ * (proof of Corollary 2.1): before the exchange a reduction computes m = max_k |X_i[k] - X_j[k]|
+ * for every matched pair, and the pair uses eps_ij = the smallest power of two >= m / (2^(b-1) - 3)
+ * (at least 2^-100), which puts the pair inside the decoding radius, so no decode can fail.
+ * Needs bits >= 4, stale_max = 0 and swarm_gossip_round (not the one-pass round or Algorithm 1);
+ * unmatched nodes publish no code. */
+enum { SWARM_SCALE_FIXED = 0, SWARM_SCALE_PAIR_LINF = 1 };
+
 /* Number of local steps per interaction.  CONSTANT: H for every node (the paper's experiments).
  * GEOMETRIC: each node draws H_i >= 1 afresh for every interaction from a geometric law of mean H
  * (Section 3 "Sequential model": approximates activation by independent Poisson clocks), capped
@@ -77,6 +86,7 @@ typedef struct {
     uint32_t apply_mode;    /* SWARM_APPLY_DEFERRED (default) or SWARM_APPLY_INPLACE           */
     uint32_t steps_law;     /* SWARM_STEPS_CONSTANT (default) or SWARM_STEPS_GEOMETRIC (H >= 1;
                                not available with the MLP objective)                           */
+    uint32_t scale_policy;  /* SWARM_SCALE_FIXED (default) or SWARM_SCALE_PAIR_LINF            */
 } swarm_config;
 
 /* Create a handle.  x0_dev: d floats (device) copied into every node's model, or NULL

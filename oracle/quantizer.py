@@ -104,3 +104,12 @@ def dequantize(buf, key, eps, bits):
     key = np.asarray(key, dtype=F32)
     z = decode(unpack(buf, bits, key.size), key, eps, bits)
     return z.astype(np.float64) * float(F32(eps))
+
+
+def pair_scale(m, bits):
+    """Lattice scale for a pair at max-norm distance m: the smallest power of two that is
+    >= m / (2^(b-1) - 3) (and >= 2^-100), so the pair sits inside the decoding radius
+    (2^(b-1) - 5/2) eps -- the case of Corollary 2.1's proof where the writer knows the distance."""
+    q = max(F32(m), F32(2.0 ** -100)) / F32((1 << (bits - 1)) - 3)
+    f, k = np.frexp(F32(q))                    # q = f 2^k, f in [1/2, 1)
+    return float(np.ldexp(F32(1.0), int(k) - 1 if f == 0.5 else int(k)))

@@ -16,7 +16,7 @@ from . import rng
 
 class SwarmOracle:
     def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None,
-                 k0=0, k1=None, state_dtype=np.float32, apply_mode="deferred", steps_law="constant"):
+                 k0=0, k1=None, state_dtype=np.float32, apply_mode="deferred", steps_law="constant", scale_policy="fixed"):
         self.n, self.d = int(n), int(d)
         self.k0 = int(k0)
         self.k1 = self.d if k1 is None else int(k1)
@@ -34,6 +34,11 @@ class SwarmOracle:
         # paper's stand-in for activation by Poisson clocks (Section 3, "Sequential model").
         assert steps_law in ("constant", "geometric") and (steps_law == "constant" or self.H >= 1)
         self.steps_law = steps_law
+        # "fixed": one eps for every exchange; "pair_linf": each matched pair uses the smallest power of
+        # two that puts it inside the decoding radius (the writer knows its distance to the key).
+        assert scale_policy in ("fixed", "pair_linf")
+        assert scale_policy == "fixed" or (self.bits >= 4 and self.S == 0)
+        self.scale_policy = scale_policy
         self.dtype = state_dtype
         dw = self.k1 - self.k0
         self.X = np.zeros((self.n, dw), dtype=state_dtype)
@@ -129,17 +134,19 @@ class SwarmOracle:
         return np.minimum(rng.scaled_index(w0, self.S + 1), self.round).astype(np.int64)
 
     # ---- quantized exchange -------------------------------------------------------------
-    def _lattice_point(self, i, event):
+    def _lattice_point(self, i, event, eps=None):
+        eps = self.eps if eps is None else eps
         r16 = rng.sr_halves(self.seed, i, event, self.k0, self.k1)
-        z = qz.stochastic_round(self.X[i], self.eps, r16)
-        self.range_clamped |= bool(qz.lattice_coordinate(self.X[i], self.eps)[1].any())
+        z = qz.stochastic_round(self.X[i], eps, r16)
+        self.range_clamped |= bool(qz.lattice_coordinate(self.X[i], eps)[1].any())
         return z
 
-    def _read(self, reader, sender, slot, z_true=None):
+    def _read(self, reader, sender, slot, z_true=None, eps=None):
         """reader decodes the sender's published code against its own model."""
+        eps = self.eps if eps is None else eps
         c = qz.unpack(self.ring[slot][sender], self.bits, self.k1 - self.k0)
-        z = qz.decode(c, self.X[reader], self.eps, self.bits)
-        self.range_clamped |= bool(qz.lattice_coordinate(self.X[reader], self.eps)[1].any())
+        z = qz.decode(c, self.X[reader], eps, self.bits)
+        self.range_clamped |= bool(qz.lattice_coordinate(self.X[reader], eps)[1].any())
         self.bits_communicated += self.d * self.bits
         if z_true is not None:
             self.decode_failures += int((z != z_true).sum())
@@ -162,6 +169,18 @@ class SwarmOracle:
                 new[i] = avg + self._delta(i, self.X[i])
                 new[j] = avg + self._delta(j, self.X[j])
                 self.bits_communicated += 2 * self.d * 32
+        elif self.scale_policy == "pair_linf":               # each pair at its own scale; full rows only
+            assert self.k0 == 0 and self.k1 == self.d
+            for i, j in pairs:
+                m = np.abs(self.X[i].astype(np.float32) - self.X[j].astype(np.float32)).max()
+                eps = qz.pair_scale(m, self.bits)
+                zi, zj = self._lattice_point(i, r, eps), self._lattice_point(j, r, eps)
+                self.ring[0][i] = qz.pack(qz.code(zi, self.bits), self.bits)
+                self.ring[0][j] = qz.pack(qz.code(zj, self.bits), self.bits)
+                zj_seen = self._read(i, j, 0, zj, eps)
+                zi_seen = self._read(j, i, 0, zi, eps)
+                new[i] = (zi + zj_seen) * (0.5 * eps) + self._delta(i, self.X[i])
+                new[j] = (zj + zi_seen) * (0.5 * eps) + self._delta(j, self.X[j])
         else:
             slot = r % (self.S + 1)
             z = {}

@@ -18,6 +18,7 @@ OK, EINVAL, ENOMEM, EDEVICE, ESTATE, ERANGE = range(6)
 COMM, LIVE, SNAP = 0, 1, 2
 DEFERRED, INPLACE = 0, 1
 CONSTANT, GEOMETRIC = 0, 1
+SCALE_FIXED, SCALE_PAIR_LINF = 0, 1
 _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_ESTATE", 5: "SWARM_ERANGE"}
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
@@ -38,7 +39,8 @@ class _Config(ctypes.Structure):
     _fields_ = [("n", ctypes.c_uint32), ("d", ctypes.c_uint64), ("n_edges", ctypes.c_uint32),
                 ("edges", ctypes.POINTER(ctypes.c_uint32)), ("bits", ctypes.c_uint32), ("eps", ctypes.c_float),
                 ("H", ctypes.c_uint32), ("lr", ctypes.c_float), ("stale_max", ctypes.c_uint32),
-                ("seed", ctypes.c_uint64), ("apply_mode", ctypes.c_uint32), ("steps_law", ctypes.c_uint32)]
+                ("seed", ctypes.c_uint64), ("apply_mode", ctypes.c_uint32), ("steps_law", ctypes.c_uint32),
+                ("scale_policy", ctypes.c_uint32)]
 
 
 def load_library():
@@ -125,14 +127,14 @@ class Swarm:
     """One simulated swarm: n node models of dimension d on one GPU."""
 
     def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None, stream=None,
-                 apply_mode=DEFERRED, steps_law=CONSTANT):
+                 apply_mode=DEFERRED, steps_law=CONSTANT, scale_policy=SCALE_FIXED):
         self._h = ctypes.c_void_p()
         self._lib = lib()
         edges = _host_u32(edges)
         self.n, self.d, self.bits, self.stale_max = int(n), int(d), int(bits), int(stale_max)
         cfg = _Config(self.n, self.d, edges.size // 2, edges.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
                       self.bits, float(eps), int(H), float(lr), self.stale_max, int(seed) & 0xFFFFFFFFFFFFFFFF,
-                      int(apply_mode), int(steps_law))
+                      int(apply_mode), int(steps_law), int(scale_policy))
         self._keep = []          # borrowed objective tensors must outlive the handle
         rc = self._lib.swarm_init(ctypes.byref(cfg), _dev_ptr(x0, torch.float32), _stream_ptr(stream),
                                   ctypes.byref(self._h))

@@ -18,7 +18,8 @@ namespace swarm {
 // guard and every load is issued before the first use; the ragged last tile of a row takes the
 // guarded variant.
 template <int BITS, int DELTA, int STALE, bool FULL>
-__device__ __forceinline__ void gossip_pair_tile(const GossipArgs &a, const PairDesc pd, uint64_t tile, uint32_t lane) {
+__device__ __forceinline__ void gossip_pair_tile(const GossipArgs &a, const PairDesc pd, uint64_t tile, uint32_t lane,
+                                                 float eps, float inv_eps) {
     const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
     const bool inA = FULL || kA < a.d, inB = FULL || kB < a.d;
     // Lanes past the end of the row load the row's last float4 instead (never stored).
@@ -62,19 +63,19 @@ __device__ __forceinline__ void gossip_pair_tile(const GossipArgs &a, const Pair
     bool clampedA = false, clampedB = false;     // counted per half: lanes past the row end hold a duplicate
     int failsA = 0, failsB = 0;
     int ziA[4], ziB[4], zjA[4], zjB[4];
-    const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, a.inv_eps, ziA, clampedA);
-    const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, a.inv_eps, ziB, clampedB);
-    const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, a.inv_eps, zjA, clampedA);
-    const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, a.inv_eps, zjB, clampedB);
-    const float half_eps = 0.5f * a.eps;
+    const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, inv_eps, ziA, clampedA);
+    const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, inv_eps, ziB, clampedB);
+    const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, inv_eps, zjA, clampedA);
+    const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, inv_eps, zjB, clampedB);
+    const float half_eps = 0.5f * eps;
 
-    const f4 oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, xiA, di ? wiA - xiA : zero, a.inv_eps, half_eps,
+    const f4 oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, xiA, di ? wiA - xiA : zero, inv_eps, half_eps,
                                   stale_i ? nullptr : zjA, failsA, clampedA);
-    const f4 oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, xiB, di ? wiB - xiB : zero, a.inv_eps, half_eps,
+    const f4 oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, xiB, di ? wiB - xiB : zero, inv_eps, half_eps,
                                   stale_i ? nullptr : zjB, failsB, clampedB);
-    const f4 ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, xjA, dj ? wjA - xjA : zero, a.inv_eps, half_eps,
+    const f4 ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, xjA, dj ? wjA - xjA : zero, inv_eps, half_eps,
                                   stale_j ? nullptr : ziA, failsA, clampedA);
-    const f4 ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, xjB, dj ? wjB - xjB : zero, a.inv_eps, half_eps,
+    const f4 ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, xjB, dj ? wjB - xjB : zero, inv_eps, half_eps,
                                   stale_j ? nullptr : ziB, failsB, clampedB);
     if (inA) {
         stg_nt(xi + kA, oiA); stg_nt(xj + kA, ojA);
@@ -93,8 +94,13 @@ __global__ __launch_bounds__(WAVES * 64) void gossip_pairs_kernel(const GossipAr
     const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
     if (tile * TILE >= a.d) return;
     const PairDesc pd = a.pairs[blockIdx.y];                       // uniform: one scalar load
-    if (tile * TILE + TILE <= a.d) gossip_pair_tile<BITS, DELTA, STALE, true>(a, pd, tile, lane);
-    else gossip_pair_tile<BITS, DELTA, STALE, false>(a, pd, tile, lane);
+    float eps = a.eps, inv_eps = a.inv_eps;
+    if (a.pair_linf) {                                             // the pair's own scale from its distance
+        eps = pair_scale(__uint_as_float(a.pair_linf[blockIdx.y]), BITS);
+        inv_eps = 1.0f / eps;
+    }
+    if (tile * TILE + TILE <= a.d) gossip_pair_tile<BITS, DELTA, STALE, true>(a, pd, tile, lane, eps, inv_eps);
+    else gossip_pair_tile<BITS, DELTA, STALE, false>(a, pd, tile, lane, eps, inv_eps);
 }
 
 // Q = identity (Corollary 4.2): plain pairwise averaging plus the pending update.

@@ -30,6 +30,8 @@ struct GossipArgs {
     uint8_t *ring;            // (S+1) x n x row_bytes packed codes
     const PairDesc *pairs;    // device: one per matched pair
     const uint32_t *singles;  // device: unmatched nodes (node id | SINGLE_PENDING)
+    const uint32_t *pair_linf; // device: bits of max_k |X_i - X_j| per pair (same order as pairs), or
+                              // null when the lattice scale is fixed
     DeviceCounters *counters;
     uint64_t d;
     uint64_t row_bytes;       // d * bits / 8
@@ -67,6 +69,9 @@ hipError_t launch_potential(const float *X, uint32_t n, uint64_t d, float *mu, d
 uint32_t potential_partials(uint64_t d);
 hipError_t launch_pair_linf(const float *X, uint64_t d, const uint32_t *pairs, uint32_t npairs,
                             uint32_t *linf_bits, hipStream_t st);
+// Same reduction over pair descriptors; linf_bits must be zero on entry.
+hipError_t launch_pair_linf_desc(const float *X, uint64_t d, const PairDesc *pairs, uint32_t npairs,
+                                 uint32_t *linf_bits, hipStream_t st);
 
 // Streaming copy of nbytes (multiple of 16, below 2^36) from src to dst.
 hipError_t launch_stream_copy(const void *src, void *dst, uint64_t nbytes, hipStream_t st);

@@ -38,4 +38,13 @@ __device__ __forceinline__ int decode_near(uint32_t c, int k) {
     return k + delta;
 }
 
+// Lattice scale for a pair at distance m (max norm): the smallest power of two >= m / (2^(b-1) - 3),
+// at least 2^-100.  frexp / ldexp and one correctly rounded division: exact on both sides.
+__device__ __forceinline__ float pair_scale(float m, int bits) {
+    const float q = fmaxf(m, 0x1p-100f) / (float)((1 << (bits - 1)) - 3);
+    int k;
+    const float f = frexpf(q, &k);                 // q = f 2^k, f in [1/2, 1)
+    return ldexpf(1.0f, f == 0.5f ? k - 1 : k);    // 2^ceil(log2 q)
+}
+
 }  // namespace swarm

@@ -62,11 +62,13 @@ __global__ __launch_bounds__(RB) void sum_partials_kernel(const double *__restri
 
 // Non-negative floats order like their bit patterns, so atomicMax on the bits is exact
 // and order-independent.
+template <bool DESC>
 __global__ __launch_bounds__(RB) void pair_linf_kernel(const float *__restrict__ X, uint64_t d,
                                                        const uint32_t *__restrict__ pairs,
                                                        uint32_t *__restrict__ linf_bits) {
     __shared__ float lds[RB / 64];
-    const uint32_t ni = pairs[2 * blockIdx.y], nj = pairs[2 * blockIdx.y + 1];
+    // DESC: pairs are 16-byte descriptors (node ids in the first two words), else packed id pairs
+    const uint32_t ni = pairs[(DESC ? 4 : 2) * blockIdx.y], nj = pairs[(DESC ? 4 : 2) * blockIdx.y + 1];
     const uint64_t f = (uint64_t)blockIdx.x * RB + threadIdx.x;
     float m = 0.f;
     if (f * 4 < d) {
@@ -95,7 +97,15 @@ hipError_t launch_pair_linf(const float *X, uint64_t d, const uint32_t *pairs, u
                             uint32_t *linf_bits, hipStream_t st) {
     if (npairs == 0) return hipSuccess;
     const dim3 grid((unsigned)((d / 4 + RB - 1) / RB), npairs, 1);
-    pair_linf_kernel<<<grid, RB, 0, st>>>(X, d, pairs, linf_bits);
+    pair_linf_kernel<false><<<grid, RB, 0, st>>>(X, d, pairs, linf_bits);
+    return hipGetLastError();
+}
+
+hipError_t launch_pair_linf_desc(const float *X, uint64_t d, const PairDesc *pairs, uint32_t npairs,
+                                 uint32_t *linf_bits, hipStream_t st) {
+    if (npairs == 0) return hipSuccess;
+    const dim3 grid((unsigned)((d / 4 + RB - 1) / RB), npairs, 1);
+    pair_linf_kernel<true><<<grid, RB, 0, st>>>(X, d, (const uint32_t *)pairs, linf_bits);
     return hipGetLastError();
 }
 

@@ -236,6 +236,9 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     if (cfg->steps_law > SWARM_STEPS_GEOMETRIC) return fail(nullptr, SWARM_EINVAL, "unknown law of the local steps");
     if (cfg->steps_law == SWARM_STEPS_GEOMETRIC && cfg->H == 0)
         return fail(nullptr, SWARM_EINVAL, "a geometric number of local steps needs mean H >= 1");
+    if (cfg->scale_policy > SWARM_SCALE_PAIR_LINF) return fail(nullptr, SWARM_EINVAL, "unknown scale policy");
+    if (cfg->scale_policy == SWARM_SCALE_PAIR_LINF && (cfg->bits < 4 || cfg->stale_max != 0))
+        return fail(nullptr, SWARM_EINVAL, "the per-pair scale needs bits >= 4 and stale_max = 0");
     if (cfg->n > SINGLE_NODE_MASK) return fail(nullptr, SWARM_EINVAL, "n exceeds 65535");
     if (cfg->n_edges == 0 || !cfg->edges) return fail(nullptr, SWARM_EINVAL, "graph has no edges");
     if (cfg->n_edges > MATCHING_MAX_EDGES) return fail(nullptr, SWARM_EINVAL, "too many edges");
@@ -494,7 +497,9 @@ swarm_status swarm_sample_pair(swarm_t h, uint32_t *i, uint32_t *j) {
 static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t npairs, const uint8_t *stale_host,
                                bool fused) {
     const swarm_config &c = h->cfg;
+    const bool pair_scale_policy = c.scale_policy == SWARM_SCALE_PAIR_LINF;
     if (fused) {
+        if (pair_scale_policy) return fail(h, SWARM_ESTATE, "the one-pass round needs the fixed lattice scale");
         if (h->kind != OBJ_DIAG) return fail(h, SWARM_ESTATE, "the fused round needs the diagonal-quadratic objective");
         if (c.bits == 0 || c.H == 0) return fail(h, SWARM_ESTATE, "the fused round needs quantized codes and H > 0");
         for (uint8_t p : h->pending)
@@ -573,8 +578,13 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     const GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
     const bool inplace = c.apply_mode == SWARM_APPLY_INPLACE;
+    if (pair_scale_policy && npairs) {   // distance of every pair first, then each pair quantizes at its own scale
+        SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * npairs, h->stream));
+        SWARM_HIP(h, launch_pair_linf_desc(h->X, c.d, a.pairs, npairs, h->linf_dev, h->stream));
+    }
     {
         GossipArgs ga = a;
+        if (pair_scale_policy) ga.pair_linf = h->linf_dev;
         for (int gidx = 0; gidx < 3; ++gidx) {
             const uint32_t count = (uint32_t)groups[gidx].size();
             if (fused)
@@ -582,6 +592,7 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
             else
                 SWARM_HIP(h, launch_gossip_pairs(ga, c.bits, delta_mode, group_mode[gidx], count, h->stream));
             ga.pairs += count;
+            if (ga.pair_linf) ga.pair_linf += count;
         }
     }
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
@@ -590,9 +601,10 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     if (fused) {
         SWARM_HIP(h, launch_fused_singles(a, h->diag, c.bits, inplace, c.H, c.lr, nsingles, h->stream));
     } else {
-        bool singles_work = c.bits != 0;
+        const uint32_t singles_bits = pair_scale_policy ? 0u : c.bits;   // no shared scale: nothing to publish
+        bool singles_work = singles_bits != 0;
         for (uint32_t u : singles) singles_work |= h->pending[u] != 0;
-        if (singles_work) SWARM_HIP(h, launch_gossip_singles(a, c.bits, nsingles, h->stream));
+        if (singles_work) SWARM_HIP(h, launch_gossip_singles(a, singles_bits, nsingles, h->stream));
     }
 
     std::fill(h->pending.begin(), h->pending.end(), 0);
@@ -618,6 +630,7 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     const swarm_config &c = h->cfg;
     if (c.stale_max != 0) return fail(h, SWARM_EINVAL, "Algorithm 1 steps need stale_max = 0");
     if (c.apply_mode != SWARM_APPLY_DEFERRED) return fail(h, SWARM_EINVAL, "Algorithm 1 defers the local steps");
+    if (c.scale_policy != SWARM_SCALE_FIXED) return fail(h, SWARM_EINVAL, "Algorithm 1 steps use the fixed lattice scale");
     if (i >= c.n || j >= c.n || i == j ||
         !std::binary_search(h->edge_keys.begin(), h->edge_keys.end(), edge_key(i, j)))
         return fail(h, SWARM_EINVAL, "responder is not a neighbour of the initiator");

@@ -484,3 +484,37 @@ def test_geometric_local_steps(gpu):
         g2.write_models(gpu.COMM, c2.X)
         g2.write_models(gpu.SNAP, c2.Xhat)
         assert_close(g2.read_models(gpu.LIVE, pair[0], 1), c2.W[pair[0]:pair[0] + 1], TOL_ELEMENTWISE, f"W_i, t={t}")
+
+
+# ------------------------------------------------------------------ per-pair lattice scale
+@pytest.mark.parametrize("bits", [4, 8])
+def test_pair_linf_scale_policy(gpu, bits):
+    """Each matched pair quantizes at the smallest power-of-two scale that keeps it inside the decoding
+    radius: codes and models match the oracle, and no decode ever fails however far apart the rows are."""
+    n, d, H, lr = 8, D_RAGGED, 2, 0.1
+    edges = wl.complete_graph(n)
+    a, cc = wl.diag_quadratic_data(n, d, 3, shift_sigma=2.0)
+    g, c = make_both(gpu, n, d, edges, bits, 1.0, H, lr, 0, seed=41, pair_scale=True)
+    c.objective = DiagQuadratic(a, cc, 0.05)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
+    gen = np.random.Generator(np.random.PCG64(41))
+    for r, spread in enumerate([1e-3, 0.3, 5.0, 40.0]):
+        c.X[:] = models(gen, 1, d) + models(gen, n, d, spread)
+        c.pending[:] = False
+        force_state(gpu, g, c)
+        c.local_steps([0, 1, 2, 5])
+        g.local_steps([0, 1, 2, 5])
+        force_state(gpu, g, c)
+        pairs = [(0, 4), (6, 1), (2, 3)]                       # 5 and 7 unmatched; 5 has pending steps
+        want = [np.abs(c.X[i] - c.X[j]).max() for i, j in pairs]
+        assert np.array_equal(g.pair_linf(pairs), np.array(want, dtype=np.float32))
+        c.gossip_round(pairs)
+        g.gossip_round(pairs)
+        for i in (0, 4, 6, 1, 2, 3):
+            assert np.array_equal(g.read_codes(i), c.ring[0][i]), (r, i)
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"X after round {r}")
+    assert c.decode_failures == 0 and g.counters()["decode_failures"] == 0
+    with pytest.raises(gpu.SwarmError):
+        g.round_fused(None)
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(n, d, edges, 2, 1.0, H, lr, 0, 0, scale_policy=gpu.SCALE_PAIR_LINF)

@@ -126,3 +126,22 @@ def test_quantize_dequantize_round_trip_with_own_model_as_key():
         # key = the vector itself: z - rint(t) is in {-1, 0, 1}, inside even the 2-bit window [-2, 1]
         q = qz.dequantize(buf, x, eps, bits)
         assert np.all(np.abs(q - x) < eps)
+
+
+@pytest.mark.parametrize("bits", [4, 8, 16])
+def test_pair_scale_is_the_smallest_power_of_two_inside_the_radius(bits):
+    """eps_ij = 2^ceil(log2(m / (2^(b-1) - 3))): a power of two, m <= (2^(b-1) - 3) eps (inside the
+    decoding radius (2^(b-1) - 5/2) eps), and eps/2 would not do; with it no decode can fail."""
+    gen = np.random.Generator(np.random.PCG64(bits))
+    R = (1 << (bits - 1)) - 3
+    for m in list(gen.uniform(1e-6, 50, 200)) + [R * 0.25, R * 0.5, float(np.float32(1e-3)), 0.0]:
+        m = float(np.float32(m))
+        eps = qz.pair_scale(m, bits)
+        assert math.log2(eps) == int(math.log2(eps))
+        if m > 2.0 ** -90:
+            assert m <= R * eps and m > R * eps / 2 * (1 - 1e-6)
+    x = (gen.standard_normal(20000) * 3).astype(np.float32)
+    y = (x + gen.uniform(-1, 1, x.size) * 0.7).astype(np.float32)
+    eps = qz.pair_scale(np.abs(x - y).max(), bits)
+    z = qz.stochastic_round(x, eps, gen.integers(0, 65536, x.size))
+    assert np.array_equal(qz.decode(qz.code(z, bits), y, eps, bits), z)
