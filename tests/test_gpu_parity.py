@@ -518,3 +518,92 @@ def test_pair_linf_scale_policy(gpu, bits):
         g.round_fused(None)
     with pytest.raises(gpu.SwarmError):
         gpu.Swarm(n, d, edges, 2, 1.0, H, lr, 0, 0, scale_policy=gpu.SCALE_PAIR_LINF)
+
+
+# ------------------------------------------------------------------ edge cases and limits
+@pytest.mark.parametrize("case", ["complete64", "ring1500", "regular3_2000", "star"])
+def test_matching_large_graphs(gpu, case):
+    """More edges and more nodes than the matching workgroup has threads; a star (every edge shares
+    one node, exactly one pair) as the degenerate case."""
+    if case == "complete64":
+        n, edges = 64, wl.complete_graph(64)                       # 2016 edges
+    elif case == "ring1500":
+        n = 1500
+        edges = np.array([(i, (i + 1) % n) for i in range(n)], dtype=np.uint32)
+    elif case == "regular3_2000":
+        n, edges = 2000, wl.random_regular_graph(2000, 3, 9)       # 3000 edges
+    else:
+        n = 300
+        edges = np.array([(0, i) for i in range(1, n)], dtype=np.uint32)
+    g, c = make_both(gpu, n, 8, edges, 8, 1.0, 0, 0.0, 0, seed=5)
+    for r in range(4):
+        want = c.sample_matching()
+        assert np.array_equal(g.sample_matching(), want.astype(np.uint32)), (case, r)
+        c.gossip_round(want)
+        g.gossip_round(None)
+    if case == "star":
+        assert len(want) == 1
+    assert g.counters()["interactions"] == c.interactions
+
+
+def test_smallest_swarm_and_empty_rounds(gpu):
+    """n = 2, d = 8 (one Philox call per row), rounds with no pair, H = 0."""
+    g, c = make_both(gpu, 2, 8, [(0, 1)], 8, 0.25, 0, 0.0, 1, seed=1)
+    c.X[:] = np.array([[0.1, -0.2, 0.3, 5.0, -5.0, 0.0, 1.0, 2.0], [0.2, -0.1, 0.1, 4.0, -4.5, 0.5, 1.5, 2.5]], dtype=np.float32)
+    force_state(gpu, g, c)
+    for pairs, stale in [([], None), ([(1, 0)], [1, 1]), ([(0, 1)], [1, 0])]:
+        c.gossip_round(pairs, stale)
+        g.gossip_round(pairs, stale)
+        assert np.array_equal(g.read_codes(0), ring_row(c, 0)) and np.array_equal(g.read_codes(1), ring_row(c, 1))
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, "two-node swarm")
+    with pytest.raises(gpu.SwarmError):
+        g.local_steps()                                   # no objective set
+    a, cc = wl.diag_quadratic_data(2, 8, 0)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.0)
+    g.local_steps()                                       # H = 0: nothing becomes pending
+    before = g.read_models(gpu.COMM)
+    g.gossip_round([])
+    assert np.array_equal(g.read_models(gpu.COMM), before) and g.counters()["rounds"] == 4
+
+
+def test_windows_of_models_and_codes(gpu):
+    n, d, bits = 5, 4096, 4
+    g, c = make_both(gpu, n, d, wl.complete_graph(n), bits, 0.5, 0, 0.0)
+    gen = np.random.Generator(np.random.PCG64(3))
+    c.X[:] = models(gen, n, d)
+    force_state(gpu, g, c)
+    patch = models(gen, 2, 100)
+    g.write_models(gpu.COMM, patch, node0=2, k0=1000)
+    c.X[2:4, 1000:1100] = patch
+    assert np.array_equal(g.read_models(gpu.COMM), c.X)
+    assert np.array_equal(g.read_models(gpu.COMM, node0=3, count=2, k0=8, length=24), c.X[3:5, 8:32])
+    c.gossip_round([(0, 1)])
+    g.gossip_round([(0, 1)])
+    assert np.array_equal(g.read_codes(2, byte0=16, length=64), ring_row(c, 2)[16:80])
+    for bad in (dict(node0=4, count=2), dict(k0=4090, length=10), dict(count=0)):
+        with pytest.raises(gpu.SwarmError):
+            g.read_models(gpu.COMM, **bad)
+    with pytest.raises(gpu.SwarmError):
+        g.read_codes(0, age=1)                           # deeper than the ring
+    view = g.models_view(gpu.COMM)
+    assert view.shape == (n, d) and np.array_equal(view.cpu().numpy(), g.read_models(gpu.COMM))
+
+
+def test_deep_stale_ring(gpu):
+    """Ring of 6 slots with reads up to 5 rounds old, staleness drawn from the STALE stream."""
+    n, d, bits, eps, S = 6, 2048 + 8, 8, 2.0 ** -3, 5
+    g, c = make_both(gpu, n, d, wl.complete_graph(n), bits, eps, 0, 0.0, S, seed=77)
+    gen = np.random.Generator(np.random.PCG64(77))
+    base = models(gen, 1, d)
+    for r in range(9):
+        c.X[:] = base + models(gen, n, d, 0.5)
+        force_state(gpu, g, c)
+        stale = g.sample_stale()
+        assert np.array_equal(stale, c.sample_stale().astype(np.uint8)) and stale.max() <= min(r, S)
+        pairs = c.sample_matching()
+        c.gossip_round(pairs, stale)
+        g.gossip_round(None, stale)
+        for i in range(n):
+            assert np.array_equal(g.read_codes(i), ring_row(c, i)), (r, i)
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"round {r}")
+    assert g.counters()["decode_failures"] == c.decode_failures
