@@ -56,6 +56,9 @@ def build_workload(cfg_id, scale_d=None):
     if cfg["objective"] == "mlp":
         means, cdf = wl.mixture_data(n, cfg["n_in"], cfg["n_out"], 0, cfg["alpha"])
         return cfg, edges, torch.from_numpy(means).cuda(), torch.from_numpy(cdf).cuda()
+    if cfg["objective"] == "lsq":
+        A, b, _ = wl.least_squares_data(n, d, cfg["m_rows"], 0, cfg["shift_sigma"])
+        return cfg, edges, torch.from_numpy(A).cuda(), torch.from_numpy(b).cuda()
     gen = torch.Generator(device="cuda")
     gen.manual_seed(0)
     # a ~ U[lo, hi] (or log-uniform), c ~ N(mu_i, 1), mu_i ~ N(0, shift^2): generated on the device, row by row
@@ -78,6 +81,8 @@ def eps_for(cfg):
     # power of two so that the decoding radius (2^(b-1) - 5/2) eps covers the usual disagreement
     if cfg["objective"] == "mlp":
         return 2.0 ** -10          # weights of order 0.02: radius 125 eps = 0.12
+    if cfg["objective"] == "lsq":
+        return 2.0 ** -6
     if cfg["shift_sigma"] >= 2.0:
         return 0.25                # strongly heterogeneous nodes sit several units apart
     return 0.5 if cfg["bits"] == 4 else 2.0 ** -4
@@ -101,6 +106,8 @@ def cpu_baseline(cfg, edges, a, c, eps, seconds_target=15.0):
     n, d = cfg["n"], cfg["d"]
     if cfg["objective"] == "mlp":
         return cpu_baseline_mlp(cfg, edges, a, c, eps)
+    if cfg["objective"] == "lsq":
+        return cpu_baseline_sequential(cfg, edges, a, c, eps)
     width = 1 << 14
     result = None
     while True:
@@ -121,6 +128,20 @@ def cpu_baseline(cfg, edges, a, c, eps, seconds_target=15.0):
         if dt >= seconds_target / 4 or k1 >= d - d % 8 or width >= 1 << 22:
             return result
         width *= 4
+
+
+def cpu_baseline_sequential(cfg, edges, A, b, eps):
+    """Algorithm 1 on the small least-squares workload: the oracle runs the same interactions in full."""
+    from oracle.objectives import LeastSquares
+    from oracle.swarm import SwarmOracle
+    o = SwarmOracle(cfg["n"], cfg["d"], edges, cfg["bits"], eps, cfg["H"], cfg["lr"], 0, 0)
+    o.objective = LeastSquares(A.cpu().numpy(), b.cpu().numpy(), cfg["batch"])
+    t0 = time.perf_counter()
+    for _ in range(cfg["steps"]):
+        o.step_sequential()
+    dt = time.perf_counter() - t0
+    return dict(value=cfg["steps"] / dt, unit="interactions/s", cores=1, kind="oracle",
+                sample=f"{cfg['steps']} sequential interactions of Algorithm 1 at full size, {dt:.2f} s")
 
 
 def cpu_baseline_mlp(cfg, edges, means, cdf, eps):
@@ -185,7 +206,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=4, help="workload configuration (2, 3, 4 or 5)")
+    ap.add_argument("--config", type=int, default=4, help="workload configuration (1 to 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-call", action="store_true",
                     help="time swarm_local_steps + swarm_gossip_round as the step instead of the one-pass round")
@@ -205,11 +226,19 @@ def main():
         x0 = 0.02 * torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0, x0=x0)
         s.set_objective_mlp(cfg["n_in"], cfg["n_hid"], cfg["n_out"], a, c, cfg["data_sigma"], cfg["batch"])
+    elif cfg["objective"] == "lsq":
+        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], 0, seed=0)
+        s.set_objective_lsq(a, c, cfg["m_rows"], cfg["batch"])
     else:
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0)
         s.set_objective_diag(a, c, cfg["sigma"])
 
+    def step_sequential():
+        s.interact(*s.sample_pair())          # one step of Algorithm 1: initiator's local steps + interaction
+
     def step_two_calls():
+        if cfg["mode"] == "sequential":
+            return step_sequential()
         s.local_steps()
         s.gossip_round(None, stale_plan(cfg, s))
 
@@ -260,6 +289,7 @@ def main():
                                f"sigma={cfg.get('sigma', cfg.get('data_sigma'))} H={cfg['H']} lr={cfg['lr']} bits={bits} "
                                f"stale_max={cfg['stale_max']} ({cfg.get('stale', 'fresh')}) eps={eps}",
                    "step": ("one-pass round (swarm_round_fused)" if use_one_pass
+                            else "swarm_sample_pair + swarm_interact (Algorithm 1)" if cfg["mode"] == "sequential"
                             else "swarm_local_steps + swarm_gossip_round"),
                    "pairs_per_round": main_m["interactions"] / args.steps,
                    "decode_failures": main_m["decode_failures"]},
