@@ -12,6 +12,11 @@
 
 namespace swarm {
 
+#ifndef SWARM_FUSED_WAVES
+#define SWARM_FUSED_WAVES 8
+#endif
+constexpr int FWAVES = SWARM_FUSED_WAVES;     // waves per workgroup of the one-pass kernels
+
 struct FusedArgs {
     GossipArgs g;
     const float *A, *C;       // n x d objective data
@@ -88,9 +93,9 @@ __device__ __forceinline__ void fused_pair_tile(const FusedArgs &fa, const PairD
 }
 
 template <int BITS, int STALE, bool INPLACE, bool NOISE>
-__global__ __launch_bounds__(WAVES * 64) void fused_pairs_kernel(const FusedArgs fa) {
+__global__ __launch_bounds__(FWAVES * 64) void fused_pairs_kernel(const FusedArgs fa) {
     const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t tile = (uint64_t)blockIdx.x * FWAVES + (threadIdx.x >> 6);
     if (tile * TILE >= fa.g.d) return;
     const PairDesc pd = fa.g.pairs[blockIdx.y];
     if (tile * TILE + TILE <= fa.g.d) fused_pair_tile<BITS, STALE, INPLACE, NOISE, true>(fa, pd, tile, lane);
@@ -100,10 +105,10 @@ __global__ __launch_bounds__(WAVES * 64) void fused_pairs_kernel(const FusedArgs
 // Unmatched nodes: take the local steps and adopt the result; publish the code of the model
 // that a partner would have read (the pre-step model when the apply is deferred).
 template <int BITS, bool INPLACE, bool NOISE>
-__global__ __launch_bounds__(WAVES * 64) void fused_singles_kernel(const FusedArgs fa) {
+__global__ __launch_bounds__(FWAVES * 64) void fused_singles_kernel(const FusedArgs fa) {
     const GossipArgs &a = fa.g;
     const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t tile = (uint64_t)blockIdx.x * FWAVES + (threadIdx.x >> 6);
     if (tile * TILE >= a.d) return;
     const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
     const bool inA = kA < a.d, inB = kB < a.d;
@@ -133,10 +138,10 @@ __global__ __launch_bounds__(WAVES * 64) void fused_singles_kernel(const FusedAr
 template <int BITS, bool INPLACE, bool NOISE>
 static void launch_pairs_stale(const FusedArgs &fa, int stale_mode, dim3 grid, hipStream_t st) {
     switch (stale_mode) {
-        case 0: fused_pairs_kernel<BITS, 0, INPLACE, NOISE><<<grid, WAVES * 64, 0, st>>>(fa); break;
-        case 1: fused_pairs_kernel<BITS, 1, INPLACE, NOISE><<<grid, WAVES * 64, 0, st>>>(fa); break;
-        case 3: fused_pairs_kernel<BITS, 3, INPLACE, NOISE><<<grid, WAVES * 64, 0, st>>>(fa); break;
-        default: fused_pairs_kernel<BITS, 2, INPLACE, NOISE><<<grid, WAVES * 64, 0, st>>>(fa); break;
+        case 0: fused_pairs_kernel<BITS, 0, INPLACE, NOISE><<<grid, FWAVES * 64, 0, st>>>(fa); break;
+        case 1: fused_pairs_kernel<BITS, 1, INPLACE, NOISE><<<grid, FWAVES * 64, 0, st>>>(fa); break;
+        case 3: fused_pairs_kernel<BITS, 3, INPLACE, NOISE><<<grid, FWAVES * 64, 0, st>>>(fa); break;
+        default: fused_pairs_kernel<BITS, 2, INPLACE, NOISE><<<grid, FWAVES * 64, 0, st>>>(fa); break;
     }
 }
 
@@ -144,15 +149,15 @@ template <int BITS>
 static void launch_bits(const FusedArgs &fa, bool inplace, bool noise, int stale_mode, uint32_t npairs,
                         uint32_t nsingles, bool singles, hipStream_t st) {
     const uint64_t tiles = (fa.g.d + TILE - 1) / TILE;
-    const unsigned gx = (unsigned)((tiles + WAVES - 1) / WAVES);
+    const unsigned gx = (unsigned)((tiles + FWAVES - 1) / FWAVES);
     if (!singles) {
         const dim3 grid(gx, npairs, 1);
         if (inplace) { if (noise) launch_pairs_stale<BITS, true, true>(fa, stale_mode, grid, st); else launch_pairs_stale<BITS, true, false>(fa, stale_mode, grid, st); }
         else { if (noise) launch_pairs_stale<BITS, false, true>(fa, stale_mode, grid, st); else launch_pairs_stale<BITS, false, false>(fa, stale_mode, grid, st); }
     } else {
         const dim3 grid(gx, nsingles, 1);
-        if (inplace) { if (noise) fused_singles_kernel<BITS, true, true><<<grid, WAVES * 64, 0, st>>>(fa); else fused_singles_kernel<BITS, true, false><<<grid, WAVES * 64, 0, st>>>(fa); }
-        else { if (noise) fused_singles_kernel<BITS, false, true><<<grid, WAVES * 64, 0, st>>>(fa); else fused_singles_kernel<BITS, false, false><<<grid, WAVES * 64, 0, st>>>(fa); }
+        if (inplace) { if (noise) fused_singles_kernel<BITS, true, true><<<grid, FWAVES * 64, 0, st>>>(fa); else fused_singles_kernel<BITS, true, false><<<grid, FWAVES * 64, 0, st>>>(fa); }
+        else { if (noise) fused_singles_kernel<BITS, false, true><<<grid, FWAVES * 64, 0, st>>>(fa); else fused_singles_kernel<BITS, false, false><<<grid, FWAVES * 64, 0, st>>>(fa); }
     }
 }
 
