@@ -46,9 +46,11 @@ def test_diag_configs_full_size_sampled_windows(gpu, cfg_id, eps):
         o = SwarmOracle(n, d, edges, bits, eps, H, lr, S, seed, k0=k0, k1=k0 + width)
         o.objective = DiagQuadratic(a[:, k0:k0 + width].cpu().numpy(), c[:, k0:k0 + width].cpu().numpy(), sigma, k0=k0)
         oracles.append(o)
+    for o, k0 in zip(oracles, starts):                               # the seeded initial state, read once
+        o.X[:] = g.read_models(gpu.COMM, k0=k0, length=width)
     for r in range(4):
-        for o, k0 in zip(oracles, starts):                           # same state on both sides
-            o.X[:] = g.read_models(gpu.COMM, k0=k0, length=width)
+        for o, k0 in zip(oracles, starts):                           # the oracle's state is forced into the device
+            g.write_models(gpu.COMM, o.X, k0=k0)
         pairs = g.sample_matching()
         assert np.array_equal(pairs, oracles[0].sample_matching().astype(np.uint32))
         if cfg.get("stale") == "fixed1":
