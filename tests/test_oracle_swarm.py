@@ -443,3 +443,33 @@ def test_geometric_steps_are_used_by_the_local_steps():
     for i in range(n):
         closed = cc[i] + (1 - np.float64(np.float32(lr)) * a[i].astype(np.float64)) ** int(steps[i]) * (X[i] - cc[i])
         assert np.allclose(o.W[i], closed, atol=1e-13)
+
+
+def test_sequential_sampling_law_initiator_and_responder_independent():
+    """Algorithm 1's sampling lines: every ordered edge (i, j) has probability 1 / (n deg(i))."""
+    edges = wl.torus_graph(4, 4)
+    n = 16
+    o = make(n, 8, edges, seed=12)
+    counts = {}
+    T = 6400
+    for t in range(T):
+        o.interactions = t
+        ij = o.sample_pair()
+        counts[ij] = counts.get(ij, 0) + 1
+    adj = wl.adjacency(n, edges)
+    assert set(counts) == {(i, j) for i in range(n) for j in adj[i]}      # all 64 ordered edges occur
+    expected = T / 64
+    chi2 = sum((c - expected) ** 2 / expected for c in counts.values())
+    assert chi2 < 63 + 5 * math.sqrt(2 * 63)
+
+
+def test_algorithm1_initiator_uses_the_decoded_partner_model():
+    """Rows farther apart than the radius: the initiator averages with what it decodes (another
+    member of the residue class), and writes that average to the responder too."""
+    n, d, eps, bits = 2, 8, 1.0, 4
+    X = np.zeros((n, d))
+    X[1] = 20.0
+    o = make(n, d, wl.complete_graph(n), bits=bits, eps=eps, X=X)
+    o.interact(0, 1)
+    assert np.all(o.X[0] == 2.0) and np.all(o.X[1] == 2.0)          # 20 is read as 20 - 16 = 4
+    assert o.decode_failures == d
