@@ -607,3 +607,32 @@ def test_deep_stale_ring(gpu):
             assert np.array_equal(g.read_codes(i), ring_row(c, i)), (r, i)
         assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"round {r}")
     assert g.counters()["decode_failures"] == c.decode_failures
+
+
+@pytest.mark.parametrize("bits", [0, 2, 4, 16])
+def test_algorithm1_all_code_widths_and_decode_failure(gpu, bits):
+    """Sequential steps with diagonal objectives for every code width; some rows are placed farther
+    apart than the decoding radius so that the initiator averages with a wrapped value."""
+    n, d, H, lr, eps = 6, 8 * 300 + 8, 2, 0.1, 0.25
+    edges = wl.complete_graph(n)
+    a, cc = wl.diag_quadratic_data(n, d, 4)
+    g, c = make_both(gpu, n, d, edges, bits, eps if bits else 0.0, H, lr, 0, seed=61)
+    c.objective = DiagQuadratic(a, cc, 0.05)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
+    gen = np.random.Generator(np.random.PCG64(61))
+    c.X[:] = models(gen, n, d, 0.1)
+    c.X[3] += 5.0                                         # far from everyone: beyond the 2- and 4-bit radius
+    c.Xhat[:] = c.X + models(gen, n, d, 0.05)
+    for t, (i, j) in enumerate([(0, 1), (3, 2), (4, 3), (1, 0), (5, 3)]):
+        g.write_models(gpu.COMM, c.X)
+        g.write_models(gpu.SNAP, c.Xhat)
+        c.interact(i, j)
+        g.interact(i, j)
+        if bits:
+            assert np.array_equal(g.read_codes(i), c.ring[0][i]) and np.array_equal(g.read_codes(j), c.ring[0][j])
+        assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"X, t={t}")
+        assert_close(g.read_models(gpu.SNAP), c.Xhat, 2 * TOL_ELEMENTWISE, f"snapshots, t={t}")
+    cnt = g.counters()
+    assert cnt["decode_failures"] == c.decode_failures and cnt["interactions"] == 5
+    if bits in (2, 4):
+        assert c.decode_failures > 0
