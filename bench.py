@@ -27,11 +27,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {("gossip", 4, True): 25.99, ("round", 4, True): 33.99}
 
 
-def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction):
+def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace=False):
     """Gossip pass: read X_i, X_j, W_i, W_j (16 B), write X_i', X_j' (8 B), write two b-bit codes, read
     two b-bit partner codes when the reads are stale.  One-pass round (local steps inside the gossip
     pass): read X, a, c of both nodes (24 B) instead of X and W; W never moves."""
-    reads = 16 if kernel == "gossip" else 24
+    reads = (8 if inplace else 16) if kernel == "gossip" else 24    # in-place apply: no second matrix to read
     return reads + 8 + 2 * bits / 8 + stale_fraction * 2 * bits / 8
 
 
@@ -183,16 +183,16 @@ def measure(torch, s, step, steps, warmup):
                 decode_failures=after["decode_failures"] - before["decode_failures"])
 
 
-def roofline(kernel, name, cfg, m, d):
+def roofline(kernel, name, cfg, m, d, inplace=False):
     """Algorithmic bytes of the timed launches / their summed HIP-event duration, against 8 TB/s."""
     bits, S = cfg["bits"], cfg["stale_max"]
     stale_fraction = {"fixed1": 1.0, "uniform": S / (S + 1.0)}.get(cfg.get("stale"), 0.0)
-    per_pc = algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction)
+    per_pc = algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace)
     launches = max(1, m["times"]["gossip_calls"])
     total = per_pc * d * m["interactions"]
     seconds = m["times"]["gossip_ms"] * 1e-3
     achieved = total / seconds / 1e9 if seconds > 0 else 0.0
-    measured = MEASURED_TRAFFIC_PER_PAIR_COORDINATE.get((kernel, bits, stale_fraction == 1.0))
+    measured = None if inplace else MEASURED_TRAFFIC_PER_PAIR_COORDINATE.get((kernel, bits, stale_fraction == 1.0))
     return {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": None if measured is None else measured * d * m["interactions"] / launches,
@@ -210,6 +210,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-call", action="store_true",
                     help="time swarm_local_steps + swarm_gossip_round as the step instead of the one-pass round")
+    ap.add_argument("--inplace", action="store_true",
+                    help="in-place apply mode (local steps update the exchanged model; one matrix) instead of the "
+                         "paper's deferred apply")
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -230,7 +233,8 @@ def main():
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], 0, seed=0)
         s.set_objective_lsq(a, c, cfg["m_rows"], cfg["batch"])
     else:
-        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0)
+        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0,
+                        apply_mode=swarm.INPLACE if args.inplace else swarm.DEFERRED)
         s.set_objective_diag(a, c, cfg["sigma"])
 
     def step_sequential():
@@ -260,7 +264,8 @@ def main():
     def two_call_report(m):
         t = m["times"]
         rep = {"interactions_per_s": m["interactions"] / m["dt"], "ms_per_step": m["dt"] / args.steps * 1e3,
-               "gossip_pass": roofline("gossip", "gossip_pairs_kernel (quantize/exchange/decode/average)", cfg, m, d),
+               "gossip_pass": roofline("gossip", "gossip_pairs_kernel (quantize/exchange/decode/average)", cfg, m, d,
+                                       args.inplace),
                "local_steps_ms_per_round": t["local_ms"] / max(1, t["local_calls"])}
         if cfg["objective"] == "mlp":
             # 5 GEMMs of 2*batch*in*hid (= 2*batch*hid*out here) flops per node and local step
@@ -288,6 +293,7 @@ def main():
         "config": {"workload": f"config {args.config}: n={n} d={d} graph={cfg['graph']} {cfg['objective']} "
                                f"sigma={cfg.get('sigma', cfg.get('data_sigma'))} H={cfg['H']} lr={cfg['lr']} bits={bits} "
                                f"stale_max={cfg['stale_max']} ({cfg.get('stale', 'fresh')}) eps={eps}",
+                   "apply_mode": "inplace" if args.inplace else "deferred",
                    "step": ("one-pass round (swarm_round_fused)" if use_one_pass
                             else "swarm_sample_pair + swarm_interact (Algorithm 1)" if cfg["mode"] == "sequential"
                             else "swarm_local_steps + swarm_gossip_round"),
