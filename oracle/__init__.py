@@ -24,11 +24,18 @@ Pin status per function (what each is checked against, other than itself):
   gossip_round (quantized) both members of a pair hold the same average when
                            both decodes succeed; contraction on the complete
                            graph by enumeration
-  interact (Algorithm 1)   responder receives the plain average; snapshot rule
+  interact (Algorithm 1)   responder receives the plain average; snapshot rule; exact
+                           potential identity of the per-step lemma; wrapped value under
+                           decode failure
   local steps, diagonal    closed form w_H = c + (1-eta a)^H (w_0 - c) at sigma=0
   local steps, least sq.   numpy gradient A^T(Ax-b) on the same batch
   local steps, MLP         torch.autograd in float64 on the same batch
+  sample_pair              every ordered edge (i, j) equally likely per 1/(n deg i), chi^2
   sample_matching          validity + brute-force greedy on tiny graphs + chi^2
+  sample_stale             uniform on {0..S}, limited to the rounds that exist
+  steps_of (geometric H)   E[H_i] = H and E[H_i^2] = 2H^2 - H (appendix, local steps)
+  pair_scale               smallest power of two inside the decoding radius; no decode fails
+  apply_mode "inplace"     X_i' = (w_i + w_j)/2 with w the closed-form local-step result
   potential                definition, and the Laplacian inequality of the appendix
   whole trajectories       parity unpinned beyond the invariants above
 """
