@@ -204,8 +204,9 @@ def roofline(kernel, name, cfg, m, d, inplace=False):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps first: the first ~10 launches run up to 15 %% slower (clock ramp)")
     ap.add_argument("--config", type=int, default=4, help="workload configuration (1 to 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-call", action="store_true",
@@ -258,7 +259,7 @@ def main():
     main_m = measure(torch, s, step_one_pass if use_one_pass else step_two_calls, args.steps, args.warmup)
     other_m = None
     if one_pass_ok:
-        other_m = measure(torch, s, step_two_calls if use_one_pass else step_one_pass, args.steps, 2)
+        other_m = measure(torch, s, step_two_calls if use_one_pass else step_one_pass, args.steps, 3)
     one_m, two_m = (main_m, other_m) if use_one_pass else (other_m, main_m)
 
     def two_call_report(m):
@@ -318,9 +319,24 @@ def main():
     ev1.record()
     torch.cuda.synchronize()
     copy_gbs = 2.0 * src.numel() * 4 * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-    del dst
     out["roofline"]["copy_kernel_GBps"] = copy_gbs
     out["roofline"]["frac_of_copy"] = out["roofline"]["achieved"] / copy_gbs
+    # The same copy with as many concurrent float streams as the timed kernel touches (bandwidth on this
+    # part falls with the number of streams): 6 read + 2 write for the one-pass round, 4 + 2 for the gossip pass.
+    n_read = 6 if use_one_pass else 4
+    rows = max(1, min(n // n_read, n // 2))                      # rows of the model matrix per stream
+    stream_bytes = rows * d * 4
+    if n_read * stream_bytes <= src.numel() * 4 and 2 * stream_bytes <= dst.numel() * 4:
+        swarm.stream_mix(dst, src, stream_bytes, n_read, 2)
+        ev0.record()
+        for _ in range(5):
+            swarm.stream_mix(dst, src, stream_bytes, n_read, 2)
+        ev1.record()
+        torch.cuda.synchronize()
+        mix_gbs = (n_read + 2) * stream_bytes * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        out["roofline"]["same_stream_count_copy_GBps"] = mix_gbs
+        out["roofline"]["frac_of_same_stream_count_copy"] = out["roofline"]["achieved"] / mix_gbs
+    del dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, edges, a, c, eps)
     print(json.dumps(out))

@@ -222,6 +222,12 @@ swarm_status swarm_kernel_times(swarm_t h, double *gossip_ms, uint32_t *gossip_c
  * device buffers on the given stream -- the copy rate the gossip pass is compared with. */
 swarm_status swarm_stream_copy(void *dst_dev, const void *src_dev, uint64_t nbytes, void *hip_stream);
 
+/* Measurement aid: the same streaming access with n_read concurrent read streams (consecutive
+ * blocks of stream_bytes in src_dev) summed into n_write write streams (consecutive blocks in
+ * dst_dev).  Shapes (n_read, n_write): (2,2), (4,2), (6,2).  stream_bytes a multiple of 16. */
+swarm_status swarm_stream_mix(void *dst_dev, const void *src_dev, uint64_t stream_bytes, uint32_t n_read,
+                              uint32_t n_write, void *hip_stream);
+
 const char *swarm_last_error(swarm_t h);
 
 #ifdef __cplusplus

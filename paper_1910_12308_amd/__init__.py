@@ -26,7 +26,7 @@ EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set
            "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
            "swarm_potential", "swarm_pair_linf", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
-           "swarm_stream_copy", "swarm_last_error"]
+           "swarm_stream_copy", "swarm_stream_mix", "swarm_last_error"]
 
 
 class SwarmError(RuntimeError):
@@ -75,6 +75,7 @@ def load_library():
         "swarm_counters": [vp, P(u64), P(u64), P(u64), P(u64)],
         "swarm_timing_reset": [vp],
         "swarm_stream_copy": [vp, vp, u64, vp],
+        "swarm_stream_mix": [vp, vp, u64, u32, u32, vp],
         "swarm_kernel_times": [vp, P(ctypes.c_double), P(u32), P(ctypes.c_double), P(u32)],
     }
     for name, argtypes in sig.items():
@@ -313,5 +314,15 @@ def stream_copy(dst, src, stream=None):
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     rc = lib().swarm_stream_copy(_dev_ptr(dst), _dev_ptr(src), nbytes, _stream_ptr(stream))
+    if rc != OK:
+        raise SwarmError(rc, lib().swarm_last_error(None).decode())
+
+
+def stream_mix(dst, src, stream_bytes, n_read, n_write, stream=None):
+    """n_read streams of stream_bytes (consecutive in src) summed into n_write streams (consecutive in dst)."""
+    assert src.numel() * src.element_size() >= n_read * stream_bytes
+    assert dst.numel() * dst.element_size() >= n_write * stream_bytes
+    rc = lib().swarm_stream_mix(_dev_ptr(dst), _dev_ptr(src), int(stream_bytes), int(n_read), int(n_write),
+                                _stream_ptr(stream))
     if rc != OK:
         raise SwarmError(rc, lib().swarm_last_error(None).decode())

@@ -75,6 +75,10 @@ hipError_t launch_pair_linf_desc(const float *X, uint64_t d, const PairDesc *pai
 
 // Streaming copy of nbytes (multiple of 16, below 2^36) from src to dst.
 hipError_t launch_stream_copy(const void *src, void *dst, uint64_t nbytes, hipStream_t st);
+// n_read streams of stream_bytes each (consecutive in src) summed into n_write streams (consecutive in
+// dst); supported shapes (n_read, n_write): (2,2), (4,2), (6,2).
+hipError_t launch_stream_mix(const void *src, void *dst, uint64_t stream_bytes, uint32_t n_read, uint32_t n_write,
+                             hipStream_t st);
 
 // Matching: one workgroup; outputs pairs (increasing edge index), their count, the
 // unmatched nodes and their count.

@@ -428,10 +428,10 @@ swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count)
 // Enqueue the matching of the current round and its copy to pinned host memory.  The matching
 // depends only on (seed, round, graph), so it can be issued a round ahead: the host then finds
 // it ready instead of draining the stream.
-static swarm_status enqueue_matching(swarm_t h) {
+static swarm_status enqueue_matching(swarm_t h, uint64_t round) {
     const swarm_config &c = h->cfg;
     const uint32_t maxp = c.n / 2;
-    SWARM_HIP(h, launch_matching(h->edges_dev, c.n_edges, c.n, c.seed, (uint32_t)h->round, h->prio_dev,
+    SWARM_HIP(h, launch_matching(h->edges_dev, c.n_edges, c.n, c.seed, (uint32_t)round, h->prio_dev,
                                  h->mpairs_dev, h->msingles_dev, h->counts_dev, h->stream));
     SWARM_HIP(h, hipMemcpyAsync(h->match_host, h->counts_dev, sizeof(uint32_t) * 2, hipMemcpyDeviceToHost, h->stream));
     SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2, h->mpairs_dev, sizeof(uint32_t) * 2 * maxp,
@@ -439,13 +439,13 @@ static swarm_status enqueue_matching(swarm_t h) {
     SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2 + 2 * maxp, h->msingles_dev, sizeof(uint32_t) * c.n,
                                 hipMemcpyDeviceToHost, h->stream));
     SWARM_HIP(h, hipEventRecord(h->match_ready, h->stream));
-    h->match_round = h->round;
+    h->match_round = round;
     return SWARM_OK;
 }
 
 static swarm_status sample_matching_device(swarm_t h, uint32_t *npairs, uint32_t *nsingles) {
     const swarm_config &c = h->cfg;
-    if (h->match_round != h->round) SWARM_TRY(enqueue_matching(h));
+    if (h->match_round != h->round) SWARM_TRY(enqueue_matching(h, h->round));
     SWARM_HIP(h, hipEventSynchronize(h->match_ready));
     *npairs = h->match_host[0];
     *nsingles = h->match_host[1];
@@ -508,7 +508,6 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     const uint32_t n = c.n;
     std::vector<uint32_t> pairs, singles;
     uint32_t nsingles = 0;
-    bool device_pairs = false;
     if (pairs_host) {
         if (npairs > n / 2) return fail(h, SWARM_EINVAL, "more pairs than floor(n/2)");
         std::vector<uint8_t> used(n, 0);
@@ -528,7 +527,9 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
         if (rc != SWARM_OK) return rc;
         pairs.assign(h->match_host + 2, h->match_host + 2 + 2 * (size_t)npairs);
         singles.assign(h->match_host + 2 + 2 * (n / 2), h->match_host + 2 + 2 * (n / 2) + nsingles);
-        device_pairs = true;
+        // The next round's matching goes into the stream now, ahead of this round's long kernels, so
+        // that the next call finds it ready without waiting for them (match_host was copied out above).
+        SWARM_TRY(enqueue_matching(h, h->round + 1));
     }
     std::vector<uint8_t> stale(n, 0);
     if (stale_host) {
@@ -611,7 +612,6 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     h->round += 1;
     h->interactions += npairs;
     h->bits_communicated += 2ull * npairs * c.d * (c.bits ? c.bits : 32);
-    if (device_pairs) SWARM_TRY(enqueue_matching(h));   // next round's matching, one round ahead
     return SWARM_OK;
 }
 
@@ -795,6 +795,15 @@ swarm_status swarm_stream_copy(void *dst_dev, const void *src_dev, uint64_t nbyt
     if (!dst_dev || !src_dev || nbytes == 0 || nbytes % 16 != 0 || nbytes > (1ull << 36))
         return fail(nullptr, SWARM_EINVAL, "stream copy: size must be a multiple of 16, at most 2^36");
     const hipError_t e = launch_stream_copy(src_dev, dst_dev, nbytes, (hipStream_t)hip_stream);
+    return e == hipSuccess ? SWARM_OK : fail(nullptr, SWARM_EDEVICE, hipGetErrorString(e));
+}
+
+swarm_status swarm_stream_mix(void *dst_dev, const void *src_dev, uint64_t stream_bytes, uint32_t n_read,
+                              uint32_t n_write, void *hip_stream) {
+    if (!dst_dev || !src_dev || stream_bytes == 0 || stream_bytes % 16 != 0 || stream_bytes > (1ull << 36))
+        return fail(nullptr, SWARM_EINVAL, "stream mix: size must be a multiple of 16, at most 2^36");
+    const hipError_t e = launch_stream_mix(src_dev, dst_dev, stream_bytes, n_read, n_write, (hipStream_t)hip_stream);
+    if (e == hipErrorInvalidValue) return fail(nullptr, SWARM_EINVAL, "stream mix: unsupported (n_read, n_write)");
     return e == hipSuccess ? SWARM_OK : fail(nullptr, SWARM_EDEVICE, hipGetErrorString(e));
 }
 
