@@ -102,6 +102,59 @@ __global__ __launch_bounds__(FWAVES * 64) void fused_pairs_kernel(const FusedArg
     else fused_pair_tile<BITS, STALE, INPLACE, NOISE, false>(fa, pd, tile, lane);
 }
 
+// Both reads of a pair are stale: neither node needs the other's current model, only the code the
+// other published earlier, so every node is processed on its own.  Same arithmetic and bytes as
+// the pair form, but a workgroup touches half as many memory streams at a time (3 float reads, one
+// float write, two code streams), and HBM bandwidth on this part falls with the number of
+// concurrent streams.
+template <int BITS, bool INPLACE, bool NOISE, bool FULL>
+__device__ __forceinline__ void fused_node_tile(const FusedArgs &fa, uint32_t node, uint32_t partner, uint32_t age,
+                                                uint32_t H, uint64_t tile, uint32_t lane) {
+    const GossipArgs &a = fa.g;
+    const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
+    const bool inA = FULL || kA < a.d, inB = FULL || kB < a.d;
+    const uint64_t lA = inA ? kA : a.d - 4, lB = inB ? kB : a.d - 4;
+    const uint64_t on = (uint64_t)node * a.d;
+    float *x = a.X + on;
+    const f4 xA = ldg_nt(x + lA), xB = ldg_nt(x + lB);
+    const f4 aA = ldg_nt(fa.A + on + lA), aB = ldg_nt(fa.A + on + lB);
+    const f4 cA = ldg_nt(fa.C + on + lA), cB = ldg_nt(fa.C + on + lB);
+    const uint64_t slot_bytes = (uint64_t)a.n * a.row_bytes;
+    const uint8_t *src = a.ring + ((a.slot_now + a.ring_depth - age) % a.ring_depth) * slot_bytes + partner * a.row_bytes;
+    const uint64_t seenA = load_code<BITS>(src, lA / 4), seenB = load_code<BITS>(src, lB / 4);
+    const f4 wA = diag_steps<NOISE>(xA, aA, cA, node, lA / 4, H, fa.lr, fa.sigma, a.seed, a.event);
+    const f4 wB = diag_steps<NOISE>(xB, aB, cB, node, lB / 4, H, fa.lr, fa.sigma, a.seed, a.event);
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    const f4 qA = INPLACE ? wA : xA, qB = INPLACE ? wB : xB;
+    const f4 dA = INPLACE ? zero : wA - xA, dB = INPLACE ? zero : wB - xB;
+    const LaneRandom r = row_random(a.seed, node, a.event, tile, lane);
+    bool clampedA = false, clampedB = false;
+    int fails = 0;
+    int zA[4], zB[4];
+    const uint64_t codeA = round_float4<BITS>(qA, r.a0, r.a1, a.inv_eps, zA, clampedA);
+    const uint64_t codeB = round_float4<BITS>(qB, r.b0, r.b1, a.inv_eps, zB, clampedB);
+    const float half_eps = 0.5f * a.eps;
+    const f4 oA = averaged<BITS>(zA, seenA, qA, dA, a.inv_eps, half_eps, nullptr, fails, clampedA);
+    const f4 oB = averaged<BITS>(zB, seenB, qB, dB, a.inv_eps, half_eps, nullptr, fails, clampedB);
+    uint8_t *pub = a.ring + a.slot_now * slot_bytes + node * a.row_bytes;
+    if (inA) { stg_nt(x + kA, oA); store_code<BITS>(pub, kA / 4, codeA); }
+    if (inB) { stg_nt(x + kB, oB); store_code<BITS>(pub, kB / 4, codeB); }
+    report(a.counters, 0, (inA && clampedA) || (inB && clampedB));
+}
+
+template <int BITS, bool INPLACE, bool NOISE>
+__global__ __launch_bounds__(FWAVES * 64) void fused_nodes_kernel(const FusedArgs fa) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t tile = (uint64_t)blockIdx.x * FWAVES + (threadIdx.x >> 6);
+    if (tile * TILE >= fa.g.d) return;
+    const PairDesc pd = fa.g.pairs[blockIdx.y >> 1];              // two rows of the grid per pair
+    const bool second = blockIdx.y & 1u;
+    const uint32_t node = second ? pd.nj : pd.ni, partner = second ? pd.ni : pd.nj;
+    const uint32_t age = (pd.flags >> (second ? 8 : 0)) & 0xFFu, H = (pd.steps >> (second ? 8 : 0)) & 0xFFu;
+    if (tile * TILE + TILE <= fa.g.d) fused_node_tile<BITS, INPLACE, NOISE, true>(fa, node, partner, age, H, tile, lane);
+    else fused_node_tile<BITS, INPLACE, NOISE, false>(fa, node, partner, age, H, tile, lane);
+}
+
 // Unmatched nodes: take the local steps and adopt the result; publish the code of the model
 // that a partner would have read (the pre-step model when the apply is deferred).
 template <int BITS, bool INPLACE, bool NOISE>
@@ -139,7 +192,9 @@ template <int BITS, bool INPLACE, bool NOISE>
 static void launch_pairs_stale(const FusedArgs &fa, int stale_mode, dim3 grid, hipStream_t st) {
     switch (stale_mode) {
         case 0: fused_pairs_kernel<BITS, 0, INPLACE, NOISE><<<grid, FWAVES * 64, 0, st>>>(fa); break;
-        case 1: fused_pairs_kernel<BITS, 1, INPLACE, NOISE><<<grid, FWAVES * 64, 0, st>>>(fa); break;
+        case 1:   // both reads stale: one grid row per node
+            fused_nodes_kernel<BITS, INPLACE, NOISE><<<dim3(grid.x, 2 * grid.y, 1), FWAVES * 64, 0, st>>>(fa);
+            break;
         case 3: fused_pairs_kernel<BITS, 3, INPLACE, NOISE><<<grid, FWAVES * 64, 0, st>>>(fa); break;
         default: fused_pairs_kernel<BITS, 2, INPLACE, NOISE><<<grid, FWAVES * 64, 0, st>>>(fa); break;
     }

@@ -88,6 +88,54 @@ __device__ __forceinline__ void gossip_pair_tile(const GossipArgs &a, const Pair
     report(a.counters, (inA ? failsA : 0) + (inB ? failsB : 0), (inA && clampedA) || (inB && clampedB));
 }
 
+// Both reads of a pair are stale: each node only needs its own rows and the code its partner
+// published earlier, so it is processed on its own -- half as many concurrent memory streams per
+// workgroup as the pair form, same arithmetic and bytes.
+template <int BITS, int DELTA, bool FULL>
+__device__ __forceinline__ void gossip_node_tile(const GossipArgs &a, uint32_t node, uint32_t partner, uint32_t age,
+                                                 bool pending, uint64_t tile, uint32_t lane) {
+    const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
+    const bool inA = FULL || kA < a.d, inB = FULL || kB < a.d;
+    const uint64_t lA = inA ? kA : a.d - 4, lB = inB ? kB : a.d - 4;
+    float *x = a.X + (uint64_t)node * a.d;
+    const float *w = a.W + (uint64_t)node * a.d;
+    const bool delta = DELTA == 1 || (DELTA == 2 && pending);
+    const f4 xA = ldg_nt(x + lA), xB = ldg_nt(x + lB);
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    f4 wA = zero, wB = zero;
+    if (delta) { wA = ldg_nt(w + lA); wB = ldg_nt(w + lB); }
+    const uint64_t slot_bytes = (uint64_t)a.n * a.row_bytes;
+    const uint8_t *src = a.ring + ((a.slot_now + a.ring_depth - age) % a.ring_depth) * slot_bytes + partner * a.row_bytes;
+    const uint64_t seenA = load_code<BITS>(src, lA / 4), seenB = load_code<BITS>(src, lB / 4);
+    const LaneRandom r = row_random(a.seed, node, a.event, tile, lane);
+    bool clampedA = false, clampedB = false;
+    int fails = 0;
+    int zA[4], zB[4];
+    const uint64_t codeA = round_float4<BITS>(xA, r.a0, r.a1, a.inv_eps, zA, clampedA);
+    const uint64_t codeB = round_float4<BITS>(xB, r.b0, r.b1, a.inv_eps, zB, clampedB);
+    const float half_eps = 0.5f * a.eps;
+    const f4 oA = averaged<BITS>(zA, seenA, xA, delta ? wA - xA : zero, a.inv_eps, half_eps, nullptr, fails, clampedA);
+    const f4 oB = averaged<BITS>(zB, seenB, xB, delta ? wB - xB : zero, a.inv_eps, half_eps, nullptr, fails, clampedB);
+    uint8_t *pub = a.ring + a.slot_now * slot_bytes + node * a.row_bytes;
+    if (inA) { stg_nt(x + kA, oA); store_code<BITS>(pub, kA / 4, codeA); }
+    if (inB) { stg_nt(x + kB, oB); store_code<BITS>(pub, kB / 4, codeB); }
+    report(a.counters, 0, (inA && clampedA) || (inB && clampedB));
+}
+
+template <int BITS, int DELTA>
+__global__ __launch_bounds__(WAVES * 64) void gossip_nodes_kernel(const GossipArgs a) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    if (tile * TILE >= a.d) return;
+    const PairDesc pd = a.pairs[blockIdx.y >> 1];                  // two rows of the grid per pair
+    const bool second = blockIdx.y & 1u;
+    const uint32_t node = second ? pd.nj : pd.ni, partner = second ? pd.ni : pd.nj;
+    const uint32_t age = (pd.flags >> (second ? 8 : 0)) & 0xFFu;
+    const bool pending = pd.flags & (second ? 1u << 17 : 1u << 16);
+    if (tile * TILE + TILE <= a.d) gossip_node_tile<BITS, DELTA, true>(a, node, partner, age, pending, tile, lane);
+    else gossip_node_tile<BITS, DELTA, false>(a, node, partner, age, pending, tile, lane);
+}
+
 template <int BITS, int DELTA, int STALE>
 __global__ __launch_bounds__(WAVES * 64) void gossip_pairs_kernel(const GossipArgs a) {
     const uint32_t lane = threadIdx.x & 63u;
@@ -245,6 +293,13 @@ static void launch_pairs_bits(const GossipArgs &a, int delta_mode, int stale_mod
     if (delta_mode == D && stale_mode == S) {                                                 \
         gossip_pairs_kernel<BITS, D, S><<<grid, WAVES * 64, 0, st>>>(a);                      \
         return;                                                                               \
+    }
+    if (stale_mode == 1 && !a.pair_linf) {   // both reads stale: one grid row per node
+        const dim3 g2(grid.x, 2 * grid.y, 1);
+        if (delta_mode == 0) gossip_nodes_kernel<BITS, 0><<<g2, WAVES * 64, 0, st>>>(a);
+        else if (delta_mode == 1) gossip_nodes_kernel<BITS, 1><<<g2, WAVES * 64, 0, st>>>(a);
+        else gossip_nodes_kernel<BITS, 2><<<g2, WAVES * 64, 0, st>>>(a);
+        return;
     }
     SWARM_CASE(0, 0) SWARM_CASE(0, 1) SWARM_CASE(0, 2) SWARM_CASE(0, 3)
     SWARM_CASE(1, 0) SWARM_CASE(1, 1) SWARM_CASE(1, 2) SWARM_CASE(1, 3)
