@@ -22,7 +22,7 @@ class DiagQuadratic:
 
     def gradient(self, node, w, seed, event, q):
         k1 = self.k0 + w.size
-        noise = rng.normals(seed, node, event, q, self.k0, k1) if self.sigma != 0.0 else 0.0
+        noise = rng.noise_normals(seed, node, event, q, self.k0, k1) if self.sigma != 0.0 else 0.0
         return self.a[node] * (w - self.c[node]) + self.sigma * noise
 
 

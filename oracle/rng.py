@@ -19,7 +19,7 @@ import numpy as np
 from .philox import philox4x32_10
 
 TAG_SR = 1      # stochastic rounding, index = coordinate // 8
-TAG_NOISE = 2   # gradient noise, index = coordinate // 4
+TAG_NOISE = 2   # gradient noise, index = coordinate // 8 (see noise_normals)
 TAG_MATCH = 3   # edge priorities of the round's matching, c2 = edge id
 TAG_PICK = 4    # sequential model: initiator and responder
 TAG_BATCH = 5   # least squares: minibatch rows, index = draw // 4
@@ -56,7 +56,7 @@ def sr_halves(seed, node, event, k0, k1):
     return halves.reshape(-1).astype(np.uint32)
 
 
-def normals(seed, node, event, q, k0, k1, tag=TAG_NOISE):
+def normals(seed, node, event, q, k0, k1, tag=TAG_DATA):
     """Standard normal draws for coordinates k0..k1-1 (multiples of 4), float64.
 
     One Philox call serves 4 consecutive coordinates through two Box-Muller
@@ -73,6 +73,30 @@ def normals(seed, node, event, q, k0, k1, tag=TAG_NOISE):
         r = np.sqrt(-2.0 * np.log(u1))
         out[:, 2 * col] = r * np.cos(2.0 * np.pi * u2)
         out[:, 2 * col + 1] = r * np.sin(2.0 * np.pi * u2)
+    return out.reshape(-1)
+
+
+def noise_normals(seed, node, event, q, k0, k1):
+    """Gradient-noise draws for coordinates k0..k1-1 (multiples of 8), float64.
+
+    One Philox call (stream TAG_NOISE, index = coordinate // 8) serves 8
+    consecutive coordinates: word p of the call gives the Box-Muller pair of
+    coordinates 8g+2p and 8g+2p+1 from its two 16-bit halves,
+        u1 = (low half + 1/2) 2^-16 in (0, 1),   u2 = high half * 2^-16 in [0, 1),
+        (r cos 2 pi u2, r sin 2 pi u2),  r = sqrt(-2 ln u1).
+    Sixteen-bit uniforms bound |z| by sqrt(34 ln 2) = 4.855 and halve the
+    generator work per draw compared with `normals`; for simulated gradient
+    noise the discretisation is far below what SGD can see."""
+    assert k0 % 8 == 0 and k1 % 8 == 0
+    g = np.arange(k0 // 8, k1 // 8, dtype=np.uint64)
+    words = stream(seed, TAG_NOISE, q, node, event, g)
+    out = np.empty((g.size, 8), dtype=np.float64)
+    for p, w in enumerate(words):
+        u1 = ((w & np.uint32(0xFFFF)).astype(np.float64) + 0.5) * 2.0 ** -16
+        u2 = (w >> np.uint32(16)).astype(np.float64) * 2.0 ** -16
+        r = np.sqrt(-2.0 * np.log(u1))
+        out[:, 2 * p] = r * np.cos(2.0 * np.pi * u2)
+        out[:, 2 * p + 1] = r * np.sin(2.0 * np.pi * u2)
     return out.reshape(-1)
 
 

@@ -57,10 +57,9 @@ __device__ __forceinline__ void fused_pair_tile(const FusedArgs &fa, const PairD
 
     // local steps of both nodes on this lane's four float4 (step counts travel in the descriptor)
     const uint32_t Hi = pd.steps & 0xFFu, Hj = (pd.steps >> 8) & 0xFFu;
-    const f4 wiA = diag_steps<NOISE>(xiA, aiA, ciA_, ni, lA / 4, Hi, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wiB = diag_steps<NOISE>(xiB, aiB, ciB_, ni, lB / 4, Hi, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wjA = diag_steps<NOISE>(xjA, ajA, cjA_, nj, lA / 4, Hj, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wjB = diag_steps<NOISE>(xjB, ajB, cjB_, nj, lB / 4, Hj, fa.lr, fa.sigma, a.seed, a.event);
+    f4 wiA = xiA, wiB = xiB, wjA = xjA, wjB = xjB;
+    diag_steps<NOISE>(wiA, wiB, aiA, aiB, ciA_, ciB_, ni, tile, lane, Hi, fa.lr, fa.sigma, a.seed, a.event);
+    diag_steps<NOISE>(wjA, wjB, ajA, ajB, cjA_, cjB_, nj, tile, lane, Hj, fa.lr, fa.sigma, a.seed, a.event);
     // what is quantized / used as decoding key, and what is added to the average
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     const f4 qiA = INPLACE ? wiA : xiA, qiB = INPLACE ? wiB : xiB, qjA = INPLACE ? wjA : xjA, qjB = INPLACE ? wjB : xjB;
@@ -122,8 +121,8 @@ __device__ __forceinline__ void fused_node_tile(const FusedArgs &fa, uint32_t no
     const uint64_t slot_bytes = (uint64_t)a.n * a.row_bytes;
     const uint8_t *src = a.ring + ((a.slot_now + a.ring_depth - age) % a.ring_depth) * slot_bytes + partner * a.row_bytes;
     const uint64_t seenA = load_code<BITS>(src, lA / 4), seenB = load_code<BITS>(src, lB / 4);
-    const f4 wA = diag_steps<NOISE>(xA, aA, cA, node, lA / 4, H, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wB = diag_steps<NOISE>(xB, aB, cB, node, lB / 4, H, fa.lr, fa.sigma, a.seed, a.event);
+    f4 wA = xA, wB = xB;
+    diag_steps<NOISE>(wA, wB, aA, aB, cA, cB, node, tile, lane, H, fa.lr, fa.sigma, a.seed, a.event);
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     const f4 qA = INPLACE ? wA : xA, qB = INPLACE ? wB : xB;
     const f4 dA = INPLACE ? zero : wA - xA, dB = INPLACE ? zero : wB - xB;
@@ -171,8 +170,9 @@ __global__ __launch_bounds__(FWAVES * 64) void fused_singles_kernel(const FusedA
     const uint64_t ou = (uint64_t)u * a.d;
     float *xu = a.X + ou;
     const f4 xA = ldg_nt(xu + lA), xB = ldg_nt(xu + lB);
-    const f4 wA = diag_steps<NOISE>(xA, ldg_nt(fa.A + ou + lA), ldg_nt(fa.C + ou + lA), u, lA / 4, Hu, fa.lr, fa.sigma, a.seed, a.event);
-    const f4 wB = diag_steps<NOISE>(xB, ldg_nt(fa.A + ou + lB), ldg_nt(fa.C + ou + lB), u, lB / 4, Hu, fa.lr, fa.sigma, a.seed, a.event);
+    f4 wA = xA, wB = xB;
+    diag_steps<NOISE>(wA, wB, ldg_nt(fa.A + ou + lA), ldg_nt(fa.A + ou + lB), ldg_nt(fa.C + ou + lA), ldg_nt(fa.C + ou + lB), u, tile,
+                      lane, Hu, fa.lr, fa.sigma, a.seed, a.event);
     if constexpr (BITS > 0) {
         const LaneRandom r = row_random(a.seed, u, a.event, tile, lane);
         bool clampedA = false, clampedB = false;

@@ -3,38 +3,44 @@
 // (appendix, definition of the local steps: the q-th gradient is taken at the base
 // model minus eta times the sum of the previous ones, with a fresh sample).  All H
 // steps of a coordinate stay in registers: one read of the base model, a and c, one
-// write of the live copy W.  One thread owns one float4; one Philox call per step
-// gives its four normals.
+// write of the live copy W.  A wave owns a 512-coordinate tile of one node's row; a lane
+// holds float4 number l and l + 64 of it (two coalesced 1 KiB accesses per array).
 #include "diag_steps.hpp"
 
 namespace swarm {
 
 template <bool NOISE>
-__global__ __launch_bounds__(256) void local_diag_kernel(const float *__restrict__ X, float *__restrict__ W,
-                                                         const float *__restrict__ A, const float *__restrict__ C,
-                                                         const uint32_t *__restrict__ nodes,
-                                                         const uint32_t *__restrict__ steps, uint64_t d, uint32_t H,
-                                                         float lr, float sigma, uint64_t seed, uint32_t event) {
-    const uint64_t f = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (f * 4 >= d) return;
+__global__ __launch_bounds__(WAVES * 64) void local_diag_kernel(const float *__restrict__ X, float *__restrict__ W,
+                                                                const float *__restrict__ A, const float *__restrict__ C,
+                                                                const uint32_t *__restrict__ nodes,
+                                                                const uint32_t *__restrict__ steps, uint64_t d, uint32_t H,
+                                                                float lr, float sigma, uint64_t seed, uint32_t event) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    if (tile * TILE >= d) return;
+    const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
+    const bool inA = kA < d, inB = kB < d;
+    const uint64_t lA = inA ? kA : d - 4, lB = inB ? kB : d - 4;   // past the row end: re-read its last float4
     const uint32_t node = nodes ? nodes[blockIdx.y] : blockIdx.y;
-    const uint64_t off = (uint64_t)node * d + f * 4;
-    f4 w = __builtin_nontemporal_load((const f4 *)(X + off));
-    const f4 a = __builtin_nontemporal_load((const f4 *)(A + off));
-    const f4 c = __builtin_nontemporal_load((const f4 *)(C + off));
-    w = diag_steps<NOISE>(w, a, c, node, f, steps ? steps[node] : H, lr, sigma, seed, event);
-    __builtin_nontemporal_store(w, (f4 *)(W + off));
+    const uint64_t off = (uint64_t)node * d;
+    f4 wA = ldg_nt(X + off + lA), wB = ldg_nt(X + off + lB);
+    const f4 aA = ldg_nt(A + off + lA), aB = ldg_nt(A + off + lB);
+    const f4 cA = ldg_nt(C + off + lA), cB = ldg_nt(C + off + lB);
+    diag_steps<NOISE>(wA, wB, aA, aB, cA, cB, node, tile, lane, steps ? steps[node] : H, lr, sigma, seed, event);
+    if (inA) stg_nt(W + off + kA, wA);
+    if (inB) stg_nt(W + off + kB, wB);
 }
 
 hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const uint32_t *nodes,
                              const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
                              uint32_t event, hipStream_t st) {
     if (count == 0) return hipSuccess;
-    const dim3 grid((unsigned)((d / 4 + 255) / 256), count, 1);
+    const uint64_t tiles = (d + TILE - 1) / TILE;
+    const dim3 grid((unsigned)((tiles + WAVES - 1) / WAVES), count, 1);
     if (sigma != 0.0f)
-        local_diag_kernel<true><<<grid, 256, 0, st>>>(X, W, a, c, nodes, steps, d, H, lr, sigma, seed, event);
+        local_diag_kernel<true><<<grid, WAVES * 64, 0, st>>>(X, W, a, c, nodes, steps, d, H, lr, sigma, seed, event);
     else
-        local_diag_kernel<false><<<grid, 256, 0, st>>>(X, W, a, c, nodes, steps, d, H, lr, sigma, seed, event);
+        local_diag_kernel<false><<<grid, WAVES * 64, 0, st>>>(X, W, a, c, nodes, steps, d, H, lr, sigma, seed, event);
     return hipGetLastError();
 }
 

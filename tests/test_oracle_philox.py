@@ -102,7 +102,7 @@ def test_normals_moments_and_window():
 
 def test_normals_box_muller_by_hand():
     """One call written out: u1=(w0>>8 +1)/2^24, u2=(w1>>8)/2^24."""
-    w = [int(x[0]) for x in rng.stream(9, rng.TAG_NOISE, 0, 4, 6, np.array([10]))]
+    w = [int(x[0]) for x in rng.stream(9, rng.TAG_DATA, 0, 4, 6, np.array([10]))]
     z = rng.normals(9, 4, 6, 0, 40, 44)
     import math
     for pair in range(2):
@@ -111,6 +111,42 @@ def test_normals_box_muller_by_hand():
         r = math.sqrt(-2 * math.log(u1))
         assert z[2 * pair] == pytest.approx(r * math.cos(2 * math.pi * u2), abs=1e-12)
         assert z[2 * pair + 1] == pytest.approx(r * math.sin(2 * math.pi * u2), abs=1e-12)
+
+
+def test_noise_normals_law_and_window():
+    """The gradient noise is standard normal: moments, a Kolmogorov-Smirnov test against
+    the normal CDF (scipy), no correlation inside a Box-Muller pair or between neighbours."""
+    from scipy import stats
+    z = rng.noise_normals(1, 2, 3, 1, 0, 1 << 18)
+    assert abs(z.mean()) < 5 / np.sqrt(z.size)
+    assert abs(z.var() - 1) < 5 * np.sqrt(2 / z.size)
+    assert abs((z ** 3).mean()) < 0.05
+    assert abs((z ** 4).mean() - 3) < 0.1
+    assert stats.kstest(z, "norm").pvalue > 1e-3
+    assert np.abs(z).max() <= np.sqrt(34 * np.log(2))            # 16-bit radius: u1 >= 2^-17
+    pairs = z.reshape(-1, 2)
+    assert abs(np.corrcoef(pairs[:, 0], pairs[:, 1])[0, 1]) < 0.01
+    assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 0.01
+    assert abs(np.corrcoef(z[:-8], z[8:])[0, 1]) < 0.01          # neighbouring generator calls
+    assert np.array_equal(rng.noise_normals(1, 2, 3, 1, 4096, 8192), z[4096:8192])
+    for other in (rng.noise_normals(1, 2, 3, 0, 0, 64), rng.noise_normals(1, 3, 3, 1, 0, 64),
+                  rng.noise_normals(1, 2, 4, 1, 0, 64), rng.noise_normals(2, 2, 3, 1, 0, 64)):
+        assert not np.array_equal(other, z[:64])                 # step, node, event and seed all matter
+
+
+def test_noise_normals_by_hand():
+    """One generator call written out: word p -> coordinates 8g+2p (cosine) and 8g+2p+1 (sine),
+    radius from the low half, angle from the high half."""
+    import math
+    g = 10
+    w = [int(x[0]) for x in rng.stream(9, rng.TAG_NOISE, 2, 4, 6, np.array([g]))]
+    z = rng.noise_normals(9, 4, 6, 2, 8 * g, 8 * g + 8)
+    for p in range(4):
+        u1 = ((w[p] & 0xFFFF) + 0.5) / 65536
+        u2 = (w[p] >> 16) / 65536
+        r = math.sqrt(-2 * math.log(u1))
+        assert z[2 * p] == pytest.approx(r * math.cos(2 * math.pi * u2), abs=1e-12)
+        assert z[2 * p + 1] == pytest.approx(r * math.sin(2 * math.pi * u2), abs=1e-12)
 
 
 def test_scaled_index_is_floor_u_times_m():
