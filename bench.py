@@ -262,10 +262,17 @@ def main():
         other_m = measure(torch, s, step_two_calls if use_one_pass else step_one_pass, args.steps, 3)
     one_m, two_m = (main_m, other_m) if use_one_pass else (other_m, main_m)
 
+    # Pairs whose reads are both stale are processed node by node (two grid rows per pair); every
+    # other class goes through the pair kernels.
+    all_stale = cfg.get("stale") == "fixed1"
+    k_round = ("fused_nodes_kernel" if all_stale else "fused_pairs_kernel") + \
+        " (H local steps + quantize/exchange/decode/average, one pass)"
+    k_gossip = ("gossip_nodes_kernel" if all_stale else "gossip_pairs_kernel") + " (quantize/exchange/decode/average)"
+
     def two_call_report(m):
         t = m["times"]
         rep = {"interactions_per_s": m["interactions"] / m["dt"], "ms_per_step": m["dt"] / args.steps * 1e3,
-               "gossip_pass": roofline("gossip", "gossip_pairs_kernel (quantize/exchange/decode/average)", cfg, m, d,
+               "gossip_pass": roofline("gossip", k_gossip, cfg, m, d,
                                        args.inplace),
                "local_steps_ms_per_round": t["local_ms"] / max(1, t["local_calls"])}
         if cfg["objective"] == "mlp":
@@ -279,10 +286,9 @@ def main():
         return rep
 
     if use_one_pass:
-        roof = roofline("round", "fused_pairs_kernel (H local steps + quantize/exchange/decode/average, one pass)",
-                        cfg, main_m, d)
+        roof = roofline("round", k_round, cfg, main_m, d)
     else:
-        roof = roofline("gossip", "gossip_pairs_kernel (quantize/exchange/decode/average)", cfg, main_m, d)
+        roof = roofline("gossip", k_gossip, cfg, main_m, d)
     out = {
         "metric": "node-interactions/sec + gossip-avg HBM GB/s (% of peak), n=64 d=25.6M",
         "value": main_m["interactions"] / main_m["dt"],
@@ -307,7 +313,7 @@ def main():
     if one_m is not None and not use_one_pass:
         out["one_pass_round"] = {"interactions_per_s": one_m["interactions"] / one_m["dt"],
                                  "ms_per_step": one_m["dt"] / args.steps * 1e3,
-                                 "roofline": roofline("round", "fused_pairs_kernel", cfg, one_m, d)}
+                                 "roofline": roofline("round", k_round, cfg, one_m, d)}
     # Measured ceiling: a plain streaming copy kernel over one model matrix worth of bytes.
     src = s.models_view(swarm.COMM)
     dst = torch.empty_like(src)
@@ -321,21 +327,19 @@ def main():
     copy_gbs = 2.0 * src.numel() * 4 * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     out["roofline"]["copy_kernel_GBps"] = copy_gbs
     out["roofline"]["frac_of_copy"] = out["roofline"]["achieved"] / copy_gbs
-    # The same copy with as many concurrent float streams as the timed kernel touches (bandwidth on this
-    # part falls with the number of streams): 6 read + 2 write for the one-pass round, 4 + 2 for the gossip pass.
-    n_read = 6 if use_one_pass else 4
-    rows = max(1, min(n // n_read, n // 2))                      # rows of the model matrix per stream
-    stream_bytes = rows * d * 4
-    if n_read * stream_bytes <= src.numel() * 4 and 2 * stream_bytes <= dst.numel() * 4:
-        swarm.stream_mix(dst, src, stream_bytes, n_read, 2)
-        ev0.record()
-        for _ in range(5):
-            swarm.stream_mix(dst, src, stream_bytes, n_read, 2)
-        ev1.record()
-        torch.cuda.synchronize()
-        mix_gbs = (n_read + 2) * stream_bytes * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-        out["roofline"]["same_stream_count_copy_GBps"] = mix_gbs
-        out["roofline"]["frac_of_same_stream_count_copy"] = out["roofline"]["achieved"] / mix_gbs
+    # The same copy with the float streams one node of the timed kernel touches: 3 reads (X, a, c) and one
+    # write for the one-pass round, 2 reads (X, W) and one write for the gossip pass.
+    n_read = 3 if use_one_pass else 2
+    stream_bytes = (n // n_read) * d * 4                         # each stream is a block of rows of the model matrix
+    swarm.stream_mix(dst, src, stream_bytes, n_read, 1)
+    ev0.record()
+    for _ in range(5):
+        swarm.stream_mix(dst, src, stream_bytes, n_read, 1)
+    ev1.record()
+    torch.cuda.synchronize()
+    mix_gbs = (n_read + 1) * stream_bytes * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    out["roofline"]["same_streams_copy_GBps"] = mix_gbs
+    out["roofline"]["frac_of_same_streams_copy"] = out["roofline"]["achieved"] / mix_gbs
     del dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, edges, a, c, eps)

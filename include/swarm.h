@@ -224,7 +224,8 @@ swarm_status swarm_stream_copy(void *dst_dev, const void *src_dev, uint64_t nbyt
 
 /* Measurement aid: the same streaming access with n_read concurrent read streams (consecutive
  * blocks of stream_bytes in src_dev) summed into n_write write streams (consecutive blocks in
- * dst_dev).  Shapes (n_read, n_write): (2,2), (4,2), (6,2).  stream_bytes a multiple of 16. */
+ * dst_dev; write stream w holds the sum plus w).  Shapes (n_read, n_write): (2,1), (3,1), (2,2),
+ * (4,2), (6,2); others return SWARM_EINVAL.  stream_bytes a multiple of 16. */
 swarm_status swarm_stream_mix(void *dst_dev, const void *src_dev, uint64_t stream_bytes, uint32_t n_read,
                               uint32_t n_write, void *hip_stream);
 

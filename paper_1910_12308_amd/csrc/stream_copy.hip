@@ -40,6 +40,8 @@ hipError_t launch_stream_mix(const void *src, void *dst, uint64_t stream_bytes, 
     if (n_read == 4 && n_write == 2) stream_mix_kernel<4, 2><<<blocks, 256, 0, st>>>(s, d, n4, n4);
     else if (n_read == 6 && n_write == 2) stream_mix_kernel<6, 2><<<blocks, 256, 0, st>>>(s, d, n4, n4);
     else if (n_read == 2 && n_write == 2) stream_mix_kernel<2, 2><<<blocks, 256, 0, st>>>(s, d, n4, n4);
+    else if (n_read == 3 && n_write == 1) stream_mix_kernel<3, 1><<<blocks, 256, 0, st>>>(s, d, n4, n4);
+    else if (n_read == 2 && n_write == 1) stream_mix_kernel<2, 1><<<blocks, 256, 0, st>>>(s, d, n4, n4);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

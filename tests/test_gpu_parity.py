@@ -636,3 +636,28 @@ def test_algorithm1_all_code_widths_and_decode_failure(gpu, bits):
     assert cnt["decode_failures"] == c.decode_failures and cnt["interactions"] == 5
     if bits in (2, 4):
         assert c.decode_failures > 0
+
+
+def test_copy_measurement_aids(gpu):
+    """The copy kernels the bandwidth figures are compared with move what they claim: stream_copy is a
+    copy; stream_mix sums its read streams (float32, in order) into every write stream, plus the
+    stream's number; an unsupported shape is an error, not a launch."""
+    gen = np.random.Generator(np.random.PCG64(5))
+    m = 4 * 1000 + 4                                       # floats per stream: several workgroups and a tail
+    src = gen.standard_normal(6 * m).astype(np.float32)
+    s = torch.from_numpy(src).cuda()
+    out = torch.zeros(2 * m, dtype=torch.float32, device="cuda")
+    gpu.stream_copy(out, s[:2 * m])
+    assert np.array_equal(out.cpu().numpy(), src[:2 * m])
+    for n_read, n_write in [(2, 1), (3, 1), (2, 2), (4, 2), (6, 2)]:
+        out.zero_()
+        gpu.stream_mix(out, s, 4 * m, n_read, n_write)
+        want = np.zeros(m, dtype=np.float32)
+        for r in range(n_read):
+            want = want + src[r * m:(r + 1) * m]
+        got = out.cpu().numpy()
+        for w in range(n_write):
+            assert np.array_equal(got[w * m:(w + 1) * m], want + np.float32(w)), (n_read, n_write, w)
+        assert not got[n_write * m:].any()
+    with pytest.raises(gpu.SwarmError):
+        gpu.stream_mix(out, s, 4 * m, 5, 1)
