@@ -35,13 +35,15 @@ def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace=
     return reads + 8 + 2 * bits / 8 + stale_fraction * 2 * bits / 8
 
 
-def build_workload(cfg_id, scale_d=None):
+def build_workload(cfg_id, scale_d=None, steps_H=None):
     import numpy as np
     import torch
     import workloads as wl
     cfg = dict(wl.CONFIGS[cfg_id])
     if scale_d:
         cfg["d"] = scale_d
+    if steps_H:
+        cfg["H"] = steps_H
     n, d = cfg["n"], cfg["d"]
     if cfg["graph"] == "regular4":
         edges = wl.random_regular_graph(n, 4, 0)
@@ -215,6 +217,8 @@ def main():
                     help="in-place apply mode (local steps update the exchanged model; one matrix) instead of the "
                          "paper's deferred apply")
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
+    ap.add_argument("--H", type=int, default=None,
+                    help="override the number of local steps (to find where a kernel turns ALU-bound)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build simulates the whole swarm on ONE GPU; --gpus must be 1 "
@@ -223,7 +227,7 @@ def main():
     import paper_1910_12308_amd as swarm
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    cfg, edges, a, c = build_workload(args.config, args.d)
+    cfg, edges, a, c = build_workload(args.config, args.d, args.H)
     n, d, bits = cfg["n"], cfg["d"], cfg["bits"]
     eps = eps_for(cfg)
     if cfg["objective"] == "mlp":
