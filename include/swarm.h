@@ -55,8 +55,19 @@ enum { SWARM_APPLY_DEFERRED = 0, SWARM_APPLY_INPLACE = 1 };
  * for every matched pair, and the pair uses eps_ij = the smallest power of two >= m / (2^(b-1) - 3)
  * (at least 2^-100), which puts the pair inside the decoding radius, so no decode can fail.
  * Needs bits >= 4, stale_max = 0 and swarm_gossip_round (not the one-pass round or Algorithm 1);
- * unmatched nodes publish no code. */
-enum { SWARM_SCALE_FIXED = 0, SWARM_SCALE_PAIR_LINF = 1 };
+ * unmatched nodes publish no code.
+ * GLOBAL_LINF: the case where the writer does not know who will read its code, or when (appendix,
+ * quantization: second case) -- with a fixed number of bits the scale has to follow the swarm.
+ * One scale eps_r per round, kept with the ring slot its codes are written to; a reader decodes a
+ * code of age s on the lattice eps_(r-s) Z it was written on and averages the two lattice points each
+ * at its own scale, X_i' = (eps_r z_i + eps_(r-s) z_j') / 2 + pending update.  Every exchange also
+ * reports max_k |X_i[k] - eps_(r-s) z_j'[k]|; with m the largest over the round,
+ * eps_(r+1) = max(smallest power of two >= 2 m / (2^(b-1) - 3), eps_r / 2), and eps_(r+1) = eps_r
+ * after a round without pairs.  A wrapped decode reads as a distance of about the decoding radius,
+ * so a scale that is too small grows fourfold per round until decoding succeeds; no extra pass over
+ * the models and no host round trip.  cfg.eps is the first round's scale and must be a power of two;
+ * needs bits >= 4; works with stale reads, both apply modes and the one-pass round, not Algorithm 1. */
+enum { SWARM_SCALE_FIXED = 0, SWARM_SCALE_PAIR_LINF = 1, SWARM_SCALE_GLOBAL_LINF = 2 };
 
 /* Number of local steps per interaction.  CONSTANT: H for every node (the paper's experiments).
  * GEOMETRIC: each node draws H_i >= 1 afresh for every interaction from a geometric law of mean H
@@ -86,7 +97,7 @@ typedef struct {
     uint32_t apply_mode;    /* SWARM_APPLY_DEFERRED (default) or SWARM_APPLY_INPLACE           */
     uint32_t steps_law;     /* SWARM_STEPS_CONSTANT (default) or SWARM_STEPS_GEOMETRIC (H >= 1;
                                not available with the MLP objective)                           */
-    uint32_t scale_policy;  /* SWARM_SCALE_FIXED (default) or SWARM_SCALE_PAIR_LINF            */
+    uint32_t scale_policy;  /* SWARM_SCALE_FIXED (default), _PAIR_LINF or _GLOBAL_LINF         */
 } swarm_config;
 
 /* Create a handle.  x0_dev: d floats (device) copied into every node's model, or NULL
@@ -201,6 +212,11 @@ swarm_status swarm_read_codes(swarm_t h, uint32_t age, uint32_t node, uint64_t b
 swarm_status swarm_potential(swarm_t h, double *gamma_host, float *mu_dev);
 swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npairs,
                              float *linf_host);
+
+/* SWARM_SCALE_GLOBAL_LINF: the scale the next round will use and the largest disagreement
+ * max |X_i - decoded partner| of the last round that had pairs (0 before the first).  Other
+ * policies: cfg.eps and 0.  Either pointer may be NULL (host memory).  Synchronises. */
+swarm_status swarm_scale(swarm_t h, float *eps_next, float *disagreement);
 
 /* Counters since init.  interactions: pairwise interactions (the paper's unit of time);
  * bits_communicated: bits read from or written to another node's buffer; decode_failures:

@@ -36,9 +36,18 @@ class SwarmOracle:
         self.steps_law = steps_law
         # "fixed": one eps for every exchange; "pair_linf": each matched pair uses the smallest power of
         # two that puts it inside the decoding radius (the writer knows its distance to the key).
-        assert scale_policy in ("fixed", "pair_linf")
-        assert scale_policy == "fixed" or (self.bits >= 4 and self.S == 0)
+        # "global_linf": one scale per round, set from the largest disagreement the previous round's
+        # pairs saw (the writer does not know who will read its code, or when; appendix, second case
+        # of the quantization discussion -- with a fixed number of bits the scale has to follow).
+        assert scale_policy in ("fixed", "pair_linf", "global_linf")
+        assert scale_policy != "pair_linf" or (self.bits >= 4 and self.S == 0)
+        if scale_policy == "global_linf":
+            assert self.bits >= 4 and self.k0 == 0 and self.k1 == self.d
+            assert np.frexp(self.eps)[0] == 0.5, "the starting scale must be a power of two"
         self.scale_policy = scale_policy
+        self.eps_ring = [np.float32(self.eps)] * (self.S + 1)   # scale of the codes in each ring slot
+        self.eps_cur = np.float32(self.eps)                      # scale of the coming round
+        self.max_disagreement = np.float32(0.0)                  # of the last round with pairs
         self.dtype = state_dtype
         dw = self.k1 - self.k0
         self.X = np.zeros((self.n, dw), dtype=state_dtype)
@@ -181,6 +190,8 @@ class SwarmOracle:
                 zi_seen = self._read(j, i, 0, zi, eps)
                 new[i] = (zi + zj_seen) * (0.5 * eps) + self._delta(i, self.X[i])
                 new[j] = (zj + zi_seen) * (0.5 * eps) + self._delta(j, self.X[j])
+        elif self.scale_policy == "global_linf":
+            self._gossip_round_global(pairs, stale, new)
         else:
             slot = r % (self.S + 1)
             z = {}
@@ -206,11 +217,46 @@ class SwarmOracle:
         self.round += 1
         self.interactions += len(pairs)
 
+    def _gossip_round_global(self, pairs, stale, new):
+        """Round with one lattice scale per round.  Every node rounds to eps_r Z and publishes the
+        code; a reader decodes a code of age s at the scale eps_(r-s) it was written with, against
+        its own model, and averages the two lattice points each at its own scale:
+            X_i' = (eps_r z_i + eps_(r-s) z_j') / 2 + delta_i .
+        The round also records m = max over matched nodes and coordinates of
+        |X_i - eps_(r-s) z_j'| (float32): how far the decoded partner is from the key.  The next round uses
+            eps_(r+1) = max(pair_scale(2 m), eps_r / 2)        (eps_r if nobody was matched),
+        i.e. the smallest power of two that puts twice the disagreement just seen inside the
+        decoding radius, shrinking by at most a factor two per round.  A wrapped decode shows up
+        as a disagreement near the radius, so a scale that is too small grows fourfold per round."""
+        r = self.round
+        eps_r = np.float32(self.eps_cur)
+        slot = r % (self.S + 1)
+        self.eps_ring[slot] = eps_r
+        z = {}
+        for i in range(self.n):
+            z[i] = self._lattice_point(i, r, float(eps_r))
+            self.ring[slot][i] = qz.pack(qz.code(z[i], self.bits), self.bits)
+        m = np.float32(0.0)
+        for i, j in pairs:
+            for me, other in ((i, j), (j, i)):
+                age = min(int(stale[me]), r)
+                assert 0 <= age <= self.S
+                src = (r - age) % (self.S + 1)
+                eps_old = np.float32(self.eps_ring[src])
+                z_seen = self._read(me, other, src, z[other] if age == 0 else None, float(eps_old))
+                mine = z[me].astype(np.float32) * eps_r                 # float32 throughout: m decides eps
+                theirs = z_seen.astype(np.float32) * eps_old
+                m = max(m, np.abs(self.X[me].astype(np.float32) - theirs).max())
+                new[me] = (mine.astype(np.float64) + theirs.astype(np.float64)) * 0.5 + self._delta(me, self.X[me])
+        if len(pairs):
+            self.max_disagreement = np.float32(m)
+            self.eps_cur = np.float32(max(qz.pair_scale(np.float32(2.0) * m, self.bits), eps_r * np.float32(0.5)))
+
     def interact(self, i, j):
         """One step of Algorithm 1: initiator i, responder j.
             X_i' = (Q(X_i) + Q(X_j)) / 2 - eta h~_i(Xhat_i) ,  X_j' = (Q(X_i) + Q(X_j)) / 2,
         i's snapshot becomes X_i'; j's snapshot and pending steps are untouched."""
-        assert self.S == 0 and j in self.adj[i]
+        assert self.S == 0 and j in self.adj[i] and self.scale_policy == "fixed"
         t = self.interactions
         if self.H > 0 and self.objective is not None:
             self.local_steps([i], sequential=True)

@@ -18,14 +18,14 @@ OK, EINVAL, ENOMEM, EDEVICE, ESTATE, ERANGE = range(6)
 COMM, LIVE, SNAP = 0, 1, 2
 DEFERRED, INPLACE = 0, 1
 CONSTANT, GEOMETRIC = 0, 1
-SCALE_FIXED, SCALE_PAIR_LINF = 0, 1
+SCALE_FIXED, SCALE_PAIR_LINF, SCALE_GLOBAL_LINF = 0, 1, 2
 _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_ESTATE", 5: "SWARM_ERANGE"}
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
            "swarm_set_objective_mlp", "swarm_local_steps", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
            "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
-           "swarm_potential", "swarm_pair_linf", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
+           "swarm_potential", "swarm_pair_linf", "swarm_scale", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
            "swarm_stream_copy", "swarm_stream_mix", "swarm_last_error"]
 
 
@@ -72,6 +72,7 @@ def load_library():
         "swarm_read_codes": [vp, u32, u32, u64, u64, vp],
         "swarm_potential": [vp, P(ctypes.c_double), vp],
         "swarm_pair_linf": [vp, vp, u32, vp],
+        "swarm_scale": [vp, vp, vp],
         "swarm_counters": [vp, P(u64), P(u64), P(u64), P(u64)],
         "swarm_timing_reset": [vp],
         "swarm_stream_copy": [vp, vp, u64, vp],
@@ -267,6 +268,12 @@ class Swarm:
         self._check(self._lib.swarm_pair_linf(self._h, pairs.ctypes.data_as(ctypes.c_void_p), pairs.size // 2,
                                               out.ctypes.data_as(ctypes.c_void_p)))
         return out
+
+    def scale(self):
+        """(scale of the next round, largest disagreement of the last round that had pairs)."""
+        eps, far = ctypes.c_float(), ctypes.c_float()
+        self._check(self._lib.swarm_scale(self._h, ctypes.byref(eps), ctypes.byref(far)))
+        return eps.value, far.value
 
     def counters(self, raise_on_range=True):
         vals = [ctypes.c_uint64() for _ in range(4)]

@@ -71,15 +71,31 @@ __device__ __forceinline__ void fused_pair_tile(const FusedArgs &fa, const PairD
     bool clampedA = false, clampedB = false;
     int failsA = 0, failsB = 0;
     int ziA[4], ziB[4], zjA[4], zjB[4];
-    const uint64_t ciA = round_float4<BITS>(qiA, ri.a0, ri.a1, a.inv_eps, ziA, clampedA);
-    const uint64_t ciB = round_float4<BITS>(qiB, ri.b0, ri.b1, a.inv_eps, ziB, clampedB);
-    const uint64_t cjA = round_float4<BITS>(qjA, rj.a0, rj.a1, a.inv_eps, zjA, clampedA);
-    const uint64_t cjB = round_float4<BITS>(qjB, rj.b0, rj.b1, a.inv_eps, zjB, clampedB);
-    const float half_eps = 0.5f * a.eps;
-    const f4 oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, qiA, diA, a.inv_eps, half_eps, stale_i ? nullptr : zjA, failsA, clampedA);
-    const f4 oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, qiB, diB, a.inv_eps, half_eps, stale_i ? nullptr : zjB, failsB, clampedB);
-    const f4 ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, qjA, djA, a.inv_eps, half_eps, stale_j ? nullptr : ziA, failsA, clampedA);
-    const f4 ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, qjB, djB, a.inv_eps, half_eps, stale_j ? nullptr : ziB, failsB, clampedB);
+    const ReadScale rsi = read_scale(a, si, a.eps, a.inv_eps), rsj = read_scale(a, sj, a.eps, a.inv_eps);
+    const float inv_now = rsi.inv_now;
+    const uint64_t ciA = round_float4<BITS>(qiA, ri.a0, ri.a1, inv_now, ziA, clampedA);
+    const uint64_t ciB = round_float4<BITS>(qiB, ri.b0, ri.b1, inv_now, ziB, clampedB);
+    const uint64_t cjA = round_float4<BITS>(qjA, rj.a0, rj.a1, inv_now, zjA, clampedA);
+    const uint64_t cjB = round_float4<BITS>(qjB, rj.b0, rj.b1, inv_now, zjB, clampedB);
+    f4 oiA, oiB, ojA, ojB;
+    if (a.eps_slots) {                           // one scale per round: the partner's code may be on an older lattice
+        float far = 0.f;
+        oiA = averaged_mixed<BITS>(ziA, stale_i ? seenjA : cjA, qiA, diA, rsi.eps_now, rsi.eps_old, rsi.inv_old,
+                                   stale_i ? nullptr : zjA, failsA, clampedA, far);
+        oiB = averaged_mixed<BITS>(ziB, stale_i ? seenjB : cjB, qiB, diB, rsi.eps_now, rsi.eps_old, rsi.inv_old,
+                                   stale_i ? nullptr : zjB, failsB, clampedB, far);
+        ojA = averaged_mixed<BITS>(zjA, stale_j ? seeniA : ciA, qjA, djA, rsj.eps_now, rsj.eps_old, rsj.inv_old,
+                                   stale_j ? nullptr : ziA, failsA, clampedA, far);
+        ojB = averaged_mixed<BITS>(zjB, stale_j ? seeniB : ciB, qjB, djB, rsj.eps_now, rsj.eps_old, rsj.inv_old,
+                                   stale_j ? nullptr : ziB, failsB, clampedB, far);
+        report_far(a.far_bits, far);
+    } else {
+        const float half_eps = 0.5f * rsi.eps_now;
+        oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, qiA, diA, inv_now, half_eps, stale_i ? nullptr : zjA, failsA, clampedA);
+        oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, qiB, diB, inv_now, half_eps, stale_i ? nullptr : zjB, failsB, clampedB);
+        ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, qjA, djA, inv_now, half_eps, stale_j ? nullptr : ziA, failsA, clampedA);
+        ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, qjB, djB, inv_now, half_eps, stale_j ? nullptr : ziB, failsB, clampedB);
+    }
     if (inA) {
         stg_nt(xi + kA, oiA); stg_nt(xj + kA, ojA);
         store_code<BITS>(pub_i, kA / 4, ciA); store_code<BITS>(pub_j, kA / 4, cjA);
@@ -130,11 +146,20 @@ __device__ __forceinline__ void fused_node_tile(const FusedArgs &fa, uint32_t no
     bool clampedA = false, clampedB = false;
     int fails = 0;
     int zA[4], zB[4];
-    const uint64_t codeA = round_float4<BITS>(qA, r.a0, r.a1, a.inv_eps, zA, clampedA);
-    const uint64_t codeB = round_float4<BITS>(qB, r.b0, r.b1, a.inv_eps, zB, clampedB);
-    const float half_eps = 0.5f * a.eps;
-    const f4 oA = averaged<BITS>(zA, seenA, qA, dA, a.inv_eps, half_eps, nullptr, fails, clampedA);
-    const f4 oB = averaged<BITS>(zB, seenB, qB, dB, a.inv_eps, half_eps, nullptr, fails, clampedB);
+    const ReadScale rs = read_scale(a, age, a.eps, a.inv_eps);
+    const uint64_t codeA = round_float4<BITS>(qA, r.a0, r.a1, rs.inv_now, zA, clampedA);
+    const uint64_t codeB = round_float4<BITS>(qB, r.b0, r.b1, rs.inv_now, zB, clampedB);
+    f4 oA, oB;
+    if (a.eps_slots) {
+        float far = 0.f;
+        oA = averaged_mixed<BITS>(zA, seenA, qA, dA, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedA, far);
+        oB = averaged_mixed<BITS>(zB, seenB, qB, dB, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedB, far);
+        report_far(a.far_bits, far);
+    } else {
+        const float half_eps = 0.5f * rs.eps_now;
+        oA = averaged<BITS>(zA, seenA, qA, dA, rs.inv_now, half_eps, nullptr, fails, clampedA);
+        oB = averaged<BITS>(zB, seenB, qB, dB, rs.inv_now, half_eps, nullptr, fails, clampedB);
+    }
     uint8_t *pub = a.ring + a.slot_now * slot_bytes + node * a.row_bytes;
     if (inA) { stg_nt(x + kA, oA); store_code<BITS>(pub, kA / 4, codeA); }
     if (inB) { stg_nt(x + kB, oB); store_code<BITS>(pub, kB / 4, codeB); }
@@ -177,8 +202,9 @@ __global__ __launch_bounds__(FWAVES * 64) void fused_singles_kernel(const FusedA
         const LaneRandom r = row_random(a.seed, u, a.event, tile, lane);
         bool clampedA = false, clampedB = false;
         int z[4];
-        const uint64_t cA = round_float4<BITS>(INPLACE ? wA : xA, r.a0, r.a1, a.inv_eps, z, clampedA);
-        const uint64_t cB = round_float4<BITS>(INPLACE ? wB : xB, r.b0, r.b1, a.inv_eps, z, clampedB);
+        const float inv_now = read_scale(a, 0, a.eps, a.inv_eps).inv_now;
+        const uint64_t cA = round_float4<BITS>(INPLACE ? wA : xA, r.a0, r.a1, inv_now, z, clampedA);
+        const uint64_t cB = round_float4<BITS>(INPLACE ? wB : xB, r.b0, r.b1, inv_now, z, clampedB);
         uint8_t *pub = a.ring + a.slot_now * ((uint64_t)a.n * a.row_bytes) + u * a.row_bytes;
         if (inA) store_code<BITS>(pub, kA / 4, cA);
         if (inB) store_code<BITS>(pub, kB / 4, cB);

@@ -59,24 +59,37 @@ __device__ __forceinline__ void gossip_pair_tile(const GossipArgs &a, const Pair
 
     const LaneRandom ri = row_random(a.seed, ni, a.event, tile, lane);
     const LaneRandom rj = row_random(a.seed, nj, a.event, tile, lane);
+    const ReadScale rsi = read_scale(a, si, eps, inv_eps), rsj = read_scale(a, sj, eps, inv_eps);
+    const float inv_now = rsi.inv_now;
 
     bool clampedA = false, clampedB = false;     // counted per half: lanes past the row end hold a duplicate
     int failsA = 0, failsB = 0;
     int ziA[4], ziB[4], zjA[4], zjB[4];
-    const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, inv_eps, ziA, clampedA);
-    const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, inv_eps, ziB, clampedB);
-    const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, inv_eps, zjA, clampedA);
-    const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, inv_eps, zjB, clampedB);
-    const float half_eps = 0.5f * eps;
-
-    const f4 oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, xiA, di ? wiA - xiA : zero, inv_eps, half_eps,
-                                  stale_i ? nullptr : zjA, failsA, clampedA);
-    const f4 oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, xiB, di ? wiB - xiB : zero, inv_eps, half_eps,
-                                  stale_i ? nullptr : zjB, failsB, clampedB);
-    const f4 ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, xjA, dj ? wjA - xjA : zero, inv_eps, half_eps,
-                                  stale_j ? nullptr : ziA, failsA, clampedA);
-    const f4 ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, xjB, dj ? wjB - xjB : zero, inv_eps, half_eps,
-                                  stale_j ? nullptr : ziB, failsB, clampedB);
+    const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, inv_now, ziA, clampedA);
+    const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, inv_now, ziB, clampedB);
+    const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, inv_now, zjA, clampedA);
+    const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, inv_now, zjB, clampedB);
+    const f4 diA = di ? wiA - xiA : zero, diB = di ? wiB - xiB : zero;
+    const f4 djA = dj ? wjA - xjA : zero, djB = dj ? wjB - xjB : zero;
+    f4 oiA, oiB, ojA, ojB;
+    if (a.eps_slots) {                           // one scale per round: the partner's code may be on an older lattice
+        float far = 0.f;
+        oiA = averaged_mixed<BITS>(ziA, stale_i ? seenjA : cjA, xiA, diA, rsi.eps_now, rsi.eps_old, rsi.inv_old,
+                                   stale_i ? nullptr : zjA, failsA, clampedA, far);
+        oiB = averaged_mixed<BITS>(ziB, stale_i ? seenjB : cjB, xiB, diB, rsi.eps_now, rsi.eps_old, rsi.inv_old,
+                                   stale_i ? nullptr : zjB, failsB, clampedB, far);
+        ojA = averaged_mixed<BITS>(zjA, stale_j ? seeniA : ciA, xjA, djA, rsj.eps_now, rsj.eps_old, rsj.inv_old,
+                                   stale_j ? nullptr : ziA, failsA, clampedA, far);
+        ojB = averaged_mixed<BITS>(zjB, stale_j ? seeniB : ciB, xjB, djB, rsj.eps_now, rsj.eps_old, rsj.inv_old,
+                                   stale_j ? nullptr : ziB, failsB, clampedB, far);
+        report_far(a.far_bits, far);
+    } else {
+        const float half_eps = 0.5f * rsi.eps_now;
+        oiA = averaged<BITS>(ziA, stale_i ? seenjA : cjA, xiA, diA, inv_now, half_eps, stale_i ? nullptr : zjA, failsA, clampedA);
+        oiB = averaged<BITS>(ziB, stale_i ? seenjB : cjB, xiB, diB, inv_now, half_eps, stale_i ? nullptr : zjB, failsB, clampedB);
+        ojA = averaged<BITS>(zjA, stale_j ? seeniA : ciA, xjA, djA, inv_now, half_eps, stale_j ? nullptr : ziA, failsA, clampedA);
+        ojB = averaged<BITS>(zjB, stale_j ? seeniB : ciB, xjB, djB, inv_now, half_eps, stale_j ? nullptr : ziB, failsB, clampedB);
+    }
     if (inA) {
         stg_nt(xi + kA, oiA); stg_nt(xj + kA, ojA);
         store_code<BITS>(pub_i, kA / 4, ciA); store_code<BITS>(pub_j, kA / 4, cjA);
@@ -108,14 +121,24 @@ __device__ __forceinline__ void gossip_node_tile(const GossipArgs &a, uint32_t n
     const uint8_t *src = a.ring + ((a.slot_now + a.ring_depth - age) % a.ring_depth) * slot_bytes + partner * a.row_bytes;
     const uint64_t seenA = load_code<BITS>(src, lA / 4), seenB = load_code<BITS>(src, lB / 4);
     const LaneRandom r = row_random(a.seed, node, a.event, tile, lane);
+    const ReadScale rs = read_scale(a, age, a.eps, a.inv_eps);
     bool clampedA = false, clampedB = false;
     int fails = 0;
     int zA[4], zB[4];
-    const uint64_t codeA = round_float4<BITS>(xA, r.a0, r.a1, a.inv_eps, zA, clampedA);
-    const uint64_t codeB = round_float4<BITS>(xB, r.b0, r.b1, a.inv_eps, zB, clampedB);
-    const float half_eps = 0.5f * a.eps;
-    const f4 oA = averaged<BITS>(zA, seenA, xA, delta ? wA - xA : zero, a.inv_eps, half_eps, nullptr, fails, clampedA);
-    const f4 oB = averaged<BITS>(zB, seenB, xB, delta ? wB - xB : zero, a.inv_eps, half_eps, nullptr, fails, clampedB);
+    const uint64_t codeA = round_float4<BITS>(xA, r.a0, r.a1, rs.inv_now, zA, clampedA);
+    const uint64_t codeB = round_float4<BITS>(xB, r.b0, r.b1, rs.inv_now, zB, clampedB);
+    const f4 dA = delta ? wA - xA : zero, dB = delta ? wB - xB : zero;
+    f4 oA, oB;
+    if (a.eps_slots) {
+        float far = 0.f;
+        oA = averaged_mixed<BITS>(zA, seenA, xA, dA, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedA, far);
+        oB = averaged_mixed<BITS>(zB, seenB, xB, dB, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedB, far);
+        report_far(a.far_bits, far);
+    } else {
+        const float half_eps = 0.5f * rs.eps_now;
+        oA = averaged<BITS>(zA, seenA, xA, dA, rs.inv_now, half_eps, nullptr, fails, clampedA);
+        oB = averaged<BITS>(zB, seenB, xB, dB, rs.inv_now, half_eps, nullptr, fails, clampedB);
+    }
     uint8_t *pub = a.ring + a.slot_now * slot_bytes + node * a.row_bytes;
     if (inA) { stg_nt(x + kA, oA); store_code<BITS>(pub, kA / 4, codeA); }
     if (inB) { stg_nt(x + kB, oB); store_code<BITS>(pub, kB / 4, codeB); }
@@ -187,8 +210,9 @@ __global__ __launch_bounds__(WAVES * 64) void gossip_singles_kernel(const Gossip
         const LaneRandom r = row_random(a.seed, u, a.event, tile, lane);
         bool clamped = false;
         int zA[4], zB[4];
-        const uint64_t cA = round_float4<BITS>(xA, r.a0, r.a1, a.inv_eps, zA, clamped);
-        const uint64_t cB = round_float4<BITS>(xB, r.b0, r.b1, a.inv_eps, zB, clamped);
+        const float inv_now = read_scale(a, 0, a.eps, a.inv_eps).inv_now;
+        const uint64_t cA = round_float4<BITS>(xA, r.a0, r.a1, inv_now, zA, clamped);
+        const uint64_t cB = round_float4<BITS>(xB, r.b0, r.b1, inv_now, zB, clamped);
         uint8_t *pub = a.ring + a.slot_now * ((uint64_t)a.n * a.row_bytes) + u * a.row_bytes;
         if (inA) store_code<BITS>(pub, kA / 4, cA);
         if (inB) store_code<BITS>(pub, kB / 4, cB);

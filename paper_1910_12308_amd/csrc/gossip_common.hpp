@@ -89,6 +89,50 @@ __device__ __forceinline__ f4 averaged(const int z_own[4], uint64_t partner_code
     return f4{o[0], o[1], o[2], o[3]};
 }
 
+// The same with one lattice scale per round: the partner's code was written at eps_old, the own
+// point at eps_now; far collects max |key - eps_old z_j'|, from which the next round's scale is set.
+template <int BITS>
+__device__ __forceinline__ f4 averaged_mixed(const int z_own[4], uint64_t partner_code, f4 key, f4 delta,
+                                             float eps_now, float eps_old, float inv_old, const int *z_true,
+                                             int &fails, bool &clamped, float &far) {
+    constexpr uint32_t MASK = (uint32_t)((1ull << BITS) - 1);
+    const float k[4] = {key.x, key.y, key.z, key.w};
+    const float dl[4] = {delta.x, delta.y, delta.z, delta.w};
+    float o[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int zp = decode_near<BITS>((uint32_t)(partner_code >> (m * BITS)) & MASK,
+                                         key_cell(k[m], inv_old, clamped));
+        if (z_true) fails += (zp != z_true[m]);
+        const float mine = (float)z_own[m] * eps_now, theirs = (float)zp * eps_old;
+        far = fmaxf(far, fabsf(k[m] - theirs));
+        o[m] = (mine + theirs) * 0.5f + dl[m];
+    }
+    return f4{o[0], o[1], o[2], o[3]};
+}
+
+// Largest disagreement of the wave into the round's maximum (float bits order like the floats: all >= 0).
+__device__ __forceinline__ void report_far(uint32_t *far_bits, float far) {
+    for (int off = 32; off > 0; off >>= 1) far = fmaxf(far, __shfl_xor(far, off));
+    if ((threadIdx.x & 63) == 0) {
+        const uint32_t b = __float_as_uint(far);
+        if (b > __atomic_load_n(far_bits, __ATOMIC_RELAXED)) atomicMax(far_bits, b);
+    }
+}
+
+// Scales of one read under the per-round policy (eps_slots not null), else the fixed ones.
+struct ReadScale { float eps_now, inv_now, eps_old, inv_old; };
+__device__ __forceinline__ ReadScale read_scale(const GossipArgs &a, uint32_t age, float eps, float inv_eps) {
+    ReadScale s{eps, inv_eps, eps, inv_eps};
+    if (a.eps_slots) {
+        s.eps_now = a.eps_slots[a.slot_now];
+        s.eps_old = a.eps_slots[(a.slot_now + a.ring_depth - age) % a.ring_depth];
+        s.inv_now = 1.0f / s.eps_now;      // powers of two: exact
+        s.inv_old = 1.0f / s.eps_old;
+    }
+    return s;
+}
+
 __device__ __forceinline__ void report(DeviceCounters *c, int fails, bool clamped) {
     if (__builtin_expect(__any(fails != 0), 0)) {
         for (int off = 32; off > 0; off >>= 1) fails += __shfl_xor(fails, off);

@@ -32,6 +32,9 @@ struct GossipArgs {
     const uint32_t *singles;  // device: unmatched nodes (node id | SINGLE_PENDING)
     const uint32_t *pair_linf; // device: bits of max_k |X_i - X_j| per pair (same order as pairs), or
                               // null when the lattice scale is fixed
+    const float *eps_slots;   // device: lattice scale of the codes in each ring slot (one scale per round), or
+                              // null when the scale is fixed or per pair
+    uint32_t *far_bits;       // device: float bits of the round's largest |key - decoded partner| (with eps_slots)
     DeviceCounters *counters;
     uint64_t d;
     uint64_t row_bytes;       // d * bits / 8
@@ -62,6 +65,13 @@ hipError_t launch_dequantize(const uint8_t *codes, const float *key, uint64_t d,
 hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const uint32_t *nodes,
                              const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
                              uint32_t event, hipStream_t st);
+
+// One lattice scale per round: state[0] = float bits of the coming round's scale, state[1] = float bits of
+// the largest disagreement seen by the round in flight, state[2] = the same of the last round with pairs.
+// Closes a round: next scale = max(pair_scale(2 m), eps / 2) if the round had pairs, written to the next
+// ring slot's entry of eps_slots; clears state[1].
+hipError_t launch_scale_close(float *eps_slots, uint32_t *state, uint32_t slot_now, uint32_t ring_depth,
+                              uint32_t bits, uint32_t npairs, hipStream_t st);
 
 // Reductions.
 hipError_t launch_potential(const float *X, uint32_t n, uint64_t d, float *mu, double *partials,

@@ -5,6 +5,7 @@
 // workgroup; the per-workgroup partials are summed by one last workgroup in a fixed
 // order, so the result does not depend on scheduling.
 #include "internal.h"
+#include "quant.hpp"
 
 namespace swarm {
 
@@ -106,6 +107,30 @@ hipError_t launch_pair_linf_desc(const float *X, uint64_t d, const PairDesc *pai
     if (npairs == 0) return hipSuccess;
     const dim3 grid((unsigned)((d / 4 + RB - 1) / RB), npairs, 1);
     pair_linf_kernel<true><<<grid, RB, 0, st>>>(X, d, (const uint32_t *)pairs, linf_bits);
+    return hipGetLastError();
+}
+
+// One lattice scale per round.  After a round: the largest |key - decoded partner| it saw sets the
+// next round's scale, the smallest power of two that puts twice that distance inside the decoding
+// radius, but no less than half the current scale (a round without pairs keeps the scale).
+__global__ void scale_close_kernel(float *eps_slots, uint32_t *state, uint32_t slot_now, uint32_t ring_depth,
+                                   uint32_t bits, uint32_t npairs) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const float eps = eps_slots[slot_now];
+    float next = eps;
+    if (npairs) {
+        const float m = __uint_as_float(state[1]);
+        next = fmaxf(pair_scale(2.0f * m, (int)bits), 0.5f * eps);
+        state[2] = state[1];
+    }
+    state[0] = __float_as_uint(next);
+    state[1] = 0u;
+    eps_slots[(slot_now + 1) % ring_depth] = next;
+}
+
+hipError_t launch_scale_close(float *eps_slots, uint32_t *state, uint32_t slot_now, uint32_t ring_depth,
+                              uint32_t bits, uint32_t npairs, hipStream_t st) {
+    scale_close_kernel<<<1, 64, 0, st>>>(eps_slots, state, slot_now, ring_depth, bits, npairs);
     return hipGetLastError();
 }
 

@@ -40,6 +40,8 @@ struct swarm_ctx {
     uint8_t *ring = nullptr;
     uint32_t *edges_dev = nullptr, *prio_dev = nullptr, *counts_dev = nullptr, *nodes_dev = nullptr;
     uint32_t *linf_dev = nullptr, *steps_dev = nullptr;   // steps_dev: local steps per node id (geometric law)
+    float *eps_slots_dev = nullptr;     // one scale per round: scale of the codes in each ring slot
+    uint32_t *scale_state_dev = nullptr; // [0] next scale, [1] disagreement of the round in flight, [2] of the last
     uint8_t *desc_dev = nullptr;                 // PairDesc[n/2] | singles[n]
     DeviceCounters *counters_dev = nullptr;
     double *partials_dev = nullptr, *gamma_dev = nullptr;
@@ -100,6 +102,8 @@ GossipArgs gossip_args(swarm_t h, uint32_t event, uint32_t slot) {
     a.d = h->cfg.d; a.row_bytes = h->row_bytes; a.seed = h->cfg.seed;
     a.n = h->cfg.n; a.event = event; a.slot_now = slot; a.ring_depth = h->cfg.stale_max + 1;
     a.eps = h->cfg.eps; a.inv_eps = h->inv_eps;
+    a.eps_slots = h->eps_slots_dev;
+    a.far_bits = h->scale_state_dev ? h->scale_state_dev + 1 : nullptr;
     return a;
 }
 
@@ -236,7 +240,12 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     if (cfg->steps_law > SWARM_STEPS_GEOMETRIC) return fail(nullptr, SWARM_EINVAL, "unknown law of the local steps");
     if (cfg->steps_law == SWARM_STEPS_GEOMETRIC && cfg->H == 0)
         return fail(nullptr, SWARM_EINVAL, "a geometric number of local steps needs mean H >= 1");
-    if (cfg->scale_policy > SWARM_SCALE_PAIR_LINF) return fail(nullptr, SWARM_EINVAL, "unknown scale policy");
+    if (cfg->scale_policy > SWARM_SCALE_GLOBAL_LINF) return fail(nullptr, SWARM_EINVAL, "unknown scale policy");
+    if (cfg->scale_policy == SWARM_SCALE_GLOBAL_LINF) {
+        int exponent;
+        if (cfg->bits < 4 || std::frexp(cfg->eps, &exponent) != 0.5f)
+            return fail(nullptr, SWARM_EINVAL, "the per-round scale needs bits >= 4 and a power of two as starting eps");
+    }
     if (cfg->scale_policy == SWARM_SCALE_PAIR_LINF && (cfg->bits < 4 || cfg->stale_max != 0))
         return fail(nullptr, SWARM_EINVAL, "the per-pair scale needs bits >= 4 and stale_max = 0");
     if (cfg->n > SINGLE_NODE_MASK) return fail(nullptr, SWARM_EINVAL, "n exceeds 65535");
@@ -293,6 +302,15 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         SWARM_HIP(h, hipMalloc((void **)&h->nodes_dev, sizeof(uint32_t) * n));
         SWARM_HIP(h, hipMalloc((void **)&h->linf_dev, sizeof(uint32_t) * (n / 2)));
         SWARM_HIP(h, hipMalloc((void **)&h->steps_dev, sizeof(uint32_t) * n));
+        if (cfg->scale_policy == SWARM_SCALE_GLOBAL_LINF) {
+            const std::vector<float> slots(cfg->stale_max + 1, cfg->eps);
+            uint32_t state[3] = {0u, 0u, 0u};
+            std::memcpy(&state[0], &cfg->eps, sizeof(float));
+            SWARM_HIP(h, hipMalloc((void **)&h->eps_slots_dev, sizeof(float) * slots.size()));
+            SWARM_HIP(h, hipMalloc((void **)&h->scale_state_dev, sizeof(state)));
+            SWARM_HIP(h, hipMemcpy(h->eps_slots_dev, slots.data(), sizeof(float) * slots.size(), hipMemcpyHostToDevice));
+            SWARM_HIP(h, hipMemcpy(h->scale_state_dev, state, sizeof(state), hipMemcpyHostToDevice));
+        }
         SWARM_HIP(h, hipMalloc((void **)&h->desc_dev, h->desc_bytes));
         SWARM_HIP(h, hipMalloc((void **)&h->mpairs_dev, sizeof(uint32_t) * 2 * (n / 2)));
         SWARM_HIP(h, hipMalloc((void **)&h->msingles_dev, sizeof(uint32_t) * n));
@@ -342,7 +360,7 @@ swarm_status swarm_destroy(swarm_t h) {
     if (h->W == h->X) h->W = nullptr;
     void *dev[] = {h->X, h->W, h->Xhat, h->ring, h->edges_dev, h->prio_dev, h->counts_dev, h->nodes_dev,
                    h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev, h->mpairs_dev,
-                   h->msingles_dev, h->steps_dev};
+                   h->msingles_dev, h->steps_dev, h->eps_slots_dev, h->scale_state_dev};
     for (void *p : dev) if (p) (void)hipFree(p);
     for (int s = 0; s < DESC_SLOTS; ++s) {
         if (h->desc_host[s]) (void)hipHostFree(h->desc_host[s]);
@@ -499,7 +517,7 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     const swarm_config &c = h->cfg;
     const bool pair_scale_policy = c.scale_policy == SWARM_SCALE_PAIR_LINF;
     if (fused) {
-        if (pair_scale_policy) return fail(h, SWARM_ESTATE, "the one-pass round needs the fixed lattice scale");
+        if (pair_scale_policy) return fail(h, SWARM_ESTATE, "the one-pass round cannot use the per-pair lattice scale");
         if (h->kind != OBJ_DIAG) return fail(h, SWARM_ESTATE, "the fused round needs the diagonal-quadratic objective");
         if (c.bits == 0 || c.H == 0) return fail(h, SWARM_ESTATE, "the fused round needs quantized codes and H > 0");
         for (uint8_t p : h->pending)
@@ -607,6 +625,10 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
         for (uint32_t u : singles) singles_work |= h->pending[u] != 0;
         if (singles_work) SWARM_HIP(h, launch_gossip_singles(a, singles_bits, nsingles, h->stream));
     }
+
+    if (c.scale_policy == SWARM_SCALE_GLOBAL_LINF)      // the disagreement this round saw sets the next round's scale
+        SWARM_HIP(h, launch_scale_close(h->eps_slots_dev, h->scale_state_dev, a.slot_now, a.ring_depth, c.bits, npairs,
+                                        h->stream));
 
     std::fill(h->pending.begin(), h->pending.end(), 0);
     h->round += 1;
@@ -760,6 +782,19 @@ swarm_status swarm_potential(swarm_t h, double *gamma_host, float *mu_dev) {
     SWARM_HIP(h, hipMemcpyAsync(h->scalar_host, h->gamma_dev, sizeof(double), hipMemcpyDeviceToHost, h->stream));
     SWARM_HIP(h, hipStreamSynchronize(h->stream));
     *gamma_host = *h->scalar_host;
+    return SWARM_OK;
+}
+
+swarm_status swarm_scale(swarm_t h, float *eps_next, float *disagreement) {
+    if (!h) return SWARM_EINVAL;
+    uint32_t state[3] = {0u, 0u, 0u};
+    std::memcpy(&state[0], &h->cfg.eps, sizeof(float));
+    if (h->scale_state_dev) {
+        SWARM_HIP(h, hipStreamSynchronize(h->stream));
+        SWARM_HIP(h, hipMemcpy(state, h->scale_state_dev, sizeof(state), hipMemcpyDeviceToHost));
+    }
+    if (eps_next) std::memcpy(eps_next, &state[0], sizeof(float));
+    if (disagreement) std::memcpy(disagreement, &state[2], sizeof(float));
     return SWARM_OK;
 }
 

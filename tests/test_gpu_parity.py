@@ -661,3 +661,56 @@ def test_copy_measurement_aids(gpu):
         assert not got[n_write * m:].any()
     with pytest.raises(gpu.SwarmError):
         gpu.stream_mix(out, s, 4 * m, 5, 1)
+
+
+# ------------------------------------------------------------------ one lattice scale per round
+@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("bits", [4, 8])
+def test_global_linf_scale_policy(gpu, bits, fused):
+    """The scale follows the disagreement the previous round saw: too small at first (decodes wrap, the
+    scale grows), then tracking a spread that shrinks and widens again, with reads up to two rounds
+    old decoded at the scale they were written with.  Codes, the scale and the disagreement match the
+    oracle exactly in every round, models to the elementwise tolerance."""
+    n, d, H, lr, S = 10, D_RAGGED, 2, 0.1, 2
+    edges = wl.complete_graph(n)
+    a, cc = wl.diag_quadratic_data(n, d, 3, shift_sigma=0.2)
+    g, c = make_both(gpu, n, d, edges, bits, 2.0 ** -12, H, lr, S, seed=77, global_scale=True)
+    c.objective = DiagQuadratic(a, cc, 0.05)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
+    gen = np.random.Generator(np.random.PCG64(77 + bits))
+    assert g.scale() == (2.0 ** -12, 0.0)
+    matchings = [[(0, 4), (6, 1), (2, 3), (8, 9)], [(1, 2), (3, 4), (5, 6)], [], [(0, 9), (7, 1), (2, 8)],
+                 [(0, 1), (2, 3), (4, 5), (6, 7), (8, 9)], [(9, 1), (2, 7)], [(0, 5), (3, 6), (4, 8)], [(1, 5), (2, 6)],
+                 [(0, 2), (1, 3), (4, 6), (5, 7)], [(0, 3), (1, 2), (8, 5)], [(0, 4), (6, 1), (2, 3), (8, 9)],
+                 [(1, 2), (3, 4), (5, 6)], [(0, 9), (7, 1), (2, 8)], [(0, 3), (1, 2), (8, 5)]]
+    rounds = list(zip([0.02] * 6 + [0.0005] * 5 + [0.3] * 3, matchings))
+    base = models(gen, 1, d)                               # the models stay near one point: stale codes stay meaningful
+    scales = []
+    for r, (spread, pairs) in enumerate(rounds):
+        c.X[:] = base + models(gen, n, d, spread)
+        c.pending[:] = False
+        force_state(gpu, g, c)
+        stale = np.minimum(gen.integers(0, S + 1, n), r).astype(np.uint8)
+        if fused:
+            c.local_steps()
+            c.gossip_round(pairs, stale)
+            g.round_fused(pairs, stale)
+        else:
+            c.local_steps([0, 1, 2, 5])
+            g.local_steps([0, 1, 2, 5])
+            force_state(gpu, g, c)
+            c.gossip_round(pairs, stale)
+            g.gossip_round(pairs, stale)
+        for i in range(n):
+            assert np.array_equal(g.read_codes(i), ring_row(c, i)), f"codes of node {i}, round {r}"
+        assert g.scale() == (float(c.eps_cur), float(c.max_disagreement)), f"scale after round {r}"
+        assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"X after round {r}")
+        assert g.counters()["decode_failures"] == c.decode_failures
+        scales.append(float(c.eps_cur))
+    assert scales[0] == 2.0 ** -10 and c.decode_failures > 0           # wrapped decodes: fourfold growth
+    assert scales[2] == scales[1]                                      # nobody matched
+    assert scales[10] < scales[5] and scales[13] >= 8 * scales[10]     # follows the spread down and up again
+    with pytest.raises(gpu.SwarmError):
+        g.interact(0, 1)
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(n, d, edges, bits, 0.3, H, lr, 0, 0, scale_policy=gpu.SCALE_GLOBAL_LINF)   # not a power of two

@@ -473,3 +473,124 @@ def test_algorithm1_initiator_uses_the_decoded_partner_model():
     o.interact(0, 1)
     assert np.all(o.X[0] == 2.0) and np.all(o.X[1] == 2.0)          # 20 is read as 20 - 16 = 4
     assert o.decode_failures == d
+
+
+# ---------------------------------------------------------------- one lattice scale per round
+def global_oracle(n, d, bits, eps, S=0, seed=0, X=None):
+    o = SwarmOracle(n, d, wl.complete_graph(n), bits, eps, 0, 0.0, S, seed, state_dtype=np.float32,
+                    scale_policy="global_linf")
+    if X is not None:
+        o.X[:] = X
+        o.W[:] = X
+    return o
+
+
+def lattice_points(o, slot, node, key, eps):
+    """Decode a published code by hand: plain Python integers, nearest member of the residue class."""
+    codes = qz.unpack(o.ring[slot][node], o.bits, o.d)
+    out = []
+    for c, y in zip(codes.tolist(), key.tolist()):
+        k = round(float(np.float32(y) * np.float32(1.0 / eps)))           # eps is a power of two: exact
+        cands = [c + w * (1 << o.bits) for w in range((k >> o.bits) - 2, (k >> o.bits) + 3)]
+        out.append(min(cands, key=lambda v: (abs(v - k), v > k)))          # window [k - 2^(b-1), k + 2^(b-1) - 1]
+    return np.array(out, dtype=np.int64)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_global_scale_equals_the_fixed_scale_rule_while_the_scale_stands_still(bits):
+    """With every code written and read at one scale the update is the fixed-scale one,
+    eps (z_i + z_j') / 2, and the pair's sum is eps (z_i + z_j) exactly."""
+    n, d, eps = 6, 64, 2.0 ** -3
+    gen = np.random.Generator(np.random.PCG64(bits))
+    X = (gen.standard_normal((n, d)) * 0.1).astype(np.float32)
+    pairs = [(0, 3), (4, 1)]
+    g = global_oracle(n, d, bits, eps, X=X)
+    f = SwarmOracle(n, d, wl.complete_graph(n), bits, eps, 0, 0.0, 0, 0, state_dtype=np.float32)
+    f.X[:] = X
+    g.gossip_round(pairs)
+    f.gossip_round(pairs)
+    assert np.array_equal(g.X, f.X)                    # eps z / 2 is exact in float32 here
+    assert g.decode_failures == 0 and [bytes(a) for a in g.ring[0]] == [bytes(a) for a in f.ring[0]]
+    for i, j in pairs:
+        zi = lattice_points(g, 0, i, X[i], eps)
+        zj = lattice_points(g, 0, j, X[j], eps)
+        assert np.array_equal(g.X[i].astype(np.float64) + g.X[j].astype(np.float64), eps * (zi + zj))
+
+
+def test_global_scale_update_rule_by_hand():
+    """eps_(r+1) = max(2^ceil(log2(2 m / (2^(b-1) - 3))), eps_r / 2) with m recomputed from the
+    published codes in plain Python; unmatched rounds leave the scale alone."""
+    n, d, bits, eps = 4, 32, 8, 2.0 ** -6
+    gen = np.random.Generator(np.random.PCG64(11))
+    X = (gen.standard_normal((n, d)) * 0.2).astype(np.float32)
+    o = global_oracle(n, d, bits, eps, X=X)
+    o.gossip_round([])                                  # nobody matched
+    assert o.eps_cur == np.float32(eps) and o.round == 1
+    before = o.X.copy()
+    pairs = [(0, 1), (2, 3)]
+    o.gossip_round(pairs)
+    m = 0.0
+    for i, j in pairs:
+        for me, other in ((i, j), (j, i)):
+            theirs = lattice_points(o, 0, other, before[me], eps)
+            m = max(m, float(np.abs(before[me].astype(np.float64) - eps * theirs).max()))
+    assert float(o.max_disagreement) == m
+    want = 2.0 ** math.ceil(math.log2(2 * m / (2 ** (bits - 1) - 3)))
+    assert want > eps / 2                                # this case exercises the first branch
+    assert float(o.eps_cur) == want
+    # a pair in full agreement: the scale halves, no faster
+    o.X[:] = 0.25
+    o.W[:] = 0.25
+    e = float(o.eps_cur)
+    o.gossip_round(pairs)
+    assert float(o.max_disagreement) == 0.0 and float(o.eps_cur) == e / 2
+
+
+def test_global_scale_recovers_from_a_scale_that_is_too_small_or_too_large():
+    """Too small: decodes wrap, the disagreement reads as about the decoding radius and the scale
+    grows fourfold per round until the failures stop.  Too large: it halves per round.  Either
+    way it settles at the power of two next above 2 (D + eps) / (2^(b-1) - 3), D the largest
+    distance between two models (the decoded partner is within eps of the partner)."""
+    n, d, bits = 8, 256, 4
+    gen = np.random.Generator(np.random.PCG64(5))
+    base = gen.standard_normal(d).astype(np.float32)
+    spread = 0.5
+    for eps0 in (2.0 ** -12, 2.0 ** 6):
+        o = global_oracle(n, d, bits, eps0, seed=3)
+        history, fails = [], []
+        for r in range(16):
+            X = (base + gen.uniform(-spread, spread, (n, d))).astype(np.float32)
+            o.X[:] = X                                    # keep the spread alive: only the scale moves
+            o.W[:] = X
+            f0 = o.decode_failures
+            o.gossip_round(o.sample_matching())
+            history.append(float(o.eps_cur))
+            fails.append(o.decode_failures - f0)
+        ratios = [b / a for a, b in zip(history, history[1:])]
+        if eps0 < 1e-3:
+            assert fails[0] > 0 and ratios[0] == 4.0 and ratios[1] == 4.0
+        else:
+            assert fails[0] == 0 and ratios[0] == 0.5 and ratios[1] == 0.5
+        assert all(f == 0 for f in fails[8:])
+        D, levels = 2 * spread, 2 ** (bits - 1) - 3
+        for e in history[8:]:
+            assert 2 * 0.8 * D / levels <= e <= 2 * 2 * (D + e) / levels
+
+
+def test_global_scale_stale_read_uses_the_scale_the_code_was_written_with():
+    """Round 1 reads the codes of round 0 (age 1) after the scale has moved: the partner's lattice
+    point is decoded on the old lattice and averaged with the own point on the new one."""
+    n, d, bits, S = 2, 16, 8, 1
+    gen = np.random.Generator(np.random.PCG64(2))
+    X0 = (gen.standard_normal((n, d)) * 0.05).astype(np.float32)
+    o = global_oracle(n, d, bits, 2.0 ** -4, S=S, X=X0)
+    o.gossip_round([(0, 1)], stale=[0, 0])
+    e0, e1 = 2.0 ** -4, float(o.eps_cur)
+    assert e1 == e0 / 2 and o.eps_ring[0] == np.float32(e0)
+    X1 = o.X.copy()
+    o.gossip_round([(0, 1)], stale=[1, 1])
+    assert o.eps_ring[1] == np.float32(e1)
+    for me, other in ((0, 1), (1, 0)):
+        mine = lattice_points(o, 1, me, X1[me], e1)          # published this round, new scale
+        theirs = lattice_points(o, 0, other, X1[me], e0)     # last round's code, its own scale
+        assert np.array_equal(o.X[me].astype(np.float64), (e1 * mine + e0 * theirs) / 2)
