@@ -27,7 +27,10 @@ Pin status per function (what each is checked against, other than itself):
   interact (Algorithm 1)   responder receives the plain average; snapshot rule; exact
                            potential identity of the per-step lemma; wrapped value under
                            decode failure
-  local steps, diagonal    closed form w_H = c + (1-eta a)^H (w_0 - c) at sigma=0
+  local steps, diagonal    closed form w_H = c + (1-eta a)^H (w_0 - c) at sigma=0; with noise,
+                           mean and variance of w_H against the closed form of the linear recursion
+  noise_normals            one generator call written out by hand; scipy's normal law
+                           (Kolmogorov-Smirnov), moments, independence inside and across calls
   local steps, least sq.   numpy gradient A^T(Ax-b) on the same batch
   local steps, MLP         torch.autograd in float64 on the same batch
   sample_pair              every ordered edge (i, j) equally likely per 1/(n deg i), chi^2
@@ -35,6 +38,9 @@ Pin status per function (what each is checked against, other than itself):
   sample_stale             uniform on {0..S}, limited to the rounds that exist
   steps_of (geometric H)   E[H_i] = H and E[H_i^2] = 2H^2 - H (appendix, local steps)
   pair_scale               smallest power of two inside the decoding radius; no decode fails
+  scale "global_linf"      update rule recomputed from the published codes in plain Python;
+                           equals the fixed-scale rule while the scale stands still; recovers
+                           from a wrong starting scale; stale read across a scale change by hand
   apply_mode "inplace"     X_i' = (w_i + w_j)/2 with w the closed-form local-step result
   potential                definition, and the Laplacian inequality of the appendix
   whole trajectories       parity unpinned beyond the invariants above
