@@ -106,6 +106,74 @@ def dequantize(buf, key, eps, bits):
     return z.astype(np.float64) * float(F32(eps))
 
 
+# ---- multi-resolution register: a 16-bit code read by prefixes ---------------------------------
+# Proof of Corollary 2.1, second case: the writer does not know its reader's key, so it writes its
+# messages for every resolution into its own register and the reader uses only a prefix; item 3 of
+# the corollary: the first B bits suffice, B growing with log(|x - y| / eps).  Here the messages are
+# nested: the b low bits of one 16-bit residue are the b-bit code, so the register holds the 16-bit
+# code split into planes (bits 0-3, 4-7, 8-15 of every coordinate) and a reader fetches planes until
+# the decode is confirmed.  The confirmation that the interactive protocol gets from the receiver's
+# reply is a 32-bit checksum of the writer's lattice coordinates, one per tile of 512 coordinates,
+# kept beside the planes: a reader stops at the first level whose decoded tile has that checksum.
+PREFIX_LEVELS = (4, 8, 16)      # bits per coordinate known after reading 1, 2, 3 planes
+PREFIX_TILE = 512               # coordinates per checksum
+
+
+def prefix_weights(count):
+    """Odd 32-bit weight of every coordinate, by its position inside its tile."""
+    j = np.arange(count, dtype=np.uint64) % np.uint64(PREFIX_TILE)
+    return ((np.uint64(2) * j + np.uint64(1)) * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)
+
+
+def prefix_checksums(z):
+    """sum_k (z_k mod 2^32) * weight_k mod 2^32 over every tile of 512 coordinates (the last may be short)."""
+    z = np.asarray(z, dtype=np.int64)
+    terms = ((z & 0xFFFFFFFF).astype(np.uint64) * prefix_weights(z.size)) & np.uint64(0xFFFFFFFF)
+    tiles = -(-z.size // PREFIX_TILE)
+    out = np.zeros(tiles, dtype=np.uint64)
+    np.add.at(out, np.arange(z.size) // PREFIX_TILE, terms)
+    return (out & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+
+
+def prefix_register(z):
+    """Register image of a lattice point: plane of bits 0-3 (d/2 bytes), plane of bits 4-7 (d/2 bytes),
+    plane of bits 8-15 (d bytes), then the tile checksums (little-endian uint32)."""
+    z = np.asarray(z, dtype=np.int64)
+    p0 = pack(z & 15, 4)
+    p1 = pack((z >> 4) & 15, 4)
+    p2 = pack((z >> 8) & 255, 8)
+    return np.concatenate([p0, p1, p2, prefix_checksums(z).astype('<u4').view(np.uint8)])
+
+
+def prefix_read(register, key, eps):
+    """Decode a register against `key`, tile by tile, from the shortest confirmed prefix.
+
+    Returns (z', level per tile in {0, 1, 2}, confirmed per tile).  Level l uses the
+    PREFIX_LEVELS[l] low bits of every coordinate; an unconfirmed tile keeps the 16-bit decode."""
+    key = np.asarray(key, dtype=F32)
+    d = key.size
+    register = np.asarray(register, dtype=np.uint8)
+    lo = unpack(register[:d // 2], 4, d)
+    mid = unpack(register[d // 2:d], 4, d)
+    hi = unpack(register[d:2 * d], 8, d)
+    checks = register[2 * d:].view('<u4')
+    codes = (lo, lo | (mid << np.uint32(4)), lo | (mid << np.uint32(4)) | (hi << np.uint32(8)))
+    tiles = -(-d // PREFIX_TILE)
+    z = np.empty(d, dtype=np.int64)
+    level = np.zeros(tiles, dtype=np.int64)
+    confirmed = np.zeros(tiles, dtype=bool)
+    for t in range(tiles):
+        k0, k1 = t * PREFIX_TILE, min((t + 1) * PREFIX_TILE, d)
+        for l, bits in enumerate(PREFIX_LEVELS):
+            zt = decode(codes[l][k0:k1], key[k0:k1], eps, bits)
+            level[t] = l
+            if prefix_checksums(zt)[0] == checks[t]:
+                confirmed[t] = True
+                break
+        z[k0:k1] = zt
+    return z, level, confirmed
+
+
 def pair_scale(m, bits):
     """Lattice scale for a pair at max-norm distance m: the smallest power of two that is
     >= m / (2^(b-1) - 3) (and >= 2^-100), so the pair sits inside the decoding radius

@@ -16,7 +16,8 @@ from . import rng
 
 class SwarmOracle:
     def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None,
-                 k0=0, k1=None, state_dtype=np.float32, apply_mode="deferred", steps_law="constant", scale_policy="fixed"):
+                 k0=0, k1=None, state_dtype=np.float32, apply_mode="deferred", steps_law="constant", scale_policy="fixed",
+                 codec="fixed"):
         self.n, self.d = int(n), int(d)
         self.k0 = int(k0)
         self.k1 = self.d if k1 is None else int(k1)
@@ -45,6 +46,15 @@ class SwarmOracle:
             assert self.bits >= 4 and self.k0 == 0 and self.k1 == self.d
             assert np.frexp(self.eps)[0] == 0.5, "the starting scale must be a power of two"
         self.scale_policy = scale_policy
+        # "fixed": every register holds and every reader fetches b bits per coordinate.  "prefix": the
+        # register holds a 16-bit code in planes plus tile checksums and a reader fetches the shortest
+        # prefix whose decode is confirmed (proof of Corollary 2.1, second case; its item 3).
+        assert codec in ("fixed", "prefix")
+        if codec == "prefix":
+            assert self.bits == 16 and scale_policy == "fixed" and self.k0 % qz.PREFIX_TILE == 0
+        self.codec = codec
+        self.prefix_levels = np.zeros(len(qz.PREFIX_LEVELS), dtype=np.int64)   # tiles decoded at each level
+        self.prefix_unconfirmed = 0                                             # tiles no level confirmed
         self.eps_ring = [np.float32(self.eps)] * (self.S + 1)   # scale of the codes in each ring slot
         self.eps_cur = np.float32(self.eps)                      # scale of the coming round
         self.max_disagreement = np.float32(0.0)                  # of the last round with pairs
@@ -153,9 +163,19 @@ class SwarmOracle:
     def _read(self, reader, sender, slot, z_true=None, eps=None):
         """reader decodes the sender's published code against its own model."""
         eps = self.eps if eps is None else eps
+        self.range_clamped |= bool(qz.lattice_coordinate(self.X[reader], eps)[1].any())
+        if self.codec == "prefix":
+            z, level, confirmed = qz.prefix_read(self.ring[slot][sender], self.X[reader], eps)
+            dw = self.k1 - self.k0
+            widths = np.minimum(qz.PREFIX_TILE, dw - np.arange(level.size) * qz.PREFIX_TILE)   # coordinates per tile
+            self.bits_communicated += int((np.array(qz.PREFIX_LEVELS)[level] * widths).sum()) + 32 * level.size
+            self.prefix_levels += np.bincount(level, minlength=len(qz.PREFIX_LEVELS))
+            self.prefix_unconfirmed += int((~confirmed).sum())
+            if z_true is not None:
+                self.decode_failures += int((z != z_true).sum())
+            return z
         c = qz.unpack(self.ring[slot][sender], self.bits, self.k1 - self.k0)
         z = qz.decode(c, self.X[reader], eps, self.bits)
-        self.range_clamped |= bool(qz.lattice_coordinate(self.X[reader], eps)[1].any())
         self.bits_communicated += self.d * self.bits
         if z_true is not None:
             self.decode_failures += int((z != z_true).sum())
@@ -197,7 +217,8 @@ class SwarmOracle:
             z = {}
             for i in range(self.n):                          # everyone publishes Enc(X_r^i)
                 z[i] = self._lattice_point(i, r)
-                self.ring[slot][i] = qz.pack(qz.code(z[i], self.bits), self.bits)
+                self.ring[slot][i] = (qz.prefix_register(z[i]) if self.codec == "prefix"
+                                      else qz.pack(qz.code(z[i], self.bits), self.bits))
             for i, j in pairs:
                 si, sj = min(int(stale[i]), r), min(int(stale[j]), r)
                 assert 0 <= si <= self.S and 0 <= sj <= self.S
@@ -256,7 +277,7 @@ class SwarmOracle:
         """One step of Algorithm 1: initiator i, responder j.
             X_i' = (Q(X_i) + Q(X_j)) / 2 - eta h~_i(Xhat_i) ,  X_j' = (Q(X_i) + Q(X_j)) / 2,
         i's snapshot becomes X_i'; j's snapshot and pending steps are untouched."""
-        assert self.S == 0 and j in self.adj[i] and self.scale_policy == "fixed"
+        assert self.S == 0 and j in self.adj[i] and self.scale_policy == "fixed" and self.codec == "fixed"
         t = self.interactions
         if self.H > 0 and self.objective is not None:
             self.local_steps([i], sequential=True)

@@ -145,3 +145,80 @@ def test_pair_scale_is_the_smallest_power_of_two_inside_the_radius(bits):
     eps = qz.pair_scale(np.abs(x - y).max(), bits)
     z = qz.stochastic_round(x, eps, gen.integers(0, 65536, x.size))
     assert np.array_equal(qz.decode(qz.code(z, bits), y, eps, bits), z)
+
+
+# ---------------------------------------------------------------- multi-resolution register
+def lattice_and_key(seed, d, eps, distance):
+    gen = np.random.Generator(np.random.PCG64(seed))
+    x = (gen.standard_normal(d) * 3).astype(np.float32)
+    z = qz.stochastic_round(x, eps, gen.integers(0, 65536, d))
+    y = (x + gen.uniform(-distance, distance, d)).astype(np.float32)
+    return z, y
+
+
+def test_prefix_register_image_by_hand():
+    """Plane of bits 0-3 (two coordinates per byte, low nibble first), plane of bits 4-7, plane of
+    bits 8-15 (one byte per coordinate), then the checksum: sum of z * (2 j + 1) * 0x9E3779B1 mod 2^32."""
+    z = np.array([0x1234, -1, 5, 0x0FF0, 7, 0x8000, 0x00A0, 3], dtype=np.int64)
+    reg = qz.prefix_register(z)
+    assert reg[:4].tolist() == [0xF4, 0x05, 0x07, 0x30]           # nibbles 4,F | 5,0 | 7,0 | 0,3
+    assert reg[4:8].tolist() == [0xF3, 0xF0, 0x00, 0x0A]          # nibbles 3,F | 0,F | 0,0 | A,0
+    assert reg[8:16].tolist() == [0x12, 0xFF, 0x00, 0x0F, 0x00, 0x80, 0x00, 0x00]
+    want = sum((int(v) % 2 ** 32) * ((2 * j + 1) * 0x9E3779B1) for j, v in enumerate(z)) % 2 ** 32
+    assert int(reg[16:].view('<u4')[0]) == want and reg.size == 20
+
+
+def test_prefix_planes_are_the_fixed_width_codes():
+    """The b low bits of the register are the b-bit code of the same lattice point: a reader of a
+    prefix sees exactly what the fixed codec would have sent with that many bits."""
+    z, _ = lattice_and_key(1, 1024, 0.25, 1.0)
+    reg = qz.prefix_register(z)
+    d = z.size
+    assert np.array_equal(reg[:d // 2], qz.pack(qz.code(z, 4), 4))
+    lo, mid = qz.unpack(reg[:d // 2], 4, d), qz.unpack(reg[d // 2:d], 4, d)
+    assert np.array_equal(lo | (mid << 4), qz.code(z, 8))
+    assert np.array_equal(lo | (mid << 4) | (qz.unpack(reg[d:2 * d], 8, d) << 8), qz.code(z, 16))
+
+
+@pytest.mark.parametrize("cells,level", [(1.0, 0), (4.0, 0), (9.0, 1), (100.0, 1), (140.0, 2), (20000.0, 2)])
+def test_prefix_read_uses_as_many_bits_as_the_distance_needs(cells, level):
+    """Item 3 of Corollary 2.1: the bits needed grow with log(|x - y| / eps).  A key within
+    (2^(b-1) - 5/2) cells decodes with b bits; the reader stops at the first level that does, and that
+    level is the smallest whose decode equals the writer's lattice point (checked against the truth,
+    not against the checksum)."""
+    eps, d = 2.0 ** -4, 512 * 3 + 40
+    z, y = lattice_and_key(int(cells), d, eps, cells * eps)
+    zp, lev, conf = qz.prefix_read(qz.prefix_register(z), y, eps)
+    assert np.array_equal(zp, z) and conf.all()
+    assert lev.max() == level or cells in (4.0, 100.0)           # well inside a radius: may need fewer bits
+    codes16 = qz.code(z, 16)
+    for t in range(lev.size):
+        sl = slice(512 * t, min(512 * (t + 1), d))
+        ok = [np.array_equal(qz.decode(codes16[sl] & ((1 << b) - 1), y[sl], eps, b), z[sl]) for b in qz.PREFIX_LEVELS]
+        assert lev[t] == ok.index(True)
+    if cells <= 2 ** 3 - 2.5:
+        assert (lev == 0).all()
+    elif cells <= 2 ** 7 - 2.5:
+        assert (lev <= 1).all()
+
+
+def test_prefix_checksum_catches_every_single_wrapped_coordinate():
+    """A decode that fails is off by a multiple of 2^b in some coordinates; with odd weights a single
+    such coordinate always changes the checksum."""
+    z, _ = lattice_and_key(3, 512, 0.5, 1.0)
+    base = qz.prefix_checksums(z)[0]
+    for k in range(0, 512, 7):
+        for b in (4, 8):
+            for mult in (-3, -1, 1, 2):
+                w = z.copy()
+                w[k] += mult * (1 << b)
+                assert qz.prefix_checksums(w)[0] != base
+
+
+def test_prefix_read_beyond_sixteen_bits_is_reported():
+    eps, d = 2.0 ** -6, 1024
+    z, y = lattice_and_key(4, d, eps, 1.0)
+    y[700] += 40000 * eps                                        # farther than the 16-bit radius: tile 1 only
+    zp, lev, conf = qz.prefix_read(qz.prefix_register(z), y, eps)
+    assert conf.tolist() == [True, False] and lev.tolist() == [lev[0], 2]
+    assert np.array_equal(zp[:512], z[:512]) and zp[700] != z[700] and (zp[700] - z[700]) % 65536 == 0

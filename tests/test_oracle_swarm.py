@@ -594,3 +594,59 @@ def test_global_scale_stale_read_uses_the_scale_the_code_was_written_with():
         mine = lattice_points(o, 1, me, X1[me], e1)          # published this round, new scale
         theirs = lattice_points(o, 0, other, X1[me], e0)     # last round's code, its own scale
         assert np.array_equal(o.X[me].astype(np.float64), (e1 * mine + e0 * theirs) / 2)
+
+
+# ---------------------------------------------------------------- multi-resolution registers
+def prefix_oracle(n, d, eps, S=0, seed=0):
+    return SwarmOracle(n, d, wl.complete_graph(n), 16, eps, 0, 0.0, S, seed, state_dtype=np.float32, codec="prefix")
+
+
+def test_prefix_codec_matches_the_short_code_where_it_decodes_and_succeeds_where_it_fails():
+    """Close pairs: same update as the fixed 4-bit codec at 4 bits per coordinate read (+ one checksum
+    per tile).  A pair too far apart for 4 bits: the fixed codec averages with a wrapped value, the
+    prefix reader goes on to 8 bits for those tiles and decodes the sender's point."""
+    n, d, eps = 4, 2048, 2.0 ** -4
+    gen = np.random.Generator(np.random.PCG64(21))
+    X = (gen.standard_normal((1, d)) + gen.uniform(-0.1, 0.1, (n, d))).astype(np.float32)
+    X[3, 512:1024] += 1.5                                     # 24 cells away on one tile
+    pairs = [(0, 1), (2, 3)]
+    p, f = prefix_oracle(n, d, eps), SwarmOracle(n, d, wl.complete_graph(n), 4, eps, 0, 0.0, 0, 0, state_dtype=np.float32)
+    for o in (p, f):
+        o.X[:] = X
+        o.gossip_round(pairs)
+    assert np.array_equal(p.X[:2], f.X[:2]) and f.decode_failures > 0 and p.decode_failures == 0
+    assert not np.array_equal(p.X[2], f.X[2])
+    assert np.array_equal(p.X[2], p.X[3])                     # both decodes right: the pair agrees
+    assert p.prefix_levels.tolist() == [14, 2, 0] and p.prefix_unconfirmed == 0
+    assert p.bits_communicated == 14 * 512 * 4 + 2 * 512 * 8 + 16 * 32
+    assert f.bits_communicated == 4 * d * 4
+
+
+def test_prefix_codec_stale_reads_decode_after_the_models_moved():
+    """Reads two rounds old of models that drifted by tens of cells: 4 bits would wrap, the reader
+    confirms at 8 bits; nothing is left unconfirmed and the levels account for every tile read."""
+    n, d, eps, S = 6, 1024, 2.0 ** -5, 2
+    gen = np.random.Generator(np.random.PCG64(22))
+    o = prefix_oracle(n, d, eps, S=S, seed=5)
+    base = gen.standard_normal(d).astype(np.float32)
+    published = []
+    for r in range(5):
+        X = (base + r * 0.4 + gen.uniform(-0.05, 0.05, (n, d))).astype(np.float32)     # 12.8 cells per round
+        o.X[:] = X
+        published.append(X.copy())
+        pairs = [(0, 1), (2, 3), (4, 5)] if r % 2 == 0 else [(1, 2), (3, 4)]
+        stale = np.full(n, min(r, S))
+        before = o.prefix_levels.copy()
+        o.gossip_round(pairs, stale)
+        used = o.prefix_levels - before
+        assert used.sum() == 2 * len(pairs) * (d // 512)
+        if r == 0:
+            assert used.tolist() == [used.sum(), 0, 0]
+        else:
+            assert used[0] == 0 and used[1] == used.sum()     # 12.8 or 25.6 cells: beyond 4 bits, inside 8
+        for i, j in pairs:                                    # each node averaged its point with the partner's old one
+            age = min(r, S)
+            old = published[r - age]
+            for me, other in ((i, j), (j, i)):
+                assert np.abs(o.X[me] - 0.5 * (X[me] + old[other])).max() <= 1.5 * eps
+    assert o.prefix_unconfirmed == 0 and o.decode_failures == 0
