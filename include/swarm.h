@@ -69,6 +69,19 @@ enum { SWARM_APPLY_DEFERRED = 0, SWARM_APPLY_INPLACE = 1 };
  * needs bits >= 4; works with stale reads, both apply modes and the one-pass round, not Algorithm 1. */
 enum { SWARM_SCALE_FIXED = 0, SWARM_SCALE_PAIR_LINF = 1, SWARM_SCALE_GLOBAL_LINF = 2 };
 
+/* What a register holds and how much of it a reader fetches.  FIXED: b = cfg.bits bits per
+ * coordinate, all of them read.  PREFIX: multi-resolution registers (proof of Corollary 2.1, second
+ * case: the writer does not know its reader's key, so it writes the code for every resolution into
+ * its own register; item 3 of the corollary: a reader needs only a prefix whose length grows with
+ * log(|x - y| / eps)).  The register row holds the 16 low bits of every lattice coordinate as three
+ * planes -- bits 0-3 (d/2 bytes), bits 4-7 (d/2 bytes), bits 8-15 (d bytes) -- followed by one
+ * 32-bit checksum per tile of 512 coordinates, sum_j (z_j mod 2^32) (2 j + 1) 0x9E3779B1 mod 2^32
+ * with j the position in the tile.  A reader decodes a tile from 4 bits, then 8, then 16, and stops
+ * at the first level whose decoded tile has the writer's checksum (the confirmation that the
+ * interactive protocol gets from the receiver's reply); a tile that no level confirms keeps the
+ * 16-bit decode and is counted.  Needs bits = 16 and the fixed scale; rounds only (not Algorithm 1). */
+enum { SWARM_CODEC_FIXED = 0, SWARM_CODEC_PREFIX = 1 };
+
 /* Number of local steps per interaction.  CONSTANT: H for every node (the paper's experiments).
  * GEOMETRIC: each node draws H_i >= 1 afresh for every interaction from a geometric law of mean H
  * (Section 3 "Sequential model": approximates activation by independent Poisson clocks), capped
@@ -98,6 +111,7 @@ typedef struct {
     uint32_t steps_law;     /* SWARM_STEPS_CONSTANT (default) or SWARM_STEPS_GEOMETRIC (H >= 1;
                                not available with the MLP objective)                           */
     uint32_t scale_policy;  /* SWARM_SCALE_FIXED (default), _PAIR_LINF or _GLOBAL_LINF         */
+    uint32_t codec;         /* SWARM_CODEC_FIXED (default) or SWARM_CODEC_PREFIX (bits = 16)   */
 } swarm_config;
 
 /* Create a handle.  x0_dev: d floats (device) copied into every node's model, or NULL
@@ -217,6 +231,11 @@ swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npa
  * max |X_i - decoded partner| of the last round that had pairs (0 before the first).  Other
  * policies: cfg.eps and 0.  Either pointer may be NULL (host memory).  Synchronises. */
 swarm_status swarm_scale(swarm_t h, float *eps_next, float *disagreement);
+
+/* SWARM_CODEC_PREFIX: how many tile reads stopped after 4, 8 and 16 bits per coordinate since init
+ * (tiles[3], host memory) and how many tiles no level confirmed.  Zeros for the fixed codec.
+ * Synchronises. */
+swarm_status swarm_prefix_stats(swarm_t h, uint64_t *tiles, uint64_t *unconfirmed);
 
 /* Counters since init.  interactions: pairwise interactions (the paper's unit of time);
  * bits_communicated: bits read from or written to another node's buffer; decode_failures:

@@ -19,13 +19,14 @@ COMM, LIVE, SNAP = 0, 1, 2
 DEFERRED, INPLACE = 0, 1
 CONSTANT, GEOMETRIC = 0, 1
 SCALE_FIXED, SCALE_PAIR_LINF, SCALE_GLOBAL_LINF = 0, 1, 2
+CODEC_FIXED, CODEC_PREFIX = 0, 1
 _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_ESTATE", 5: "SWARM_ERANGE"}
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
            "swarm_set_objective_mlp", "swarm_local_steps", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
            "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
-           "swarm_potential", "swarm_pair_linf", "swarm_scale", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
+           "swarm_potential", "swarm_pair_linf", "swarm_scale", "swarm_prefix_stats", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
            "swarm_stream_copy", "swarm_stream_mix", "swarm_last_error"]
 
 
@@ -40,7 +41,7 @@ class _Config(ctypes.Structure):
                 ("edges", ctypes.POINTER(ctypes.c_uint32)), ("bits", ctypes.c_uint32), ("eps", ctypes.c_float),
                 ("H", ctypes.c_uint32), ("lr", ctypes.c_float), ("stale_max", ctypes.c_uint32),
                 ("seed", ctypes.c_uint64), ("apply_mode", ctypes.c_uint32), ("steps_law", ctypes.c_uint32),
-                ("scale_policy", ctypes.c_uint32)]
+                ("scale_policy", ctypes.c_uint32), ("codec", ctypes.c_uint32)]
 
 
 def load_library():
@@ -73,6 +74,7 @@ def load_library():
         "swarm_potential": [vp, P(ctypes.c_double), vp],
         "swarm_pair_linf": [vp, vp, u32, vp],
         "swarm_scale": [vp, vp, vp],
+        "swarm_prefix_stats": [vp, vp, P(u64)],
         "swarm_counters": [vp, P(u64), P(u64), P(u64), P(u64)],
         "swarm_timing_reset": [vp],
         "swarm_stream_copy": [vp, vp, u64, vp],
@@ -129,14 +131,15 @@ class Swarm:
     """One simulated swarm: n node models of dimension d on one GPU."""
 
     def __init__(self, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, x0=None, stream=None,
-                 apply_mode=DEFERRED, steps_law=CONSTANT, scale_policy=SCALE_FIXED):
+                 apply_mode=DEFERRED, steps_law=CONSTANT, scale_policy=SCALE_FIXED, codec=CODEC_FIXED):
         self._h = ctypes.c_void_p()
         self._lib = lib()
         edges = _host_u32(edges)
         self.n, self.d, self.bits, self.stale_max = int(n), int(d), int(bits), int(stale_max)
+        self.row_bytes = self.d * self.bits // 8 + (4 * ((self.d + 511) // 512) if codec == CODEC_PREFIX else 0)
         cfg = _Config(self.n, self.d, edges.size // 2, edges.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
                       self.bits, float(eps), int(H), float(lr), self.stale_max, int(seed) & 0xFFFFFFFFFFFFFFFF,
-                      int(apply_mode), int(steps_law), int(scale_policy))
+                      int(apply_mode), int(steps_law), int(scale_policy), int(codec))
         self._keep = []          # borrowed objective tensors must outlive the handle
         rc = self._lib.swarm_init(ctypes.byref(cfg), _dev_ptr(x0, torch.float32), _stream_ptr(stream),
                                   ctypes.byref(self._h))
@@ -250,8 +253,7 @@ class Swarm:
         return torch.as_tensor(_DeviceView(ptr.value, (self.n, self.d), self), device="cuda")
 
     def read_codes(self, node, age=0, byte0=0, length=None):
-        row_bytes = self.d * self.bits // 8
-        length = row_bytes - byte0 if length is None else length
+        length = self.row_bytes - byte0 if length is None else length
         out = np.empty(length, dtype=np.uint8)
         self._check(self._lib.swarm_read_codes(self._h, age, node, byte0, length,
                                                out.ctypes.data_as(ctypes.c_void_p)))
@@ -274,6 +276,12 @@ class Swarm:
         eps, far = ctypes.c_float(), ctypes.c_float()
         self._check(self._lib.swarm_scale(self._h, ctypes.byref(eps), ctypes.byref(far)))
         return eps.value, far.value
+
+    def prefix_stats(self):
+        """(tile reads that stopped after 4, 8, 16 bits per coordinate; tiles that no level confirmed)."""
+        tiles, bad = (ctypes.c_uint64 * 3)(), ctypes.c_uint64()
+        self._check(self._lib.swarm_prefix_stats(self._h, tiles, ctypes.byref(bad)))
+        return list(tiles), bad.value
 
     def counters(self, raise_on_range=True):
         vals = [ctypes.c_uint64() for _ in range(4)]

@@ -10,6 +10,9 @@ struct DeviceCounters {
     unsigned long long decode_failures;
     unsigned int range_clamped;
     unsigned int pad;
+    // multi-resolution registers: tiles read beyond the first plane (to 8 bits, to 16 bits), the
+    // coordinates in those tiles, and tiles that no level confirmed
+    unsigned long long prefix_tiles[2], prefix_coords[2], prefix_unconfirmed;
 };
 
 // One matched pair of a round.  flags: bits 0-7 = age (in rounds) of the code i reads from j,
@@ -65,6 +68,14 @@ hipError_t launch_dequantize(const uint8_t *codes, const float *key, uint64_t d,
 hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const uint32_t *nodes,
                              const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
                              uint32_t event, hipStream_t st);
+
+// Round kernels for multi-resolution registers (16-bit code in three planes plus tile checksums, read by
+// prefixes).  kind: 0 = pairs with any mix of fresh and stale reads, 1 = pairs whose reads are both stale,
+// 2 = unmatched nodes (rows = their number).  local: objective of the one-pass round, or null.
+struct DiagObjective;
+hipError_t launch_prefix(const GossipArgs &g, const DiagObjective *local, bool inplace, float lr, int kind, uint32_t rows,
+                         hipStream_t st);
+constexpr uint32_t PREFIX_TILE = 512;      // coordinates per checksum (one wave tile)
 
 // One lattice scale per round: state[0] = float bits of the coming round's scale, state[1] = float bits of
 // the largest disagreement seen by the round in flight, state[2] = the same of the last round with pairs.

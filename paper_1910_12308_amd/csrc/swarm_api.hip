@@ -65,6 +65,7 @@ struct swarm_ctx {
     MlpObjective mlp{};
 
     uint64_t round = 0, interactions = 0, bits_communicated = 0;
+    uint64_t prefix_tile_reads = 0;      // multi-resolution registers: tiles read since init
     std::vector<hipEvent_t> ev_gossip, ev_local;   // start/stop pairs, created on demand
     uint32_t timed_gossip = 0, timed_local = 0;    // recorded calls since the last reset
     std::string err;
@@ -248,6 +249,9 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     }
     if (cfg->scale_policy == SWARM_SCALE_PAIR_LINF && (cfg->bits < 4 || cfg->stale_max != 0))
         return fail(nullptr, SWARM_EINVAL, "the per-pair scale needs bits >= 4 and stale_max = 0");
+    if (cfg->codec > SWARM_CODEC_PREFIX) return fail(nullptr, SWARM_EINVAL, "unknown codec");
+    if (cfg->codec == SWARM_CODEC_PREFIX && (cfg->bits != 16 || cfg->scale_policy != SWARM_SCALE_FIXED))
+        return fail(nullptr, SWARM_EINVAL, "multi-resolution registers need bits = 16 and the fixed lattice scale");
     if (cfg->n > SINGLE_NODE_MASK) return fail(nullptr, SWARM_EINVAL, "n exceeds 65535");
     if (cfg->n_edges == 0 || !cfg->edges) return fail(nullptr, SWARM_EINVAL, "graph has no edges");
     if (cfg->n_edges > MATCHING_MAX_EDGES) return fail(nullptr, SWARM_EINVAL, "too many edges");
@@ -277,6 +281,8 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     h->stream = (hipStream_t)hip_stream;
     h->inv_eps = cfg->bits ? 1.0f / cfg->eps : 0.f;
     h->row_bytes = cfg->d * cfg->bits / 8;
+    if (cfg->codec == SWARM_CODEC_PREFIX)            // three planes (2 d bytes) and one checksum per tile
+        h->row_bytes += sizeof(uint32_t) * ((cfg->d + PREFIX_TILE - 1) / PREFIX_TILE);
     h->pending.assign(cfg->n, 0);
 
     const uint32_t n = cfg->n;
@@ -597,33 +603,48 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     const GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
     const bool inplace = c.apply_mode == SWARM_APPLY_INPLACE;
-    if (pair_scale_policy && npairs) {   // distance of every pair first, then each pair quantizes at its own scale
-        SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * npairs, h->stream));
-        SWARM_HIP(h, launch_pair_linf_desc(h->X, c.d, a.pairs, npairs, h->linf_dev, h->stream));
-    }
-    {
+    if (c.codec == SWARM_CODEC_PREFIX) {
+        // multi-resolution registers: pairs whose reads are both stale run node by node, all others through
+        // the kernel that takes any mix (the groups are laid out as fresh/fresh, stale/stale, one stale)
+        const DiagObjective *local = fused ? &h->diag : nullptr;
         GossipArgs ga = a;
-        if (pair_scale_policy) ga.pair_linf = h->linf_dev;
+        const uint32_t counts[3] = {(uint32_t)groups[0].size(), (uint32_t)groups[1].size(), (uint32_t)groups[2].size()};
         for (int gidx = 0; gidx < 3; ++gidx) {
-            const uint32_t count = (uint32_t)groups[gidx].size();
-            if (fused)
-                SWARM_HIP(h, launch_fused_pairs(ga, h->diag, c.bits, inplace, c.H, c.lr, group_mode[gidx], count, h->stream));
-            else
-                SWARM_HIP(h, launch_gossip_pairs(ga, c.bits, delta_mode, group_mode[gidx], count, h->stream));
-            ga.pairs += count;
-            if (ga.pair_linf) ga.pair_linf += count;
+            SWARM_HIP(h, launch_prefix(ga, local, inplace, c.lr, gidx == 1 ? 1 : 0, counts[gidx], h->stream));
+            ga.pairs += counts[gidx];
         }
-    }
-    SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
-    h->timed_gossip += 1;
-    // unmatched nodes: publish their code (needed by later stale reads) and apply their own steps
-    if (fused) {
-        SWARM_HIP(h, launch_fused_singles(a, h->diag, c.bits, inplace, c.H, c.lr, nsingles, h->stream));
+        SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
+        h->timed_gossip += 1;
+        SWARM_HIP(h, launch_prefix(a, local, inplace, c.lr, 2, nsingles, h->stream));
     } else {
-        const uint32_t singles_bits = pair_scale_policy ? 0u : c.bits;   // no shared scale: nothing to publish
-        bool singles_work = singles_bits != 0;
-        for (uint32_t u : singles) singles_work |= h->pending[u] != 0;
-        if (singles_work) SWARM_HIP(h, launch_gossip_singles(a, singles_bits, nsingles, h->stream));
+        if (pair_scale_policy && npairs) {   // distance of every pair first, then each pair quantizes at its own scale
+            SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * npairs, h->stream));
+            SWARM_HIP(h, launch_pair_linf_desc(h->X, c.d, a.pairs, npairs, h->linf_dev, h->stream));
+        }
+        {
+            GossipArgs ga = a;
+            if (pair_scale_policy) ga.pair_linf = h->linf_dev;
+            for (int gidx = 0; gidx < 3; ++gidx) {
+                const uint32_t count = (uint32_t)groups[gidx].size();
+                if (fused)
+                    SWARM_HIP(h, launch_fused_pairs(ga, h->diag, c.bits, inplace, c.H, c.lr, group_mode[gidx], count, h->stream));
+                else
+                    SWARM_HIP(h, launch_gossip_pairs(ga, c.bits, delta_mode, group_mode[gidx], count, h->stream));
+                ga.pairs += count;
+                if (ga.pair_linf) ga.pair_linf += count;
+            }
+        }
+        SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
+        h->timed_gossip += 1;
+        // unmatched nodes: publish their code (needed by later stale reads) and apply their own steps
+        if (fused) {
+            SWARM_HIP(h, launch_fused_singles(a, h->diag, c.bits, inplace, c.H, c.lr, nsingles, h->stream));
+        } else {
+            const uint32_t singles_bits = pair_scale_policy ? 0u : c.bits;   // no shared scale: nothing to publish
+            bool singles_work = singles_bits != 0;
+            for (uint32_t u : singles) singles_work |= h->pending[u] != 0;
+            if (singles_work) SWARM_HIP(h, launch_gossip_singles(a, singles_bits, nsingles, h->stream));
+        }
     }
 
     if (c.scale_policy == SWARM_SCALE_GLOBAL_LINF)      // the disagreement this round saw sets the next round's scale
@@ -633,7 +654,11 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     std::fill(h->pending.begin(), h->pending.end(), 0);
     h->round += 1;
     h->interactions += npairs;
-    h->bits_communicated += 2ull * npairs * c.d * (c.bits ? c.bits : 32);
+    if (c.codec == SWARM_CODEC_PREFIX)      // first plane and checksums of every read; escalations are counted on the device
+        h->bits_communicated += 2ull * npairs * (c.d * 4 + 32ull * ((c.d + PREFIX_TILE - 1) / PREFIX_TILE));
+    else
+        h->bits_communicated += 2ull * npairs * c.d * (c.bits ? c.bits : 32);
+    h->prefix_tile_reads += c.codec == SWARM_CODEC_PREFIX ? 2ull * npairs * ((c.d + PREFIX_TILE - 1) / PREFIX_TILE) : 0ull;
     return SWARM_OK;
 }
 
@@ -653,6 +678,7 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     if (c.stale_max != 0) return fail(h, SWARM_EINVAL, "Algorithm 1 steps need stale_max = 0");
     if (c.apply_mode != SWARM_APPLY_DEFERRED) return fail(h, SWARM_EINVAL, "Algorithm 1 defers the local steps");
     if (c.scale_policy != SWARM_SCALE_FIXED) return fail(h, SWARM_EINVAL, "Algorithm 1 steps use the fixed lattice scale");
+    if (c.codec != SWARM_CODEC_FIXED) return fail(h, SWARM_EINVAL, "Algorithm 1 steps use fixed-width registers");
     if (i >= c.n || j >= c.n || i == j ||
         !std::binary_search(h->edge_keys.begin(), h->edge_keys.end(), edge_key(i, j)))
         return fail(h, SWARM_EINVAL, "responder is not a neighbour of the initiator");
@@ -820,9 +846,24 @@ swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions,
     SWARM_HIP(h, hipStreamSynchronize(h->stream));
     if (rounds) *rounds = h->round;
     if (interactions) *interactions = h->interactions;
-    if (bits_communicated) *bits_communicated = h->bits_communicated;
+    if (bits_communicated)     // escalated tiles read 4 (to 8 bits) or 12 (to 16 bits) more bits per coordinate
+        *bits_communicated = h->bits_communicated + 4ull * dc->prefix_coords[0] + 12ull * dc->prefix_coords[1];
     if (decode_failures) *decode_failures = dc->decode_failures;
     if (dc->range_clamped) return fail(h, SWARM_ERANGE, "|x/eps| reached the clamp 2^29");
+    return SWARM_OK;
+}
+
+swarm_status swarm_prefix_stats(swarm_t h, uint64_t *tiles, uint64_t *unconfirmed) {
+    if (!h) return SWARM_EINVAL;
+    DeviceCounters *dc = (DeviceCounters *)h->scalar_host;
+    SWARM_HIP(h, hipMemcpyAsync(dc, h->counters_dev, sizeof(DeviceCounters), hipMemcpyDeviceToHost, h->stream));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    if (tiles) {
+        tiles[1] = dc->prefix_tiles[0];
+        tiles[2] = dc->prefix_tiles[1];
+        tiles[0] = h->prefix_tile_reads - tiles[1] - tiles[2];
+    }
+    if (unconfirmed) *unconfirmed = dc->prefix_unconfirmed;
     return SWARM_OK;
 }
 

@@ -25,16 +25,18 @@ def assert_close(gpu, cpu, tol, what=""):
 
 
 def make_both(swarm_mod, n, d, edges, bits, eps, H, lr, stale_max=0, seed=0, inplace=False, geometric=False, pair_scale=False,
-              global_scale=False):
+              global_scale=False, prefix=False):
     gpu = swarm_mod.Swarm(n, d, edges, bits, eps, H, lr, stale_max, seed,
                           apply_mode=swarm_mod.INPLACE if inplace else swarm_mod.DEFERRED,
                           steps_law=swarm_mod.GEOMETRIC if geometric else swarm_mod.CONSTANT,
                           scale_policy=(swarm_mod.SCALE_PAIR_LINF if pair_scale else
-                                        swarm_mod.SCALE_GLOBAL_LINF if global_scale else swarm_mod.SCALE_FIXED))
+                                        swarm_mod.SCALE_GLOBAL_LINF if global_scale else swarm_mod.SCALE_FIXED),
+                          codec=swarm_mod.CODEC_PREFIX if prefix else swarm_mod.CODEC_FIXED)
     cpu = SwarmOracle(n, d, edges, bits, eps, H, lr, stale_max, seed,
                       apply_mode="inplace" if inplace else "deferred",
                       steps_law="geometric" if geometric else "constant",
-                      scale_policy="pair_linf" if pair_scale else "global_linf" if global_scale else "fixed")
+                      scale_policy="pair_linf" if pair_scale else "global_linf" if global_scale else "fixed",
+                      codec="prefix" if prefix else "fixed")
     return gpu, cpu
 
 

@@ -714,3 +714,55 @@ def test_global_linf_scale_policy(gpu, bits, fused):
         g.interact(0, 1)
     with pytest.raises(gpu.SwarmError):
         gpu.Swarm(n, d, edges, bits, 0.3, H, lr, 0, 0, scale_policy=gpu.SCALE_GLOBAL_LINF)   # not a power of two
+
+
+# ------------------------------------------------------------------ multi-resolution registers
+@pytest.mark.parametrize("fused", [False, True])
+def test_prefix_codec_rounds(gpu, fused):
+    """Registers hold 16 bits per coordinate in three planes plus tile checksums; readers fetch the
+    shortest confirmed prefix.  The models drift by tens of lattice cells per round, so stale reads
+    escalate to 8 bits; one node sits hundreds of cells away (16 bits) and in one round one coordinate is
+    beyond even that (a tile nobody can confirm).  Register images, levels, unconfirmed tiles, bits read
+    and decode failures equal the oracle's; models to the elementwise tolerance."""
+    n, d, H, lr, S, eps = 10, D_RAGGED, 2, 0.1, 2, 2.0 ** -5
+    edges = wl.complete_graph(n)
+    a, cc = wl.diag_quadratic_data(n, d, 3, shift_sigma=0.2)
+    g, c = make_both(gpu, n, d, edges, 16, eps, H, lr, S, seed=91, prefix=True)
+    c.objective = DiagQuadratic(a, cc, 0.05)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
+    gen = np.random.Generator(np.random.PCG64(91))
+    base = models(gen, 1, d)
+    matchings = [[(0, 4), (6, 1), (2, 3), (8, 9)], [(1, 2), (3, 4), (5, 6)], [], [(0, 9), (7, 1), (2, 8)],
+                 [(0, 1), (2, 3), (4, 5), (6, 7), (8, 9)], [(9, 1), (2, 7)]]
+    stales = [np.zeros(n), np.ones(n), np.ones(n), np.array([2, 0, 1, 2, 0, 1, 2, 0, 1, 2]),
+              np.array([0, 0, 1, 1, 2, 0, 0, 2, 1, 0]), np.full(n, 2)]
+    for r, (pairs, stale) in enumerate(zip(matchings, stales)):
+        c.X[:] = base + 0.4 * r + models(gen, n, d, 0.02)          # 12.8 cells per round
+        c.X[9] += 20.0                                             # 640 cells from everyone: needs 16 bits
+        if r == 3:
+            c.X[7, 1000] += 3000.0                                 # 96000 cells: beyond the 16-bit radius
+        c.pending[:] = False
+        force_state(gpu, g, c)
+        stale = np.minimum(stale, r).astype(np.uint8)
+        if fused:
+            c.local_steps()
+            c.gossip_round(pairs, stale)
+            g.round_fused(pairs, stale)
+        else:
+            c.local_steps([0, 1, 2, 5])
+            g.local_steps([0, 1, 2, 5])
+            force_state(gpu, g, c)
+            c.gossip_round(pairs, stale)
+            g.gossip_round(pairs, stale)
+        for i in range(n):
+            assert np.array_equal(g.read_codes(i), ring_row(c, i)), f"register of node {i}, round {r}"
+        assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"X after round {r}")
+        tiles, unconfirmed = g.prefix_stats()
+        assert tiles == c.prefix_levels.tolist() and unconfirmed == c.prefix_unconfirmed, f"levels after round {r}"
+        cnt = g.counters()
+        assert cnt["decode_failures"] == c.decode_failures and cnt["bits_communicated"] == c.bits_communicated
+    assert c.prefix_levels[1] > 0 and c.prefix_levels[2] > 0 and c.prefix_unconfirmed > 0
+    with pytest.raises(gpu.SwarmError):
+        g.interact(0, 1)
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(n, d, edges, 8, eps, H, lr, 0, 0, codec=gpu.CODEC_PREFIX)
