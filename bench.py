@@ -27,11 +27,15 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {("gossip", 4, True): 25.99, ("round", 4, True): 33.99}
 
 
-def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace=False):
+def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace=False, prefix=False):
     """Gossip pass: read X_i, X_j, W_i, W_j (16 B), write X_i', X_j' (8 B), write two b-bit codes, read
     two b-bit partner codes when the reads are stale.  One-pass round (local steps inside the gossip
-    pass): read X, a, c of both nodes (24 B) instead of X and W; W never moves."""
+    pass): read X, a, c of both nodes (24 B) instead of X and W; W never moves.  Multi-resolution
+    registers: 16 bits and 4/512 B of checksum written per coordinate, 4 bits and the checksum read by a
+    stale reader (tiles that escalate to 8 or 16 bits are added by the caller from the library's counts)."""
     reads = (8 if inplace else 16) if kernel == "gossip" else 24    # in-place apply: no second matrix to read
+    if prefix:
+        return reads + 8 + 2 * (2 + 4 / 512) + stale_fraction * 2 * (0.5 + 4 / 512)
     return reads + 8 + 2 * bits / 8 + stale_fraction * 2 * bits / 8
 
 
@@ -114,7 +118,8 @@ def cpu_baseline(cfg, edges, a, c, eps, seconds_target=15.0):
     result = None
     while True:
         k1 = min(width, d - d % 8)
-        o = SwarmOracle(n, d, edges, cfg["bits"], eps, cfg["H"], cfg["lr"], cfg["stale_max"], 0, k0=0, k1=k1)
+        o = SwarmOracle(n, d, edges, cfg["bits"], eps, cfg["H"], cfg["lr"], cfg["stale_max"], 0, k0=0, k1=k1,
+                        codec=cfg.get("codec", "fixed"))
         o.objective = DiagQuadratic(a[:, :k1].cpu().numpy(), c[:, :k1].cpu().numpy(), cfg["sigma"], k0=0)
         o.local_steps()
         o.gossip_round(o.sample_matching())           # round 0 fills the ring so that round 1 can read stale codes
@@ -174,6 +179,7 @@ def measure(torch, s, step, steps, warmup):
         step()
     torch.cuda.synchronize()
     before = s.counters(raise_on_range=False)
+    tiles_before = s.prefix_stats()[0]
     s.timing_reset()
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -182,19 +188,23 @@ def measure(torch, s, step, steps, warmup):
     dt = time.perf_counter() - t0
     after = s.counters(raise_on_range=False)
     return dict(dt=dt, times=s.kernel_times(), interactions=after["interactions"] - before["interactions"],
-                decode_failures=after["decode_failures"] - before["decode_failures"])
+                decode_failures=after["decode_failures"] - before["decode_failures"],
+                prefix_tiles=[x - y for x, y in zip(s.prefix_stats()[0], tiles_before)])
 
 
 def roofline(kernel, name, cfg, m, d, inplace=False):
     """Algorithmic bytes of the timed launches / their summed HIP-event duration, against 8 TB/s."""
     bits, S = cfg["bits"], cfg["stale_max"]
+    prefix = cfg.get("codec") == "prefix"
     stale_fraction = {"fixed1": 1.0, "uniform": S / (S + 1.0)}.get(cfg.get("stale"), 0.0)
-    per_pc = algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace)
+    per_pc = algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace, prefix)
     launches = max(1, m["times"]["gossip_calls"])
     total = per_pc * d * m["interactions"]
+    if prefix:                                   # planes 1 and 2 of the tiles that escalated
+        total += 512 * (0.5 * (m["prefix_tiles"][1] + m["prefix_tiles"][2]) + 1.0 * m["prefix_tiles"][2])
     seconds = m["times"]["gossip_ms"] * 1e-3
     achieved = total / seconds / 1e9 if seconds > 0 else 0.0
-    measured = None if inplace else MEASURED_TRAFFIC_PER_PAIR_COORDINATE.get((kernel, bits, stale_fraction == 1.0))
+    measured = None if inplace or prefix else MEASURED_TRAFFIC_PER_PAIR_COORDINATE.get((kernel, bits, stale_fraction == 1.0))
     return {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": None if measured is None else measured * d * m["interactions"] / launches,
@@ -216,6 +226,9 @@ def main():
     ap.add_argument("--inplace", action="store_true",
                     help="in-place apply mode (local steps update the exchanged model; one matrix) instead of the "
                          "paper's deferred apply")
+    ap.add_argument("--prefix", action="store_true",
+                    help="multi-resolution registers: 16-bit codes in planes, readers fetch the shortest confirmed "
+                         "prefix (instead of the configuration's fixed b bits)")
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
     ap.add_argument("--H", type=int, default=None,
                     help="override the number of local steps (to find where a kernel turns ALU-bound)")
@@ -228,8 +241,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg, edges, a, c = build_workload(args.config, args.d, args.H)
+    if args.prefix:
+        if cfg["objective"] != "diag" or cfg["bits"] == 0:
+            raise SystemExit("bench.py: --prefix needs a configuration with the diagonal objective and quantized codes")
+    eps = eps_for(cfg)         # the configuration's scale: the first plane decodes what its b-bit code would
+    if args.prefix:
+        cfg["codec"], cfg["bits"] = "prefix", 16
     n, d, bits = cfg["n"], cfg["d"], cfg["bits"]
-    eps = eps_for(cfg)
     if cfg["objective"] == "mlp":
         x0 = 0.02 * torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0, x0=x0)
@@ -239,7 +257,8 @@ def main():
         s.set_objective_lsq(a, c, cfg["m_rows"], cfg["batch"])
     else:
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0,
-                        apply_mode=swarm.INPLACE if args.inplace else swarm.DEFERRED)
+                        apply_mode=swarm.INPLACE if args.inplace else swarm.DEFERRED,
+                        codec=swarm.CODEC_PREFIX if args.prefix else swarm.CODEC_FIXED)
         s.set_objective_diag(a, c, cfg["sigma"])
 
     def step_sequential():
@@ -269,9 +288,10 @@ def main():
     # Pairs whose reads are both stale are processed node by node (two grid rows per pair); every
     # other class goes through the pair kernels.
     all_stale = cfg.get("stale") == "fixed1"
-    k_round = ("fused_nodes_kernel" if all_stale else "fused_pairs_kernel") + \
+    form = "nodes" if all_stale else "pairs"
+    k_round = (f"prefix_{form}_kernel<local steps>" if args.prefix else f"fused_{form}_kernel") + \
         " (H local steps + quantize/exchange/decode/average, one pass)"
-    k_gossip = ("gossip_nodes_kernel" if all_stale else "gossip_pairs_kernel") + " (quantize/exchange/decode/average)"
+    k_gossip = (f"prefix_{form}_kernel" if args.prefix else f"gossip_{form}_kernel") + " (quantize/exchange/decode/average)"
 
     def two_call_report(m):
         t = m["times"]
@@ -309,7 +329,9 @@ def main():
                             else "swarm_sample_pair + swarm_interact (Algorithm 1)" if cfg["mode"] == "sequential"
                             else "swarm_local_steps + swarm_gossip_round"),
                    "pairs_per_round": main_m["interactions"] / args.steps,
-                   "decode_failures": main_m["decode_failures"]},
+                   "decode_failures": main_m["decode_failures"],
+                   **({"registers": "multi-resolution (16-bit planes, prefix reads)",
+                       "tile_reads_at_4_8_16_bits": main_m["prefix_tiles"]} if args.prefix else {})},
         "roofline": roof,
     }
     if two_m is not None:

@@ -10,10 +10,16 @@ struct DeviceCounters {
     unsigned long long decode_failures;
     unsigned int range_clamped;
     unsigned int pad;
-    // multi-resolution registers: tiles read beyond the first plane (to 8 bits, to 16 bits), the
-    // coordinates in those tiles, and tiles that no level confirmed
-    unsigned long long prefix_tiles[2], prefix_coords[2], prefix_unconfirmed;
 };
+
+// Multi-resolution registers: tiles read beyond the first plane (to 8 bits, to 16 bits), the coordinates
+// in those tiles, and tiles that no level confirmed.  Kept in PREFIX_STRIPES copies that workgroups
+// spread over, so that a round in which every tile escalates does not serialise on one address; the
+// host adds the stripes up.
+struct PrefixStats {
+    unsigned long long tiles[2], coords[2], unconfirmed, pad[3];
+};
+constexpr uint32_t PREFIX_STRIPES = 4096;
 
 // One matched pair of a round.  flags: bits 0-7 = age (in rounds) of the code i reads from j,
 // bits 8-15 = age of the code j reads from i, bit 16 / 17 = W_i / W_j carries unapplied steps.
@@ -38,6 +44,7 @@ struct GossipArgs {
     const float *eps_slots;   // device: lattice scale of the codes in each ring slot (one scale per round), or
                               // null when the scale is fixed or per pair
     uint32_t *far_bits;       // device: float bits of the round's largest |key - decoded partner| (with eps_slots)
+    PrefixStats *prefix_stats; // device: PREFIX_STRIPES entries (multi-resolution registers), or null
     DeviceCounters *counters;
     uint64_t d;
     uint64_t row_bytes;       // d * bits / 8

@@ -169,16 +169,18 @@ __device__ __forceinline__ int read_prefix(const Register &src, const NodeTile &
     return 2;
 }
 
-// Tiles that needed more than the first plane, and tiles no level confirmed (one lane per wave).
-__device__ __forceinline__ void report_level(DeviceCounters *c, int level, bool confirmed, uint64_t tile, uint64_t d,
+// Tiles that needed more than the first plane, and tiles no level confirmed (one lane per wave, into
+// the stripe of its workgroup).
+__device__ __forceinline__ void report_level(PrefixStats *stats, int level, bool confirmed, uint64_t tile, uint64_t d,
                                              uint32_t lane) {
     if (lane != 0 || (level == 0 && confirmed)) return;
+    PrefixStats *c = stats + ((blockIdx.x + 977u * blockIdx.y) & (PREFIX_STRIPES - 1));
     const unsigned long long coords = (tile + 1) * TILE <= d ? TILE : d - tile * TILE;
     if (level > 0) {
-        atomicAdd(&c->prefix_tiles[level - 1], 1ull);
-        atomicAdd(&c->prefix_coords[level - 1], coords);
+        atomicAdd(&c->tiles[level - 1], 1ull);
+        atomicAdd(&c->coords[level - 1], coords);
     }
-    if (!confirmed) atomicAdd(&c->prefix_unconfirmed, 1ull);
+    if (!confirmed) atomicAdd(&c->unconfirmed, 1ull);
 }
 
 // X' = eps (z + z') / 2 + delta for the lane's two float4.
@@ -231,7 +233,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_nodes_kernel(const PrefixAr
                                         clamped, confirmed);
     publish(a, node, me, g.tile, g.lane, g.kA, g.kB, g.inA, g.inB);
     finish(a, node, me, zpA, zpB, g.kA, g.kB, g.inA, g.inB);
-    report_level(a.counters, level, confirmed, g.tile, a.d, g.lane);
+    report_level(a.prefix_stats, level, confirmed, g.tile, a.d, g.lane);
     report(a.counters, 0, me.clamped || ((g.inA || g.inB) && clamped));
 }
 
@@ -268,8 +270,8 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_pairs_kernel(const PrefixAr
     publish(a, pd.nj, tj, g.tile, g.lane, g.kA, g.kB, g.inA, g.inB);
     finish(a, pd.ni, ti, zjA, zjB, g.kA, g.kB, g.inA, g.inB);
     finish(a, pd.nj, tj, ziA, ziB, g.kA, g.kB, g.inA, g.inB);
-    report_level(a.counters, level_i, conf_i, g.tile, a.d, g.lane);
-    report_level(a.counters, level_j, conf_j, g.tile, a.d, g.lane);
+    report_level(a.prefix_stats, level_i, conf_i, g.tile, a.d, g.lane);
+    report_level(a.prefix_stats, level_j, conf_j, g.tile, a.d, g.lane);
     report(a.counters, fails, ti.clamped || tj.clamped || ((g.inA || g.inB) && clamped));
 }
 

@@ -40,6 +40,7 @@ struct swarm_ctx {
     uint8_t *ring = nullptr;
     uint32_t *edges_dev = nullptr, *prio_dev = nullptr, *counts_dev = nullptr, *nodes_dev = nullptr;
     uint32_t *linf_dev = nullptr, *steps_dev = nullptr;   // steps_dev: local steps per node id (geometric law)
+    PrefixStats *prefix_stats_dev = nullptr;   // multi-resolution registers: striped escalation counts
     float *eps_slots_dev = nullptr;     // one scale per round: scale of the codes in each ring slot
     uint32_t *scale_state_dev = nullptr; // [0] next scale, [1] disagreement of the round in flight, [2] of the last
     uint8_t *desc_dev = nullptr;                 // PairDesc[n/2] | singles[n]
@@ -104,6 +105,7 @@ GossipArgs gossip_args(swarm_t h, uint32_t event, uint32_t slot) {
     a.n = h->cfg.n; a.event = event; a.slot_now = slot; a.ring_depth = h->cfg.stale_max + 1;
     a.eps = h->cfg.eps; a.inv_eps = h->inv_eps;
     a.eps_slots = h->eps_slots_dev;
+    a.prefix_stats = h->prefix_stats_dev;
     a.far_bits = h->scale_state_dev ? h->scale_state_dev + 1 : nullptr;
     return a;
 }
@@ -308,6 +310,10 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         SWARM_HIP(h, hipMalloc((void **)&h->nodes_dev, sizeof(uint32_t) * n));
         SWARM_HIP(h, hipMalloc((void **)&h->linf_dev, sizeof(uint32_t) * (n / 2)));
         SWARM_HIP(h, hipMalloc((void **)&h->steps_dev, sizeof(uint32_t) * n));
+        if (cfg->codec == SWARM_CODEC_PREFIX) {
+            SWARM_HIP(h, hipMalloc((void **)&h->prefix_stats_dev, sizeof(PrefixStats) * PREFIX_STRIPES));
+            SWARM_HIP(h, hipMemsetAsync(h->prefix_stats_dev, 0, sizeof(PrefixStats) * PREFIX_STRIPES, h->stream));
+        }
         if (cfg->scale_policy == SWARM_SCALE_GLOBAL_LINF) {
             const std::vector<float> slots(cfg->stale_max + 1, cfg->eps);
             uint32_t state[3] = {0u, 0u, 0u};
@@ -366,7 +372,7 @@ swarm_status swarm_destroy(swarm_t h) {
     if (h->W == h->X) h->W = nullptr;
     void *dev[] = {h->X, h->W, h->Xhat, h->ring, h->edges_dev, h->prio_dev, h->counts_dev, h->nodes_dev,
                    h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev, h->mpairs_dev,
-                   h->msingles_dev, h->steps_dev, h->eps_slots_dev, h->scale_state_dev};
+                   h->msingles_dev, h->steps_dev, h->eps_slots_dev, h->scale_state_dev, h->prefix_stats_dev};
     for (void *p : dev) if (p) (void)hipFree(p);
     for (int s = 0; s < DESC_SLOTS; ++s) {
         if (h->desc_host[s]) (void)hipHostFree(h->desc_host[s]);
@@ -838,6 +844,20 @@ swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npa
     return SWARM_OK;
 }
 
+// Sum of the striped escalation counts (synchronises; zeros without multi-resolution registers).
+static swarm_status prefix_totals(swarm_t h, PrefixStats *total) {
+    *total = PrefixStats{};
+    if (!h->prefix_stats_dev) return SWARM_OK;
+    std::vector<PrefixStats> stripes(PREFIX_STRIPES);
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    SWARM_HIP(h, hipMemcpy(stripes.data(), h->prefix_stats_dev, sizeof(PrefixStats) * PREFIX_STRIPES, hipMemcpyDeviceToHost));
+    for (const PrefixStats &s : stripes) {
+        for (int l = 0; l < 2; ++l) { total->tiles[l] += s.tiles[l]; total->coords[l] += s.coords[l]; }
+        total->unconfirmed += s.unconfirmed;
+    }
+    return SWARM_OK;
+}
+
 swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions, uint64_t *bits_communicated,
                             uint64_t *decode_failures) {
     if (!h) return SWARM_EINVAL;
@@ -846,8 +866,11 @@ swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions,
     SWARM_HIP(h, hipStreamSynchronize(h->stream));
     if (rounds) *rounds = h->round;
     if (interactions) *interactions = h->interactions;
-    if (bits_communicated)     // escalated tiles read 4 (to 8 bits) or 12 (to 16 bits) more bits per coordinate
-        *bits_communicated = h->bits_communicated + 4ull * dc->prefix_coords[0] + 12ull * dc->prefix_coords[1];
+    if (bits_communicated) {   // escalated tiles read 4 (to 8 bits) or 12 (to 16 bits) more bits per coordinate
+        PrefixStats total;
+        SWARM_TRY(prefix_totals(h, &total));
+        *bits_communicated = h->bits_communicated + 4ull * total.coords[0] + 12ull * total.coords[1];
+    }
     if (decode_failures) *decode_failures = dc->decode_failures;
     if (dc->range_clamped) return fail(h, SWARM_ERANGE, "|x/eps| reached the clamp 2^29");
     return SWARM_OK;
@@ -855,15 +878,14 @@ swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions,
 
 swarm_status swarm_prefix_stats(swarm_t h, uint64_t *tiles, uint64_t *unconfirmed) {
     if (!h) return SWARM_EINVAL;
-    DeviceCounters *dc = (DeviceCounters *)h->scalar_host;
-    SWARM_HIP(h, hipMemcpyAsync(dc, h->counters_dev, sizeof(DeviceCounters), hipMemcpyDeviceToHost, h->stream));
-    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    PrefixStats total;
+    SWARM_TRY(prefix_totals(h, &total));
     if (tiles) {
-        tiles[1] = dc->prefix_tiles[0];
-        tiles[2] = dc->prefix_tiles[1];
+        tiles[1] = total.tiles[0];
+        tiles[2] = total.tiles[1];
         tiles[0] = h->prefix_tile_reads - tiles[1] - tiles[2];
     }
-    if (unconfirmed) *unconfirmed = dc->prefix_unconfirmed;
+    if (unconfirmed) *unconfirmed = total.unconfirmed;
     return SWARM_OK;
 }
 
