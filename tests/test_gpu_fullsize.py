@@ -20,10 +20,26 @@ def graph_of(cfg):
             "torus8x8": lambda: wl.torus_graph(8, 8), "complete": lambda: wl.complete_graph(n)}[cfg["graph"]]()
 
 
-@pytest.mark.parametrize("cfg_id,eps", [(2, 2.0 ** -4), (4, 0.5), (5, 0.25)])
-def test_diag_configs_full_size_sampled_windows(gpu, cfg_id, eps):
+def register_window(g, gpu, node, k0, width, bits, prefix, d):
+    """Bytes of a node's last published register that cover columns [k0, k0 + width)."""
+    if not prefix:
+        return g.read_codes(node, byte0=k0 * bits // 8, length=width * bits // 8)
+    return np.concatenate([g.read_codes(node, byte0=k0 // 2, length=width // 2),               # bits 0-3
+                           g.read_codes(node, byte0=d // 2 + k0 // 2, length=width // 2),      # bits 4-7
+                           g.read_codes(node, byte0=d + k0, length=width),                     # bits 8-15
+                           g.read_codes(node, byte0=2 * d + 4 * (k0 // 512), length=4 * (width // 512))])
+
+
+@pytest.mark.parametrize("cfg_id,eps,mode", [(2, 2.0 ** -4, "two calls"), (4, 0.5, "two calls"), (5, 0.25, "two calls"),
+                                             (4, 0.5, "one pass"), (5, 0.25, "one pass"), (4, 0.5, "one pass, prefix")])
+def test_diag_configs_full_size_sampled_windows(gpu, cfg_id, eps, mode):
+    """mode: the two entry points (swarm_local_steps + swarm_gossip_round) or the one-pass round the
+    benchmark times by default; "prefix": 16-bit multi-resolution registers instead of the fixed b bits."""
     cfg = wl.CONFIGS[cfg_id]
     n, d, bits, H, lr, S, sigma = cfg["n"], cfg["d"], cfg["bits"], cfg["H"], cfg["lr"], cfg["stale_max"], cfg["sigma"]
+    one_pass, prefix = mode.startswith("one pass"), mode.endswith("prefix")
+    if prefix:
+        bits = 16
     seed = cfg_id
     edges = graph_of(cfg)
     gen = torch.Generator(device="cuda")
@@ -35,15 +51,18 @@ def test_diag_configs_full_size_sampled_windows(gpu, cfg_id, eps):
         a.mul_(float(np.log(cfg["a_hi"] / cfg["a_lo"]))).add_(float(np.log(cfg["a_lo"]))).exp_()
     c = torch.empty((n, d), dtype=torch.float32, device="cuda").normal_(0.0, 1.0, generator=gen)
     c += cfg["shift_sigma"] * torch.randn(n, 1, generator=gen, device="cuda")
-    g = gpu.Swarm(n, d, edges, bits, eps, H, lr, S, seed)
+    g = gpu.Swarm(n, d, edges, bits, eps, H, lr, S, seed, codec=gpu.CODEC_PREFIX if prefix else gpu.CODEC_FIXED)
     g.set_objective_diag(a, c, sigma)
     g.models_view(gpu.COMM).normal_(0.0, 0.7, generator=gen)        # any state: start away from zero
     torch.cuda.synchronize()
     width = 6 * 512 + 8                                             # several tiles and a ragged edge
     starts = [0, 8 * (d // 24) + 8, d - width]                      # first, an unaligned middle, last columns
+    if prefix:                                                      # whole checksum tiles
+        width = 6 * 512
+        starts = [0, 512 * (d // 1536), 512 * ((d - width) // 512)]
     oracles = []
     for k0 in starts:
-        o = SwarmOracle(n, d, edges, bits, eps, H, lr, S, seed, k0=k0, k1=k0 + width)
+        o = SwarmOracle(n, d, edges, bits, eps, H, lr, S, seed, k0=k0, k1=k0 + width, codec="prefix" if prefix else "fixed")
         o.objective = DiagQuadratic(a[:, k0:k0 + width].cpu().numpy(), c[:, k0:k0 + width].cpu().numpy(), sigma, k0=k0)
         oracles.append(o)
     for o, k0 in zip(oracles, starts):                               # the seeded initial state, read once
@@ -60,20 +79,25 @@ def test_diag_configs_full_size_sampled_windows(gpu, cfg_id, eps):
             assert np.array_equal(stale, oracles[0].sample_stale().astype(np.uint8))
         else:
             stale = None
-        g.local_steps()
-        g.gossip_round(None, stale)                                  # the launch configuration bench.py times
+        if one_pass:                                                 # the launch configurations bench.py times
+            g.round_fused(None, stale)
+        else:
+            g.local_steps()
+            g.gossip_round(None, stale)
         for o, k0 in zip(oracles, starts):
             o.local_steps()
-            assert_close(g.read_models(gpu.LIVE, k0=k0, length=width), o.W, TOL_ELEMENTWISE, f"W window {k0} round {r}")
+            if not one_pass:
+                assert_close(g.read_models(gpu.LIVE, k0=k0, length=width), o.W, TOL_ELEMENTWISE, f"W window {k0} round {r}")
             o.gossip_round(pairs, stale)
             for node in (0, n // 3, n - 1):
-                got = g.read_codes(node, byte0=k0 * bits // 8, length=width * bits // 8)
+                got = register_window(g, gpu, node, k0, width, bits, prefix, d)
                 assert np.array_equal(got, o.ring[r % (S + 1)][node]), f"codes window {k0} node {node} round {r}"
             assert_close(g.read_models(gpu.COMM, k0=k0, length=width), o.X, 2 * TOL_ELEMENTWISE,
                          f"X window {k0} round {r}")
     cnt = g.counters()
     assert cnt["rounds"] == 4 and cnt["interactions"] == oracles[0].interactions
-    assert cnt["bits_communicated"] == oracles[0].bits_communicated
+    if not prefix:                                                   # prefix reads: the bits depend on every tile of the row
+        assert cnt["bits_communicated"] == oracles[0].bits_communicated
     assert np.isfinite(g.potential()) and g.potential() > 0
 
 
