@@ -650,3 +650,28 @@ def test_prefix_codec_stale_reads_decode_after_the_models_moved():
             for me, other in ((i, j), (j, i)):
                 assert np.abs(o.X[me] - 0.5 * (X[me] + old[other])).max() <= 1.5 * eps
     assert o.prefix_unconfirmed == 0 and o.decode_failures == 0
+
+
+def test_global_scale_adds_the_pending_local_steps_on_top_of_the_average():
+    """Deferred apply under the per-round scale: X_i' = average + (W_i - X_i), as under the fixed one."""
+    n, d, eps = 4, 64, 2.0 ** -5
+    gen = np.random.Generator(np.random.PCG64(31))
+    X = (gen.standard_normal((n, d)) * 0.1).astype(np.float32)
+    plain, stepped = global_oracle(n, d, 8, eps, X=X), global_oracle(n, d, 8, eps, X=X)
+    step = (gen.standard_normal(d) * 0.01).astype(np.float32)
+    stepped.W[0] = X[0] + step
+    stepped.pending[0] = True
+    for o in (plain, stepped):
+        o.gossip_round([(0, 1), (2, 3)])
+    assert np.allclose(stepped.X[0], plain.X[0].astype(np.float64) + (stepped.W[0].astype(np.float64) - X[0]), atol=1e-7)
+    assert np.array_equal(stepped.X[1:], plain.X[1:]) and stepped.eps_cur == plain.eps_cur
+
+
+def test_prefix_codec_counts_tiles_that_no_level_confirms():
+    n, d, eps = 2, 1024, 2.0 ** -6
+    gen = np.random.Generator(np.random.PCG64(32))
+    o = prefix_oracle(n, d, eps)
+    o.X[:] = (gen.standard_normal((1, d)) + gen.uniform(-0.01, 0.01, (n, d))).astype(np.float32)
+    o.X[1, 600] += 40000 * eps                               # beyond the 16-bit radius, second tile only
+    o.gossip_round([(0, 1)])
+    assert o.prefix_unconfirmed == 2 and o.prefix_levels.tolist() == [2, 0, 2] and o.decode_failures == 2
