@@ -149,6 +149,15 @@ swarm_status swarm_set_objective_mlp(swarm_t h, uint32_t n_in, uint32_t n_hid, u
  * nodes: host array of `count` distinct node ids, or NULL for all nodes. */
 swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count);
 
+/* Local steps computed outside the library (any objective, e.g. a network trained by the
+ * caller's framework): the caller has written W_i = X_i - eta * (sum of its H local gradients)
+ * into the LIVE matrix (swarm_models_ptr) with work ordered before the handle's stream, and
+ * declares those nodes' steps pending; the next round adds W_i - X_i on top of the average
+ * exactly as for the built-in objectives.  nodes: host array of `count` distinct ids, or NULL
+ * for all nodes.  No objective needs to be set.  SWARM_ESTATE in INPLACE mode (there the caller
+ * updates the COMM matrix itself and nothing is pending). */
+swarm_status swarm_mark_pending(swarm_t h, const uint32_t *nodes, uint32_t count);
+
 /* Random maximal matching of G for the current round (round model: nodes meet in
  * disjoint pairs).  Edges get random 64-bit priorities; an edge is kept when both
  * endpoints are free, scanning by increasing priority.  pairs_host receives up to

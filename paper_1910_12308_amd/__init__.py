@@ -23,7 +23,7 @@ CODEC_FIXED, CODEC_PREFIX = 0, 1
 _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_ESTATE", 5: "SWARM_ERANGE"}
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
-           "swarm_set_objective_mlp", "swarm_local_steps", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
+           "swarm_set_objective_mlp", "swarm_local_steps", "swarm_mark_pending", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
            "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
            "swarm_potential", "swarm_pair_linf", "swarm_scale", "swarm_prefix_stats", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
@@ -58,6 +58,7 @@ def load_library():
         "swarm_set_objective_lsq": [vp, vp, vp, u32, u32],
         "swarm_set_objective_mlp": [vp, u32, u32, u32, vp, vp, f32, u32],
         "swarm_local_steps": [vp, vp, u32],
+        "swarm_mark_pending": [vp, vp, u32],
         "swarm_sample_matching": [vp, vp, P(u32)],
         "swarm_sample_stale": [vp, vp],
         "swarm_sample_steps": [vp, vp],
@@ -186,6 +187,13 @@ class Swarm:
         else:
             nodes = _host_u32(nodes)
             self._check(self._lib.swarm_local_steps(self._h, nodes.ctypes.data_as(ctypes.c_void_p), nodes.size))
+
+    def mark_pending(self, nodes=None):
+        if nodes is None:
+            self._check(self._lib.swarm_mark_pending(self._h, None, 0))
+        else:
+            nodes = _host_u32(nodes)
+            self._check(self._lib.swarm_mark_pending(self._h, nodes.ctypes.data_as(ctypes.c_void_p), nodes.size))
 
     def sample_matching(self):
         pairs = np.zeros(2 * (self.n // 2), dtype=np.uint32)

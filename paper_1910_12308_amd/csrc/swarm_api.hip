@@ -455,6 +455,25 @@ swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count)
     return SWARM_OK;
 }
 
+swarm_status swarm_mark_pending(swarm_t h, const uint32_t *nodes, uint32_t count) {
+    if (!h) return SWARM_EINVAL;
+    if (h->cfg.apply_mode == SWARM_APPLY_INPLACE)
+        return fail(h, SWARM_ESTATE, "in-place apply: update the exchanged models directly, nothing is pending");
+    const uint32_t n = h->cfg.n;
+    if (!nodes) {
+        std::fill(h->pending.begin(), h->pending.end(), 1);
+        return SWARM_OK;
+    }
+    if (count == 0 || count > n) return fail(h, SWARM_EINVAL, "node count out of range");
+    std::vector<uint8_t> seen(n, 0);
+    for (uint32_t k = 0; k < count; ++k) {
+        if (nodes[k] >= n || seen[nodes[k]]) return fail(h, SWARM_EINVAL, "node id out of range or repeated");
+        seen[nodes[k]] = 1;
+    }
+    for (uint32_t k = 0; k < count; ++k) h->pending[nodes[k]] = 1;
+    return SWARM_OK;
+}
+
 // Enqueue the matching of the current round and its copy to pinned host memory.  The matching
 // depends only on (seed, round, graph), so it can be issued a round ahead: the host then finds
 // it ready instead of draining the stream.

@@ -766,3 +766,34 @@ def test_prefix_codec_rounds(gpu, fused):
         g.interact(0, 1)
     with pytest.raises(gpu.SwarmError):
         gpu.Swarm(n, d, edges, 8, eps, H, lr, 0, 0, codec=gpu.CODEC_PREFIX)
+
+
+def test_local_steps_computed_by_the_caller(gpu):
+    """Gradients from outside the library: the caller writes W = X - eta * (its own gradients) into the
+    live matrix on the device and declares the steps pending; the round treats them like its own."""
+    n, d, bits, eps, S = 6, D_RAGGED, 8, 2.0 ** -5, 1
+    edges = wl.complete_graph(n)
+    g, c = make_both(gpu, n, d, edges, bits, eps, 0, 0.0, S, seed=13)
+    gen = np.random.Generator(np.random.PCG64(13))
+    for r, (nodes, pairs) in enumerate([([0, 2, 3], [(0, 1), (2, 5)]), (None, [(4, 0), (1, 3)]), ([5], [])]):
+        c.X[:] = models(gen, 1, d) + models(gen, n, d, 0.05)
+        c.pending[:] = False
+        force_state(gpu, g, c)
+        live = g.models_view(gpu.LIVE)
+        ids = list(range(n)) if nodes is None else nodes
+        for i in ids:                                             # a gradient step of the caller's own making
+            step = models(gen, 1, d, 0.01)[0]
+            c.W[i] = c.X[i] - step
+            c.pending[i] = True
+            live[i].copy_(torch.from_numpy(c.W[i]).cuda())
+        g.mark_pending(nodes)
+        stale = np.minimum(1, r) * np.ones(n, dtype=np.uint8)
+        c.gossip_round(pairs, stale)
+        g.gossip_round(pairs, stale)
+        for i in range(n):
+            assert np.array_equal(g.read_codes(i), ring_row(c, i))
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"X after round {r}")
+    with pytest.raises(gpu.SwarmError):
+        g.mark_pending([0, 0])
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(n, d, edges, bits, eps, 0, 0.0, 0, 0, apply_mode=gpu.INPLACE).mark_pending()
