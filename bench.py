@@ -329,6 +329,7 @@ def main():
                             else "swarm_sample_pair + swarm_interact (Algorithm 1)" if cfg["mode"] == "sequential"
                             else "swarm_local_steps + swarm_gossip_round"),
                    "pairs_per_round": main_m["interactions"] / args.steps,
+                   "node_updates_per_s": 2.0 * main_m["interactions"] / main_m["dt"],
                    "decode_failures": main_m["decode_failures"],
                    **({"registers": "multi-resolution (16-bit planes, prefix reads)",
                        "tile_reads_at_4_8_16_bits": main_m["prefix_tiles"]} if args.prefix else {})},
