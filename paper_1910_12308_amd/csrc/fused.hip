@@ -81,13 +81,13 @@ __device__ __forceinline__ void fused_pair_tile(const FusedArgs &fa, const PairD
     if (a.eps_slots) {                           // one scale per round: the partner's code may be on an older lattice
         float far = 0.f;
         oiA = averaged_mixed<BITS>(ziA, stale_i ? seenjA : cjA, qiA, diA, rsi.eps_now, rsi.eps_old, rsi.inv_old,
-                                   stale_i ? nullptr : zjA, failsA, clampedA, far);
+                                   stale_i ? nullptr : zjA, failsA, clampedA, far, inA);
         oiB = averaged_mixed<BITS>(ziB, stale_i ? seenjB : cjB, qiB, diB, rsi.eps_now, rsi.eps_old, rsi.inv_old,
-                                   stale_i ? nullptr : zjB, failsB, clampedB, far);
+                                   stale_i ? nullptr : zjB, failsB, clampedB, far, inB);
         ojA = averaged_mixed<BITS>(zjA, stale_j ? seeniA : ciA, qjA, djA, rsj.eps_now, rsj.eps_old, rsj.inv_old,
-                                   stale_j ? nullptr : ziA, failsA, clampedA, far);
+                                   stale_j ? nullptr : ziA, failsA, clampedA, far, inA);
         ojB = averaged_mixed<BITS>(zjB, stale_j ? seeniB : ciB, qjB, djB, rsj.eps_now, rsj.eps_old, rsj.inv_old,
-                                   stale_j ? nullptr : ziB, failsB, clampedB, far);
+                                   stale_j ? nullptr : ziB, failsB, clampedB, far, inB);
         report_far(a.far_bits, far);
     } else {
         const float half_eps = 0.5f * rsi.eps_now;
@@ -152,8 +152,8 @@ __device__ __forceinline__ void fused_node_tile(const FusedArgs &fa, uint32_t no
     f4 oA, oB;
     if (a.eps_slots) {
         float far = 0.f;
-        oA = averaged_mixed<BITS>(zA, seenA, qA, dA, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedA, far);
-        oB = averaged_mixed<BITS>(zB, seenB, qB, dB, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedB, far);
+        oA = averaged_mixed<BITS>(zA, seenA, qA, dA, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedA, far, inA);
+        oB = averaged_mixed<BITS>(zB, seenB, qB, dB, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedB, far, inB);
         report_far(a.far_bits, far);
     } else {
         const float half_eps = 0.5f * rs.eps_now;

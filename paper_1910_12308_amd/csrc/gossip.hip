@@ -75,13 +75,13 @@ __device__ __forceinline__ void gossip_pair_tile(const GossipArgs &a, const Pair
     if (a.eps_slots) {                           // one scale per round: the partner's code may be on an older lattice
         float far = 0.f;
         oiA = averaged_mixed<BITS>(ziA, stale_i ? seenjA : cjA, xiA, diA, rsi.eps_now, rsi.eps_old, rsi.inv_old,
-                                   stale_i ? nullptr : zjA, failsA, clampedA, far);
+                                   stale_i ? nullptr : zjA, failsA, clampedA, far, inA);
         oiB = averaged_mixed<BITS>(ziB, stale_i ? seenjB : cjB, xiB, diB, rsi.eps_now, rsi.eps_old, rsi.inv_old,
-                                   stale_i ? nullptr : zjB, failsB, clampedB, far);
+                                   stale_i ? nullptr : zjB, failsB, clampedB, far, inB);
         ojA = averaged_mixed<BITS>(zjA, stale_j ? seeniA : ciA, xjA, djA, rsj.eps_now, rsj.eps_old, rsj.inv_old,
-                                   stale_j ? nullptr : ziA, failsA, clampedA, far);
+                                   stale_j ? nullptr : ziA, failsA, clampedA, far, inA);
         ojB = averaged_mixed<BITS>(zjB, stale_j ? seeniB : ciB, xjB, djB, rsj.eps_now, rsj.eps_old, rsj.inv_old,
-                                   stale_j ? nullptr : ziB, failsB, clampedB, far);
+                                   stale_j ? nullptr : ziB, failsB, clampedB, far, inB);
         report_far(a.far_bits, far);
     } else {
         const float half_eps = 0.5f * rsi.eps_now;
@@ -131,8 +131,8 @@ __device__ __forceinline__ void gossip_node_tile(const GossipArgs &a, uint32_t n
     f4 oA, oB;
     if (a.eps_slots) {
         float far = 0.f;
-        oA = averaged_mixed<BITS>(zA, seenA, xA, dA, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedA, far);
-        oB = averaged_mixed<BITS>(zB, seenB, xB, dB, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedB, far);
+        oA = averaged_mixed<BITS>(zA, seenA, xA, dA, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedA, far, inA);
+        oB = averaged_mixed<BITS>(zB, seenB, xB, dB, rs.eps_now, rs.eps_old, rs.inv_old, nullptr, fails, clampedB, far, inB);
         report_far(a.far_bits, far);
     } else {
         const float half_eps = 0.5f * rs.eps_now;

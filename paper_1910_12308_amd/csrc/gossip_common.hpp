@@ -90,11 +90,12 @@ __device__ __forceinline__ f4 averaged(const int z_own[4], uint64_t partner_code
 }
 
 // The same with one lattice scale per round: the partner's code was written at eps_old, the own
-// point at eps_now; far collects max |key - eps_old z_j'|, from which the next round's scale is set.
+// point at eps_now; far collects max |key - eps_old z_j'|, from which the next round's scale is set
+// (live = false for lanes past the row end: they hold a duplicate rounded with other random words).
 template <int BITS>
 __device__ __forceinline__ f4 averaged_mixed(const int z_own[4], uint64_t partner_code, f4 key, f4 delta,
                                              float eps_now, float eps_old, float inv_old, const int *z_true,
-                                             int &fails, bool &clamped, float &far) {
+                                             int &fails, bool &clamped, float &far, bool live) {
     constexpr uint32_t MASK = (uint32_t)((1ull << BITS) - 1);
     const float k[4] = {key.x, key.y, key.z, key.w};
     const float dl[4] = {delta.x, delta.y, delta.z, delta.w};
@@ -105,7 +106,7 @@ __device__ __forceinline__ f4 averaged_mixed(const int z_own[4], uint64_t partne
                                          key_cell(k[m], inv_old, clamped));
         if (z_true) fails += (zp != z_true[m]);
         const float mine = (float)z_own[m] * eps_now, theirs = (float)zp * eps_old;
-        far = fmaxf(far, fabsf(k[m] - theirs));
+        if (live) far = fmaxf(far, fabsf(k[m] - theirs));
         o[m] = (mine + theirs) * 0.5f + dl[m];
     }
     return f4{o[0], o[1], o[2], o[3]};

@@ -797,3 +797,26 @@ def test_local_steps_computed_by_the_caller(gpu):
         g.mark_pending([0, 0])
     with pytest.raises(gpu.SwarmError):
         gpu.Swarm(n, d, edges, bits, eps, 0, 0.0, 0, 0, apply_mode=gpu.INPLACE).mark_pending()
+
+
+@pytest.mark.parametrize("kind", ["prefix", "global"])
+def test_smallest_swarm_with_prefix_registers_and_per_round_scale(gpu, kind):
+    """n = 2, d = 8: a row shorter than one lane group, one checksum tile of 8 coordinates; an empty
+    round, stale and mixed reads."""
+    bits = 16 if kind == "prefix" else 8
+    g, c = make_both(gpu, 2, 8, [(0, 1)], bits, 0.25, 0, 0.0, 1, seed=1, prefix=kind == "prefix",
+                     global_scale=kind == "global")
+    X = np.array([[0.1, -0.2, 0.3, 5.0, -5.0, 0.0, 1.0, 2.0], [0.2, -0.1, 0.1, 4.0, -4.5, 0.5, 1.5, 30.0]], dtype=np.float32)
+    for r, (pairs, stale) in enumerate([([], None), ([(1, 0)], [1, 1]), ([(0, 1)], [1, 0]), ([(0, 1)], None)]):
+        c.X[:] = X + np.float32(0.05 * r)
+        force_state(gpu, g, c)
+        c.gossip_round(pairs, stale)
+        g.gossip_round(pairs, stale)
+        assert np.array_equal(g.read_codes(0), ring_row(c, 0)) and np.array_equal(g.read_codes(1), ring_row(c, 1))
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"two-node swarm, round {r}")
+        if kind == "prefix":
+            assert g.prefix_stats() == (c.prefix_levels.tolist(), c.prefix_unconfirmed)
+            assert g.counters()["bits_communicated"] == c.bits_communicated
+        else:
+            assert g.scale() == (float(c.eps_cur), float(c.max_disagreement))
+    assert g.counters()["decode_failures"] == c.decode_failures
