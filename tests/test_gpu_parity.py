@@ -820,3 +820,40 @@ def test_smallest_swarm_with_prefix_registers_and_per_round_scale(gpu, kind):
         else:
             assert g.scale() == (float(c.eps_cur), float(c.max_disagreement))
     assert g.counters()["decode_failures"] == c.decode_failures
+
+
+@pytest.mark.parametrize("d", [8, 16, 504, 512, 520, 1032])
+def test_row_lengths_around_the_tile_edges(gpu, d):
+    """Rows shorter than a lane group, one short of / exactly / just over one 512-coordinate tile and
+    two tiles plus 8: local steps with noise, the gossip pass with fresh and stale reads, the one-pass
+    round and the multi-resolution registers all agree with the oracle."""
+    n, H, lr, S, eps = 4, 2, 0.1, 1, 2.0 ** -4
+    edges = wl.complete_graph(n)
+    a, cc = wl.diag_quadratic_data(n, d, 3, shift_sigma=0.2)
+    ad, cd = torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda()
+    gen = np.random.Generator(np.random.PCG64(d))
+    for bits, prefix in [(4, False), (8, False), (16, True)]:
+        two, c2 = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=d, prefix=prefix)
+        one, c1 = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=d, prefix=prefix)
+        for g, c in ((two, c2), (one, c1)):
+            c.objective = DiagQuadratic(a, cc, 0.05)
+            g.set_objective_diag(ad, cd, 0.05)
+        for r, (pairs, stale) in enumerate([([(0, 1), (2, 3)], [0, 0, 0, 0]), ([(1, 2)], [1, 1, 1, 1]), ([(3, 0), (2, 1)], [0, 1, 1, 0])]):
+            X = models(gen, 1, d) + models(gen, n, d, 0.05)
+            for g, c in ((two, c2), (one, c1)):
+                c.X[:] = X
+                c.pending[:] = False
+                force_state(gpu, g, c)
+                c.local_steps()
+            two.local_steps()
+            assert_close(two.read_models(gpu.LIVE), c2.W, TOL_ELEMENTWISE, f"W, bits {bits}, round {r}")
+            force_state(gpu, two, c2)
+            c2.gossip_round(pairs, stale)
+            two.gossip_round(pairs, stale)
+            c1.gossip_round(pairs, stale)
+            one.round_fused(pairs, stale)
+            for g, c, what in ((two, c2, "two calls"), (one, c1, "one pass")):
+                for i in range(n):
+                    assert np.array_equal(g.read_codes(i), ring_row(c, i)), f"{what}: codes of node {i}, bits {bits}, round {r}"
+                assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"{what}: X, bits {bits}, round {r}")
+                assert g.counters()["decode_failures"] == c.decode_failures
