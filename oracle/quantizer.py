@@ -113,36 +113,50 @@ def dequantize(buf, key, eps, bits):
 # nested: the b low bits of one 16-bit residue are the b-bit code, so the register holds the 16-bit
 # code split into planes (bits 0-3, 4-7, 8-15 of every coordinate) and a reader fetches planes until
 # the decode is confirmed.  The confirmation that the interactive protocol gets from the receiver's
-# reply is a 32-bit checksum of the writer's lattice coordinates, one per tile of 512 coordinates,
-# kept beside the planes: a reader stops at the first level whose decoded tile has that checksum.
+# reply is a 64-bit checksum of the writer's lattice coordinates (two 32-bit sums with pseudo-random
+# odd weights), one per tile of 512 coordinates, kept beside the planes: a reader stops at the first
+# level whose decoded tile has that checksum.  A failed decode is off by multiples of 2^b in some
+# coordinates, often +1 and -1 multiples in many of them at once, so weights that are linear in the
+# position would cancel far too often; hashed weights make a false confirmation a 2^-(64-2b) event.
 PREFIX_LEVELS = (4, 8, 16)      # bits per coordinate known after reading 1, 2, 3 planes
 PREFIX_TILE = 512               # coordinates per checksum
+_M32 = np.uint64(0xFFFFFFFF)
 
 
 def prefix_weights(count):
-    """Odd 32-bit weight of every coordinate, by its position inside its tile."""
+    """The two odd 32-bit weights of every coordinate, by its position j inside its tile:
+    x = (2j+1) 0x9E3779B1;  x ^= x >> 15;  x *= 0x85EBCA6B;  x ^= x >> 13;  w1 = x | 1;
+    y = x 0xC2B2AE35;  y ^= y >> 16;  w2 = y | 1   (all modulo 2^32)."""
     j = np.arange(count, dtype=np.uint64) % np.uint64(PREFIX_TILE)
-    return ((np.uint64(2) * j + np.uint64(1)) * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF)
+    x = ((np.uint64(2) * j + np.uint64(1)) * np.uint64(0x9E3779B1)) & _M32
+    x ^= x >> np.uint64(15)
+    x = (x * np.uint64(0x85EBCA6B)) & _M32
+    x ^= x >> np.uint64(13)
+    y = (x * np.uint64(0xC2B2AE35)) & _M32
+    y ^= y >> np.uint64(16)
+    return x | np.uint64(1), y | np.uint64(1)
 
 
 def prefix_checksums(z):
-    """sum_k (z_k mod 2^32) * weight_k mod 2^32 over every tile of 512 coordinates (the last may be short)."""
+    """(tiles, 2) uint32: sum_k (z_k mod 2^32) * w_k mod 2^32 for both weight families over every
+    tile of 512 coordinates (the last may be short)."""
     z = np.asarray(z, dtype=np.int64)
-    terms = ((z & 0xFFFFFFFF).astype(np.uint64) * prefix_weights(z.size)) & np.uint64(0xFFFFFFFF)
+    zu = (z & 0xFFFFFFFF).astype(np.uint64)
     tiles = -(-z.size // PREFIX_TILE)
-    out = np.zeros(tiles, dtype=np.uint64)
-    np.add.at(out, np.arange(z.size) // PREFIX_TILE, terms)
-    return (out & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+    out = np.zeros((tiles, 2), dtype=np.uint64)
+    for col, w in enumerate(prefix_weights(z.size)):
+        np.add.at(out[:, col], np.arange(z.size) // PREFIX_TILE, (zu * w) & _M32)
+    return (out & _M32).astype(np.uint32)
 
 
 def prefix_register(z):
     """Register image of a lattice point: plane of bits 0-3 (d/2 bytes), plane of bits 4-7 (d/2 bytes),
-    plane of bits 8-15 (d bytes), then the tile checksums (little-endian uint32)."""
+    plane of bits 8-15 (d bytes), then the tile checksums (two little-endian uint32 per tile)."""
     z = np.asarray(z, dtype=np.int64)
     p0 = pack(z & 15, 4)
     p1 = pack((z >> 4) & 15, 4)
     p2 = pack((z >> 8) & 255, 8)
-    return np.concatenate([p0, p1, p2, prefix_checksums(z).astype('<u4').view(np.uint8)])
+    return np.concatenate([p0, p1, p2, prefix_checksums(z).astype('<u4').reshape(-1).view(np.uint8)])
 
 
 def prefix_read(register, key, eps):
@@ -156,7 +170,7 @@ def prefix_read(register, key, eps):
     lo = unpack(register[:d // 2], 4, d)
     mid = unpack(register[d // 2:d], 4, d)
     hi = unpack(register[d:2 * d], 8, d)
-    checks = register[2 * d:].view('<u4')
+    checks = register[2 * d:].view('<u4').reshape(-1, 2)
     codes = (lo, lo | (mid << np.uint32(4)), lo | (mid << np.uint32(4)) | (hi << np.uint32(8)))
     tiles = -(-d // PREFIX_TILE)
     z = np.empty(d, dtype=np.int64)
@@ -167,7 +181,7 @@ def prefix_read(register, key, eps):
         for l, bits in enumerate(PREFIX_LEVELS):
             zt = decode(codes[l][k0:k1], key[k0:k1], eps, bits)
             level[t] = l
-            if prefix_checksums(zt)[0] == checks[t]:
+            if np.array_equal(prefix_checksums(zt)[0], checks[t]):
                 confirmed[t] = True
                 break
         z[k0:k1] = zt

@@ -168,7 +168,7 @@ class SwarmOracle:
             z, level, confirmed = qz.prefix_read(self.ring[slot][sender], self.X[reader], eps)
             dw = self.k1 - self.k0
             widths = np.minimum(qz.PREFIX_TILE, dw - np.arange(level.size) * qz.PREFIX_TILE)   # coordinates per tile
-            self.bits_communicated += int((np.array(qz.PREFIX_LEVELS)[level] * widths).sum()) + 32 * level.size
+            self.bits_communicated += int((np.array(qz.PREFIX_LEVELS)[level] * widths).sum()) + 64 * level.size
             self.prefix_levels += np.bincount(level, minlength=len(qz.PREFIX_LEVELS))
             self.prefix_unconfirmed += int((~confirmed).sum())
             if z_true is not None:

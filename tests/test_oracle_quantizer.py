@@ -156,16 +156,31 @@ def lattice_and_key(seed, d, eps, distance):
     return z, y
 
 
+def hashed_weights(j):
+    """The two weights of position j, in plain Python integers."""
+    x = ((2 * j + 1) * 0x9E3779B1) % 2 ** 32
+    x ^= x >> 15
+    x = (x * 0x85EBCA6B) % 2 ** 32
+    x ^= x >> 13
+    y = (x * 0xC2B2AE35) % 2 ** 32
+    y ^= y >> 16
+    return x | 1, y | 1
+
+
 def test_prefix_register_image_by_hand():
     """Plane of bits 0-3 (two coordinates per byte, low nibble first), plane of bits 4-7, plane of
-    bits 8-15 (one byte per coordinate), then the checksum: sum of z * (2 j + 1) * 0x9E3779B1 mod 2^32."""
+    bits 8-15 (one byte per coordinate), then per tile the two sums of z * weight mod 2^32."""
     z = np.array([0x1234, -1, 5, 0x0FF0, 7, 0x8000, 0x00A0, 3], dtype=np.int64)
     reg = qz.prefix_register(z)
     assert reg[:4].tolist() == [0xF4, 0x05, 0x07, 0x30]           # nibbles 4,F | 5,0 | 7,0 | 0,3
     assert reg[4:8].tolist() == [0xF3, 0xF0, 0x00, 0x0A]          # nibbles 3,F | 0,F | 0,0 | A,0
     assert reg[8:16].tolist() == [0x12, 0xFF, 0x00, 0x0F, 0x00, 0x80, 0x00, 0x00]
-    want = sum((int(v) % 2 ** 32) * ((2 * j + 1) * 0x9E3779B1) for j, v in enumerate(z)) % 2 ** 32
-    assert int(reg[16:].view('<u4')[0]) == want and reg.size == 20
+    want = [sum((int(v) % 2 ** 32) * hashed_weights(j)[f] for j, v in enumerate(z)) % 2 ** 32 for f in (0, 1)]
+    assert reg[16:].view('<u4').tolist() == want and reg.size == 24
+    w = [hashed_weights(j) for j in range(512)]
+    assert all(a % 2 == 1 and b % 2 == 1 for a, b in w) and len({a for a, _ in w}) == 512 and len({b for _, b in w}) == 512
+    two_tiles = qz.prefix_checksums(np.concatenate([z, np.zeros(504, dtype=np.int64), z]))
+    assert np.array_equal(two_tiles[0], two_tiles[1])             # the position inside the tile sets the weight
 
 
 def test_prefix_planes_are_the_fixed_width_codes():
@@ -212,7 +227,35 @@ def test_prefix_checksum_catches_every_single_wrapped_coordinate():
             for mult in (-3, -1, 1, 2):
                 w = z.copy()
                 w[k] += mult * (1 << b)
-                assert qz.prefix_checksums(w)[0] != base
+                assert not np.array_equal(qz.prefix_checksums(w)[0], base)
+
+
+def test_prefix_checksum_does_not_cancel_on_balanced_wraps():
+    """What a failed decode looks like: many coordinates off by +2^b and as many by -2^b.  With weights
+    linear in the position every pattern with equal position sums cancels; the hashed weights must not
+    (all such four-coordinate patterns in a stretch of the tile, and random larger ones)."""
+    z, _ = lattice_and_key(5, 512, 0.5, 1.0)
+    base = qz.prefix_checksums(z)[0]
+    for b in (4, 8):
+        step = 1 << b
+        for j1 in range(0, 40):
+            for j2 in range(j1 + 1, 40):
+                for j3 in range(j1 + 1, j2):
+                    j4 = j1 + j2 - j3                       # j1 + j2 = j3 + j4: cancels for linear weights
+                    if j4 <= j3:
+                        continue
+                    w = z.copy()
+                    w[[j1, j2]] += step
+                    w[[j3, j4]] -= step
+                    assert not np.array_equal(qz.prefix_checksums(w)[0], base)
+    gen = np.random.Generator(np.random.PCG64(6))
+    for _ in range(2000):
+        count = int(gen.integers(1, 120))
+        idx = gen.choice(512, 2 * count, replace=False)
+        w = z.copy()
+        w[idx[:count]] += 16
+        w[idx[count:]] -= 16
+        assert not np.array_equal(qz.prefix_checksums(w)[0], base)
 
 
 def test_prefix_read_beyond_sixteen_bits_is_reported():

@@ -618,7 +618,7 @@ def test_prefix_codec_matches_the_short_code_where_it_decodes_and_succeeds_where
     assert not np.array_equal(p.X[2], f.X[2])
     assert np.array_equal(p.X[2], p.X[3])                     # both decodes right: the pair agrees
     assert p.prefix_levels.tolist() == [14, 2, 0] and p.prefix_unconfirmed == 0
-    assert p.bits_communicated == 14 * 512 * 4 + 2 * 512 * 8 + 16 * 32
+    assert p.bits_communicated == 14 * 512 * 4 + 2 * 512 * 8 + 16 * 64
     assert f.bits_communicated == 4 * d * 4
 
 
