@@ -31,11 +31,11 @@ def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace=
     """Gossip pass: read X_i, X_j, W_i, W_j (16 B), write X_i', X_j' (8 B), write two b-bit codes, read
     two b-bit partner codes when the reads are stale.  One-pass round (local steps inside the gossip
     pass): read X, a, c of both nodes (24 B) instead of X and W; W never moves.  Multi-resolution
-    registers: 16 bits and 4/512 B of checksum written per coordinate, 4 bits and the checksum read by a
+    registers: 16 bits and 8/512 B of checksum written per coordinate, 4 bits and the checksum read by a
     stale reader (tiles that escalate to 8 or 16 bits are added by the caller from the library's counts)."""
     reads = (8 if inplace else 16) if kernel == "gossip" else 24    # in-place apply: no second matrix to read
     if prefix:
-        return reads + 8 + 2 * (2 + 4 / 512) + stale_fraction * 2 * (0.5 + 4 / 512)
+        return reads + 8 + 2 * (2 + 8 / 512) + stale_fraction * 2 * (0.5 + 8 / 512)
     return reads + 8 + 2 * bits / 8 + stale_fraction * 2 * bits / 8
 
 

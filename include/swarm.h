@@ -66,7 +66,9 @@ enum { SWARM_APPLY_DEFERRED = 0, SWARM_APPLY_INPLACE = 1 };
  * after a round without pairs.  A wrapped decode reads as a distance of about the decoding radius,
  * so a scale that is too small grows fourfold per round until decoding succeeds; no extra pass over
  * the models and no host round trip.  cfg.eps is the first round's scale and must be a power of two;
- * needs bits >= 4; works with stale reads, both apply modes and the one-pass round, not Algorithm 1. */
+ * needs bits >= 8 (the max-norm rule would make a 4-bit lattice coarser than the typical disagreement,
+ * and the rounding noise then feeds the very disagreement the scale is sized from: measured to
+ * diverge); works with stale reads, both apply modes and the one-pass round, not Algorithm 1. */
 enum { SWARM_SCALE_FIXED = 0, SWARM_SCALE_PAIR_LINF = 1, SWARM_SCALE_GLOBAL_LINF = 2 };
 
 /* What a register holds and how much of it a reader fetches.  FIXED: b = cfg.bits bits per
@@ -75,8 +77,10 @@ enum { SWARM_SCALE_FIXED = 0, SWARM_SCALE_PAIR_LINF = 1, SWARM_SCALE_GLOBAL_LINF
  * its own register; item 3 of the corollary: a reader needs only a prefix whose length grows with
  * log(|x - y| / eps)).  The register row holds the 16 low bits of every lattice coordinate as three
  * planes -- bits 0-3 (d/2 bytes), bits 4-7 (d/2 bytes), bits 8-15 (d bytes) -- followed by one
- * 32-bit checksum per tile of 512 coordinates, sum_j (z_j mod 2^32) (2 j + 1) 0x9E3779B1 mod 2^32
- * with j the position in the tile.  A reader decodes a tile from 4 bits, then 8, then 16, and stops
+ * 64-bit checksum per tile of 512 coordinates: two uint32 sums s_f = sum_j (z_j mod 2^32) w_f(j)
+ * mod 2^32, j the position in the tile, with the odd weights  x = (2j+1) 0x9E3779B1; x ^= x >> 15;
+ * x *= 0x85EBCA6B; x ^= x >> 13; w_1 = x | 1;  y = x 0xC2B2AE35; y ^= y >> 16; w_2 = y | 1.
+ * A reader decodes a tile from 4 bits, then 8, then 16, and stops
  * at the first level whose decoded tile has the writer's checksum (the confirmation that the
  * interactive protocol gets from the receiver's reply); a tile that no level confirms keeps the
  * 16-bit decode and is counted.  Needs bits = 16 and the fixed scale; rounds only (not Algorithm 1). */

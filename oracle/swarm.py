@@ -43,7 +43,9 @@ class SwarmOracle:
         assert scale_policy in ("fixed", "pair_linf", "global_linf")
         assert scale_policy != "pair_linf" or (self.bits >= 4 and self.S == 0)
         if scale_policy == "global_linf":
-            assert self.bits >= 4 and self.k0 == 0 and self.k1 == self.d
+            # at least 8 bits: the max-norm rule makes a 4-bit lattice coarser than the typical
+            # disagreement, and the rounding noise then feeds the disagreement it is sized from
+            assert self.bits >= 8 and self.k0 == 0 and self.k1 == self.d
             assert np.frexp(self.eps)[0] == 0.5, "the starting scale must be a power of two"
         self.scale_policy = scale_policy
         # "fixed": every register holds and every reader fetches b bits per coordinate.  "prefix": the

@@ -137,7 +137,7 @@ class Swarm:
         self._lib = lib()
         edges = _host_u32(edges)
         self.n, self.d, self.bits, self.stale_max = int(n), int(d), int(bits), int(stale_max)
-        self.row_bytes = self.d * self.bits // 8 + (4 * ((self.d + 511) // 512) if codec == CODEC_PREFIX else 0)
+        self.row_bytes = self.d * self.bits // 8 + (8 * ((self.d + 511) // 512) if codec == CODEC_PREFIX else 0)
         cfg = _Config(self.n, self.d, edges.size // 2, edges.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
                       self.bits, float(eps), int(H), float(lr), self.stale_max, int(seed) & 0xFFFFFFFFFFFFFFFF,
                       int(apply_mode), int(steps_law), int(scale_policy), int(codec))

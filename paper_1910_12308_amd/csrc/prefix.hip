@@ -3,9 +3,11 @@
 // resolution into its own register, and a reader fetches only the prefix it needs.  Here the codes
 // are nested -- the b low bits of a 16-bit residue are the b-bit code -- so a register row holds
 //   plane 0: bits 0-3 of every coordinate (d/2 bytes),  plane 1: bits 4-7 (d/2 bytes),
-//   plane 2: bits 8-15 (d bytes),  then one 32-bit checksum per tile of 512 coordinates,
+//   plane 2: bits 8-15 (d bytes),  then one 64-bit checksum per tile of 512 coordinates,
 // and a reader fetches planes until the decoded tile has the writer's checksum (the confirmation the
-// interactive protocol gets from the receiver's reply).  A wave owns exactly one checksum tile, so
+// interactive protocol gets from the receiver's reply).  The checksum is two 32-bit sums of
+// z * weight with pseudo-random odd weights per position: a failed decode is off by +2^b in some
+// coordinates and -2^b in others, which weights linear in the position would cancel too often.  A wave owns exactly one checksum tile, so
 // the loop over levels is wave-uniform: plane 0 is the only code traffic unless a tile escalates.
 // The kernels are the round kernels of gossip.hip / fused.hip with this register format:
 // LOCAL = the H local steps of a diagonal-quadratic objective are taken in registers (one-pass
@@ -25,44 +27,82 @@ struct PrefixArgs {
 // Register row of `node` in ring slot `slot`.
 struct Register {
     uint8_t *p0, *p1, *p2;
-    uint32_t *checks;
+    uint2 *checks;
 };
 __device__ __forceinline__ Register register_of(const GossipArgs &a, uint32_t slot, uint32_t node) {
     uint8_t *base = a.ring + ((uint64_t)slot * a.n + node) * a.row_bytes;
-    return Register{base, base + a.d / 2, base + a.d, (uint32_t *)(base + 2 * a.d)};
+    return Register{base, base + a.d / 2, base + a.d, (uint2 *)(base + 2 * a.d)};
 }
 
+// Sum over the wave as a scalar: four cross-lane adds inside each row of 16 lanes (data-parallel
+// primitives, no LDS round trip), then the four row sums through lane reads.
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return __builtin_amdgcn_readfirstlane(v);
+    v += (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    v += (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    v += (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x141, 0xF, 0xF, true);   // row_half_mirror
+    v += (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x140, 0xF, 0xF, true);   // row_mirror
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) + (uint32_t)__builtin_amdgcn_readlane((int)v, 16) +
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) + (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
 }
 
-// Odd weight of coordinate j of a tile in the checksum.
-__device__ __forceinline__ uint32_t weight(uint32_t j) { return (2u * j + 1u) * 0x9E3779B1u; }
+// The two odd weights of coordinate j of a tile: x = (2j+1) 0x9E3779B1; x ^= x >> 15; x *= 0x85EBCA6B;
+// x ^= x >> 13; w1 = x | 1; y = x 0xC2B2AE35; y ^= y >> 16; w2 = y | 1.  Tabulated at compile time
+// (4 KiB, read-only, stays in cache): hashing eight positions per lane in every wave cost more
+// vector ALU time than the rest of the checksum.
+struct WeightTable {
+    uint32_t w[PREFIX_TILE][2];
+    constexpr WeightTable() : w{} {
+        for (uint32_t j = 0; j < PREFIX_TILE; ++j) {
+            uint32_t x = (2u * j + 1u) * 0x9E3779B1u;
+            x ^= x >> 15;
+            x *= 0x85EBCA6Bu;
+            x ^= x >> 13;
+            uint32_t y = x * 0xC2B2AE35u;
+            y ^= y >> 16;
+            w[j][0] = x | 1u;
+            w[j][1] = y | 1u;
+        }
+    }
+};
+__device__ const WeightTable WEIGHTS{};
 
-// sum over the lane's in-range coordinates of z * weight (mod 2^32), reduced over the wave.
-__device__ __forceinline__ uint32_t tile_checksum(const int zA[4], const int zB[4], uint32_t lane, bool inA, bool inB) {
-    uint32_t s = 0;
+// Weights of the lane's eight positions (float4 number lane and lane + 64 of the tile).
+struct LaneWeights { uint2 a[4], b[4]; };
+__device__ __forceinline__ LaneWeights lane_weights(uint32_t lane) {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    const u4 *ta = (const u4 *)&WEIGHTS.w[4u * lane][0], *tb = (const u4 *)&WEIGHTS.w[256u + 4u * lane][0];
+    const u4 a0 = ta[0], a1 = ta[1], b0 = tb[0], b1 = tb[1];
+    LaneWeights w;
+    w.a[0] = uint2{a0.x, a0.y}; w.a[1] = uint2{a0.z, a0.w}; w.a[2] = uint2{a1.x, a1.y}; w.a[3] = uint2{a1.z, a1.w};
+    w.b[0] = uint2{b0.x, b0.y}; w.b[1] = uint2{b0.z, b0.w}; w.b[2] = uint2{b1.x, b1.y}; w.b[3] = uint2{b1.z, b1.w};
+    return w;
+}
+
+// Both sums over the lane's in-range coordinates of z * weight (mod 2^32), reduced over the wave.
+__device__ __forceinline__ uint2 tile_checksum(const int zA[4], const int zB[4], const LaneWeights &w, bool inA, bool inB) {
+    uint32_t s1 = 0, s2 = 0;
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
-        if (inA) s += (uint32_t)zA[m] * weight(4u * lane + m);
-        if (inB) s += (uint32_t)zB[m] * weight(256u + 4u * lane + m);
+        if (inA) { s1 += (uint32_t)zA[m] * w.a[m].x; s2 += (uint32_t)zA[m] * w.a[m].y; }
+        if (inB) { s1 += (uint32_t)zB[m] * w.b[m].x; s2 += (uint32_t)zB[m] * w.b[m].y; }
     }
-    return wave_sum(s);
+    return uint2{wave_sum(s1), wave_sum(s2)};
 }
+__device__ __forceinline__ bool same(uint2 p, uint2 q) { return p.x == q.x && p.y == q.y; }
 
 // What one node brings to the exchange: its row as read (x), what is rounded and serves as decoding
 // key (q), the update added on top of the average (delta), its lattice point and tile checksum.
 struct NodeTile {
     f4 qA, qB, dA, dB;
     int zA[4], zB[4];
-    uint32_t check;
+    uint2 check;
     bool clamped;
 };
 
 template <bool LOCAL, bool INPLACE, bool NOISE>
 __device__ __forceinline__ NodeTile prepare(const PrefixArgs &pa, uint32_t node, uint32_t H, bool pending,
-                                            uint64_t tile, uint32_t lane, uint64_t lA, uint64_t lB, bool inA, bool inB) {
+                                            uint64_t tile, uint32_t lane, uint64_t lA, uint64_t lB, bool inA, bool inB,
+                                            const LaneWeights &lw) {
     const GossipArgs &a = pa.g;
     const uint64_t on = (uint64_t)node * a.d;
     const f4 xA = ldg_nt(a.X + on + lA), xB = ldg_nt(a.X + on + lB);
@@ -86,7 +126,7 @@ __device__ __forceinline__ NodeTile prepare(const PrefixArgs &pa, uint32_t node,
     round_float4<16>(t.qA, r.a0, r.a1, a.inv_eps, t.zA, clampedA);
     round_float4<16>(t.qB, r.b0, r.b1, a.inv_eps, t.zB, clampedB);
     t.clamped = (inA && clampedA) || (inB && clampedB);
-    t.check = tile_checksum(t.zA, t.zB, lane, inA, inB);
+    t.check = tile_checksum(t.zA, t.zB, lw, inA, inB);
     return t;
 }
 
@@ -109,20 +149,23 @@ __device__ __forceinline__ void publish(const GossipArgs &a, uint32_t node, cons
     };
     if (inA) planes(t.zA, kA);
     if (inB) planes(t.zB, kB);
-    if (lane == 0) __builtin_nontemporal_store(t.check, reg.checks + tile);
+    if (lane == 0) {
+        __builtin_nontemporal_store(t.check.x, &reg.checks[tile].x);
+        __builtin_nontemporal_store(t.check.y, &reg.checks[tile].y);
+    }
 }
 
 // The three residue widths a reader may stop at.
 template <int BITS>
-__device__ __forceinline__ uint32_t decode_tile(const uint32_t cA[4], const uint32_t cB[4], const int kA[4], const int kB[4],
-                                                int zpA[4], int zpB[4], uint32_t lane, bool inA, bool inB) {
+__device__ __forceinline__ uint2 decode_tile(const uint32_t cA[4], const uint32_t cB[4], const int kA[4], const int kB[4],
+                                             int zpA[4], int zpB[4], const LaneWeights &lw, bool inA, bool inB) {
     constexpr uint32_t MASK = (1u << BITS) - 1u;
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         zpA[m] = decode_near<BITS>(cA[m] & MASK, kA[m]);
         zpB[m] = decode_near<BITS>(cB[m] & MASK, kB[m]);
     }
-    return tile_checksum(zpA, zpB, lane, inA, inB);
+    return tile_checksum(zpA, zpB, lw, inA, inB);
 }
 
 // Decode the partner's lattice point against the own key from the shortest confirmed prefix.
@@ -130,7 +173,7 @@ __device__ __forceinline__ uint32_t decode_tile(const uint32_t cA[4], const uint
 // in registers (a fresh read inside one pair: same decisions, no code traffic).  Returns the level.
 template <bool MEMORY>
 __device__ __forceinline__ int read_prefix(const Register &src, const NodeTile &partner, const NodeTile &me, float inv_eps,
-                                           uint64_t tile, uint32_t lane, uint64_t lA, uint64_t lB, bool inA, bool inB,
+                                           uint64_t tile, const LaneWeights &lw, uint64_t lA, uint64_t lB, bool inA, bool inB,
                                            int zpA[4], int zpB[4], bool &clamped, bool &confirmed) {
     int kA[4], kB[4];
     const float qa[4] = {me.qA.x, me.qA.y, me.qA.z, me.qA.w}, qb[4] = {me.qB.x, me.qB.y, me.qB.z, me.qB.w};
@@ -139,7 +182,11 @@ __device__ __forceinline__ int read_prefix(const Register &src, const NodeTile &
         kA[m] = key_cell(qa[m], inv_eps, clamped);
         kB[m] = key_cell(qb[m], inv_eps, clamped);
     }
-    const uint32_t want = MEMORY ? __builtin_amdgcn_readfirstlane(src.checks[tile]) : partner.check;
+    uint2 want = partner.check;
+    if (MEMORY) {
+        const uint2 c = src.checks[tile];
+        want = uint2{__builtin_amdgcn_readfirstlane(c.x), __builtin_amdgcn_readfirstlane(c.y)};
+    }
     uint32_t cA[4], cB[4];
     if (MEMORY) {
         const uint32_t a0 = __builtin_nontemporal_load((const uint16_t *)(src.p0 + lA / 2));
@@ -151,21 +198,21 @@ __device__ __forceinline__ int read_prefix(const Register &src, const NodeTile &
         for (int m = 0; m < 4; ++m) { cA[m] = (uint32_t)partner.zA[m] & 0xFFFFu; cB[m] = (uint32_t)partner.zB[m] & 0xFFFFu; }
     }
     confirmed = true;
-    if (decode_tile<4>(cA, cB, kA, kB, zpA, zpB, lane, inA, inB) == want) return 0;
+    if (same(decode_tile<4>(cA, cB, kA, kB, zpA, zpB, lw, inA, inB), want)) return 0;
     if (MEMORY) {
         const uint32_t a1 = __builtin_nontemporal_load((const uint16_t *)(src.p1 + lA / 2));
         const uint32_t b1 = __builtin_nontemporal_load((const uint16_t *)(src.p1 + lB / 2));
 #pragma unroll
         for (int m = 0; m < 4; ++m) { cA[m] |= ((a1 >> (4 * m)) & 15u) << 4; cB[m] |= ((b1 >> (4 * m)) & 15u) << 4; }
     }
-    if (decode_tile<8>(cA, cB, kA, kB, zpA, zpB, lane, inA, inB) == want) return 1;
+    if (same(decode_tile<8>(cA, cB, kA, kB, zpA, zpB, lw, inA, inB), want)) return 1;
     if (MEMORY) {
         const uint32_t a2 = __builtin_nontemporal_load((const uint32_t *)(src.p2 + lA));
         const uint32_t b2 = __builtin_nontemporal_load((const uint32_t *)(src.p2 + lB));
 #pragma unroll
         for (int m = 0; m < 4; ++m) { cA[m] |= ((a2 >> (8 * m)) & 255u) << 8; cB[m] |= ((b2 >> (8 * m)) & 255u) << 8; }
     }
-    confirmed = decode_tile<16>(cA, cB, kA, kB, zpA, zpB, lane, inA, inB) == want;
+    confirmed = same(decode_tile<16>(cA, cB, kA, kB, zpA, zpB, lw, inA, inB), want);
     return 2;
 }
 
@@ -225,11 +272,12 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_nodes_kernel(const PrefixAr
     const uint32_t node = second ? pd.nj : pd.ni, partner = second ? pd.ni : pd.nj;
     const uint32_t age = (pd.flags >> (second ? 8 : 0)) & 0xFFu, H = (pd.steps >> (second ? 8 : 0)) & 0xFFu;
     const bool pending = pd.flags & (second ? 1u << 17 : 1u << 16);
-    const NodeTile me = prepare<LOCAL, INPLACE, NOISE>(pa, node, H, pending, g.tile, g.lane, g.lA, g.lB, g.inA, g.inB);
+    const LaneWeights lw = lane_weights(g.lane);
+    const NodeTile me = prepare<LOCAL, INPLACE, NOISE>(pa, node, H, pending, g.tile, g.lane, g.lA, g.lB, g.inA, g.inB, lw);
     const Register src = register_of(a, (a.slot_now + a.ring_depth - age) % a.ring_depth, partner);
     int zpA[4], zpB[4];
     bool clamped = false, confirmed;
-    const int level = read_prefix<true>(src, me, me, a.inv_eps, g.tile, g.lane, g.lA, g.lB, g.inA, g.inB, zpA, zpB,
+    const int level = read_prefix<true>(src, me, me, a.inv_eps, g.tile, lw, g.lA, g.lB, g.inA, g.inB, zpA, zpB,
                                         clamped, confirmed);
     publish(a, node, me, g.tile, g.lane, g.kA, g.kB, g.inA, g.inB);
     finish(a, node, me, zpA, zpB, g.kA, g.kB, g.inA, g.inB);
@@ -245,20 +293,21 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_pairs_kernel(const PrefixAr
     if (!geometry(a.d, WAVES, g)) return;
     const PairDesc pd = a.pairs[blockIdx.y];
     const uint32_t si = pd.flags & 0xFFu, sj = (pd.flags >> 8) & 0xFFu;
+    const LaneWeights lw = lane_weights(g.lane);
     const NodeTile ti = prepare<LOCAL, INPLACE, NOISE>(pa, pd.ni, pd.steps & 0xFFu, pd.flags & (1u << 16), g.tile, g.lane,
-                                                       g.lA, g.lB, g.inA, g.inB);
+                                                       g.lA, g.lB, g.inA, g.inB, lw);
     const NodeTile tj = prepare<LOCAL, INPLACE, NOISE>(pa, pd.nj, (pd.steps >> 8) & 0xFFu, pd.flags & (1u << 17), g.tile,
-                                                       g.lane, g.lA, g.lB, g.inA, g.inB);
+                                                       g.lane, g.lA, g.lB, g.inA, g.inB, lw);
     int zjA[4], zjB[4], ziA[4], ziB[4];          // what i decodes of j, what j decodes of i
     bool clamped = false, conf_i, conf_j;
     int level_i, level_j;
     if (si) level_i = read_prefix<true>(register_of(a, (a.slot_now + a.ring_depth - si) % a.ring_depth, pd.nj), tj, ti,
-                                        a.inv_eps, g.tile, g.lane, g.lA, g.lB, g.inA, g.inB, zjA, zjB, clamped, conf_i);
-    else level_i = read_prefix<false>(Register{}, tj, ti, a.inv_eps, g.tile, g.lane, g.lA, g.lB, g.inA, g.inB, zjA, zjB,
+                                        a.inv_eps, g.tile, lw, g.lA, g.lB, g.inA, g.inB, zjA, zjB, clamped, conf_i);
+    else level_i = read_prefix<false>(Register{}, tj, ti, a.inv_eps, g.tile, lw, g.lA, g.lB, g.inA, g.inB, zjA, zjB,
                                       clamped, conf_i);
     if (sj) level_j = read_prefix<true>(register_of(a, (a.slot_now + a.ring_depth - sj) % a.ring_depth, pd.ni), ti, tj,
-                                        a.inv_eps, g.tile, g.lane, g.lA, g.lB, g.inA, g.inB, ziA, ziB, clamped, conf_j);
-    else level_j = read_prefix<false>(Register{}, ti, tj, a.inv_eps, g.tile, g.lane, g.lA, g.lB, g.inA, g.inB, ziA, ziB,
+                                        a.inv_eps, g.tile, lw, g.lA, g.lB, g.inA, g.inB, ziA, ziB, clamped, conf_j);
+    else level_j = read_prefix<false>(Register{}, ti, tj, a.inv_eps, g.tile, lw, g.lA, g.lB, g.inA, g.inB, ziA, ziB,
                                       clamped, conf_j);
     int fails = 0;                               // fresh reads: coordinates decoded to another point than the sender's
 #pragma unroll
@@ -284,7 +333,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_singles_kernel(const Prefix
     const uint32_t entry = a.singles[blockIdx.y];
     const uint32_t u = entry & SINGLE_NODE_MASK;
     const NodeTile t = prepare<LOCAL, INPLACE, NOISE>(pa, u, (entry >> 16) & 0xFFu, entry & SINGLE_PENDING, g.tile, g.lane,
-                                                      g.lA, g.lB, g.inA, g.inB);
+                                                      g.lA, g.lB, g.inA, g.inB, lane_weights(g.lane));
     publish(a, u, t, g.tile, g.lane, g.kA, g.kB, g.inA, g.inB);
     float *x = a.X + (uint64_t)u * a.d;
     if (LOCAL || (entry & SINGLE_PENDING)) {     // X_u <- X_u + delta (the rounded model q is X_u, or already X_u + delta)

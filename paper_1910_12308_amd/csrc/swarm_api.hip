@@ -246,8 +246,8 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     if (cfg->scale_policy > SWARM_SCALE_GLOBAL_LINF) return fail(nullptr, SWARM_EINVAL, "unknown scale policy");
     if (cfg->scale_policy == SWARM_SCALE_GLOBAL_LINF) {
         int exponent;
-        if (cfg->bits < 4 || std::frexp(cfg->eps, &exponent) != 0.5f)
-            return fail(nullptr, SWARM_EINVAL, "the per-round scale needs bits >= 4 and a power of two as starting eps");
+        if (cfg->bits < 8 || std::frexp(cfg->eps, &exponent) != 0.5f)
+            return fail(nullptr, SWARM_EINVAL, "the per-round scale needs bits >= 8 and a power of two as starting eps");
     }
     if (cfg->scale_policy == SWARM_SCALE_PAIR_LINF && (cfg->bits < 4 || cfg->stale_max != 0))
         return fail(nullptr, SWARM_EINVAL, "the per-pair scale needs bits >= 4 and stale_max = 0");
@@ -283,8 +283,8 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     h->stream = (hipStream_t)hip_stream;
     h->inv_eps = cfg->bits ? 1.0f / cfg->eps : 0.f;
     h->row_bytes = cfg->d * cfg->bits / 8;
-    if (cfg->codec == SWARM_CODEC_PREFIX)            // three planes (2 d bytes) and one checksum per tile
-        h->row_bytes += sizeof(uint32_t) * ((cfg->d + PREFIX_TILE - 1) / PREFIX_TILE);
+    if (cfg->codec == SWARM_CODEC_PREFIX)            // three planes (2 d bytes) and one 64-bit checksum per tile
+        h->row_bytes += 2 * sizeof(uint32_t) * ((cfg->d + PREFIX_TILE - 1) / PREFIX_TILE);
     h->pending.assign(cfg->n, 0);
 
     const uint32_t n = cfg->n;
@@ -680,7 +680,7 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     h->round += 1;
     h->interactions += npairs;
     if (c.codec == SWARM_CODEC_PREFIX)      // first plane and checksums of every read; escalations are counted on the device
-        h->bits_communicated += 2ull * npairs * (c.d * 4 + 32ull * ((c.d + PREFIX_TILE - 1) / PREFIX_TILE));
+        h->bits_communicated += 2ull * npairs * (c.d * 4 + 64ull * ((c.d + PREFIX_TILE - 1) / PREFIX_TILE));
     else
         h->bits_communicated += 2ull * npairs * c.d * (c.bits ? c.bits : 32);
     h->prefix_tile_reads += c.codec == SWARM_CODEC_PREFIX ? 2ull * npairs * ((c.d + PREFIX_TILE - 1) / PREFIX_TILE) : 0ull;

@@ -27,7 +27,7 @@ def register_window(g, gpu, node, k0, width, bits, prefix, d):
     return np.concatenate([g.read_codes(node, byte0=k0 // 2, length=width // 2),               # bits 0-3
                            g.read_codes(node, byte0=d // 2 + k0 // 2, length=width // 2),      # bits 4-7
                            g.read_codes(node, byte0=d + k0, length=width),                     # bits 8-15
-                           g.read_codes(node, byte0=2 * d + 4 * (k0 // 512), length=4 * (width // 512))])
+                           g.read_codes(node, byte0=2 * d + 8 * (k0 // 512), length=8 * (width // 512))])
 
 
 @pytest.mark.parametrize("cfg_id,eps,mode", [(2, 2.0 ** -4, "two calls"), (4, 0.5, "two calls"), (5, 0.25, "two calls"),
