@@ -311,26 +311,41 @@ def test_algorithm1_free_running_matches_statistically(gpu):
     assert d1 < d0
 
 
-def test_round_mode_free_running_matches_statistically(gpu):
-    """40 rounds on a torus with noisy diagonal quadratics, matching sampled on the device."""
-    n, d, H, lr, bits, eps = 16, 8192, 3, 0.1, 8, 2.0 ** -4
+@pytest.mark.parametrize("mode", ["fixed scale", "per-round scale, stale reads", "prefix registers, stale reads, one pass"])
+def test_round_mode_free_running_matches_statistically(gpu, mode):
+    """40 rounds on a torus with noisy diagonal quadratics, matching and staleness sampled on the device,
+    nothing forced: the potential follows the oracle's to 2 %, the models stay within a few lattice
+    steps, and the integer bookkeeping that does not depend on last-bit differences is equal."""
+    n, d, H, lr, eps = 16, 8192, 3, 0.1, 2.0 ** -4
     edges = wl.torus_graph(4, 4)
     a, cc = wl.diag_quadratic_data(n, d, 2)
-    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, 0, seed=3)
+    bits, S = (16, 2) if mode.startswith("prefix") else (8, 2 if "stale" in mode else 0)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=3, global_scale=mode.startswith("per-round"),
+                     prefix=mode.startswith("prefix"))
     c.objective = DiagQuadratic(a, cc, 0.1)
     g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.1)
     gam_g, gam_c = [], []
     for r in range(40):
+        stale = c.sample_stale() if S else None
         c.local_steps()
-        g.local_steps()
-        c.gossip_round(c.sample_matching())
-        g.gossip_round(None)
+        c.gossip_round(c.sample_matching(), stale)
+        if mode.endswith("one pass"):
+            g.round_fused(None, None if stale is None else g.sample_stale())
+        else:
+            g.local_steps()
+            g.gossip_round(None, None if stale is None else g.sample_stale())
         gam_g.append(g.potential())
         gam_c.append(c.potential())
     assert np.allclose(gam_g, gam_c, rtol=0.02)
     assert g.counters()["interactions"] == c.interactions
     X = g.read_models(gpu.COMM).astype(np.float64)
-    assert np.abs(X - c.X).max() <= 8 * eps
+    assert np.abs(X - c.X).max() <= 8 * max(eps, float(c.eps_cur))
+    if mode.startswith("per-round"):
+        assert g.scale()[0] == float(c.eps_cur)              # a power of two: robust to last-bit differences
+    if mode.startswith("prefix"):
+        tiles, unconfirmed = g.prefix_stats()
+        assert unconfirmed == 0 == c.prefix_unconfirmed and sum(tiles) == int(c.prefix_levels.sum())
+        assert abs(tiles[0] - int(c.prefix_levels[0])) <= 0.02 * sum(tiles)
 
 
 # ------------------------------------------------------------------ MLP local steps (MFMA GEMMs)
