@@ -76,7 +76,7 @@ hipError_t launch_local_diag(const float *X, float *W, const float *a, const flo
                              const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
                              uint32_t event, hipStream_t st);
 
-// Round kernels for multi-resolution registers (16-bit code in three planes plus tile checksums, read by
+// Round kernels for multi-resolution registers (16-bit code in three planes plus 64-bit tile checksums, read by
 // prefixes).  kind: 0 = pairs with any mix of fresh and stale reads, 1 = pairs whose reads are both stale,
 // 2 = unmatched nodes (rows = their number).  local: objective of the one-pass round, or null.
 struct DiagObjective;
@@ -104,7 +104,7 @@ hipError_t launch_pair_linf_desc(const float *X, uint64_t d, const PairDesc *pai
 // Streaming copy of nbytes (multiple of 16, below 2^36) from src to dst.
 hipError_t launch_stream_copy(const void *src, void *dst, uint64_t nbytes, hipStream_t st);
 // n_read streams of stream_bytes each (consecutive in src) summed into n_write streams (consecutive in
-// dst); supported shapes (n_read, n_write): (2,2), (4,2), (6,2).
+// dst; write stream w gets the sum plus w); supported shapes (n_read, n_write): (2,1), (3,1), (2,2), (4,2), (6,2).
 hipError_t launch_stream_mix(const void *src, void *dst, uint64_t stream_bytes, uint32_t n_read, uint32_t n_write,
                              hipStream_t st);
 
