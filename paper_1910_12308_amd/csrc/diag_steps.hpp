@@ -11,13 +11,14 @@
 namespace swarm {
 
 #if defined(__HIPCC__)
-// Two standard normals from one word: u1 = (low half + 1/2) 2^-16 in (0,1), u2 = high half * 2^-16
-// in [0,1); (r cos 2 pi u2, r sin 2 pi u2), r = sqrt(-2 ln u1).  Hardware log2 / sqrt / sine /
-// cosine (the latter two take revolutions, so u2 needs no range reduction).
-__device__ __forceinline__ void box_muller16(uint32_t w, float &n0, float &n1) {
+// Two normals of standard deviation sigma from one word: u1 = (low half + 1/2) 2^-16 in (0,1),
+// u2 = high half * 2^-16 in [0,1); (r cos 2 pi u2, r sin 2 pi u2), r = sigma sqrt(-2 ln u1), with
+// sigma^2 folded into the factor of the logarithm: scale = -2 ln 2 sigma^2.  Hardware log2 / sqrt /
+// sine / cosine (the latter two take revolutions, so u2 needs no range reduction).
+__device__ __forceinline__ void box_muller16(uint32_t w, float scale, float &n0, float &n1) {
     const float u1 = fmaf((float)(w & 0xFFFFu), 0x1p-16f, 0x1p-17f);
     const float u2 = (float)(w >> 16) * 0x1p-16f;
-    const float r = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u1));   // -2 ln 2 * log2 u1
+    const float r = __builtin_amdgcn_sqrtf(scale * __builtin_amdgcn_logf(u1));
     n0 = r * __builtin_amdgcn_cosf(u2);
     n1 = r * __builtin_amdgcn_sinf(u2);
 }
@@ -41,6 +42,7 @@ __device__ __forceinline__ void diag_steps(f4 &wA, f4 &wB, const f4 aA, const f4
                                            float sigma, uint64_t seed, uint32_t event) {
     const bool odd = lane & 1u;
     const uint64_t group = tile * (TILE / 8) + (lane >> 1) + (odd ? 32u : 0u);
+    const float scale = -1.3862943611198906f * sigma * sigma;     // -2 ln 2 sigma^2
     for (uint32_t q = 0; q < H; ++q) {
         f4 nA = {0.f, 0.f, 0.f, 0.f}, nB = nA;
         if (NOISE) {
@@ -50,12 +52,12 @@ __device__ __forceinline__ void diag_steps(f4 &wA, f4 &wB, const f4 aA, const f4
             const uint32_t r0 = swap_with_neighbour(odd ? w.w0 : w.w2);
             const uint32_t r1 = swap_with_neighbour(odd ? w.w1 : w.w3);
             float z0, z1, z2, z3, z4, z5, z6, z7;
-            box_muller16(odd ? r0 : w.w0, z0, z1);
-            box_muller16(odd ? r1 : w.w1, z2, z3);
-            box_muller16(odd ? w.w2 : r0, z4, z5);
-            box_muller16(odd ? w.w3 : r1, z6, z7);
-            nA = f4{z0, z1, z2, z3} * sigma;
-            nB = f4{z4, z5, z6, z7} * sigma;
+            box_muller16(odd ? r0 : w.w0, scale, z0, z1);
+            box_muller16(odd ? r1 : w.w1, scale, z2, z3);
+            box_muller16(odd ? w.w2 : r0, scale, z4, z5);
+            box_muller16(odd ? w.w3 : r1, scale, z6, z7);
+            nA = f4{z0, z1, z2, z3};
+            nB = f4{z4, z5, z6, z7};
         }
         wA = diag_update(wA, aA, cA, nA, lr);
         wB = diag_update(wB, aB, cB, nB, lr);
