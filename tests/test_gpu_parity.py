@@ -386,12 +386,14 @@ def test_local_steps_mlp(gpu, shape):
 
 
 # ------------------------------------------------------------------ in-place apply mode
-def test_inplace_apply_mode_rounds(gpu):
+@pytest.mark.parametrize("registers", ["fixed", "per-round scale", "prefix"])
+def test_inplace_apply_mode_rounds(gpu, registers):
     """One matrix: the local steps update the exchanged model, the averaging acts on the result."""
-    n, d, H, lr, bits, eps, S = 8, D_RAGGED, 3, 0.1, 8, 2.0 ** -4, 1
+    n, d, H, lr, bits, eps, S = 8, D_RAGGED, 3, 0.1, 16 if registers == "prefix" else 8, 2.0 ** -4, 1
     edges = wl.torus_graph(2, 4)
     a, cc = wl.diag_quadratic_data(n, d, 7)
-    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=31, inplace=True)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=31, inplace=True,
+                     global_scale=registers == "per-round scale", prefix=registers == "prefix")
     c.objective = DiagQuadratic(a, cc, 0.05)
     g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
     gen = np.random.Generator(np.random.PCG64(31))
@@ -409,6 +411,10 @@ def test_inplace_apply_mode_rounds(gpu):
         for i in range(n):
             assert np.array_equal(g.read_codes(i), ring_row(c, i)), (r, i)
         assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, f"X after round {r}")
+        if registers == "per-round scale":
+            assert g.scale() == (float(c.eps_cur), float(c.max_disagreement))
+        if registers == "prefix":
+            assert g.prefix_stats() == (c.prefix_levels.tolist(), c.prefix_unconfirmed)
     with pytest.raises(gpu.SwarmError):
         g.interact(0, 1)
 
