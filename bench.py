@@ -229,6 +229,9 @@ def main():
     ap.add_argument("--prefix", action="store_true",
                     help="multi-resolution registers: 16-bit codes in planes, readers fetch the shortest confirmed "
                          "prefix (instead of the configuration's fixed b bits)")
+    ap.add_argument("--global-scale", action="store_true",
+                    help="one lattice scale per round, set from the disagreement the previous round reported "
+                         "(needs a configuration with at least 8-bit codes)")
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
     ap.add_argument("--H", type=int, default=None,
                     help="override the number of local steps (to find where a kernel turns ALU-bound)")
@@ -258,7 +261,8 @@ def main():
     else:
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0,
                         apply_mode=swarm.INPLACE if args.inplace else swarm.DEFERRED,
-                        codec=swarm.CODEC_PREFIX if args.prefix else swarm.CODEC_FIXED)
+                        codec=swarm.CODEC_PREFIX if args.prefix else swarm.CODEC_FIXED,
+                        scale_policy=swarm.SCALE_GLOBAL_LINF if args.global_scale else swarm.SCALE_FIXED)
         s.set_objective_diag(a, c, cfg["sigma"])
 
     def step_sequential():
@@ -325,6 +329,8 @@ def main():
                                f"sigma={cfg.get('sigma', cfg.get('data_sigma'))} H={cfg['H']} lr={cfg['lr']} bits={bits} "
                                f"stale_max={cfg['stale_max']} ({cfg.get('stale', 'fresh')}) eps={eps}",
                    "apply_mode": "inplace" if args.inplace else "deferred",
+                   **({"scale": "per round (SWARM_SCALE_GLOBAL_LINF)", "eps_after_the_run": s.scale()[0]}
+                      if args.global_scale else {}),
                    "step": ("one-pass round (swarm_round_fused)" if use_one_pass
                             else "swarm_sample_pair + swarm_interact (Algorithm 1)" if cfg["mode"] == "sequential"
                             else "swarm_local_steps + swarm_gossip_round"),

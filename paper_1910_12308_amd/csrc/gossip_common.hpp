@@ -112,12 +112,19 @@ __device__ __forceinline__ f4 averaged_mixed(const int z_own[4], uint64_t partne
     return f4{o[0], o[1], o[2], o[3]};
 }
 
-// Largest disagreement of the wave into the round's maximum (float bits order like the floats: all >= 0).
+// Largest disagreement of the wave into the stripe of its workgroup (float bits order like the floats:
+// all >= 0).  Row maxima through DPP, the four rows through lane reads; the plain load only filters.
 __device__ __forceinline__ void report_far(uint32_t *far_bits, float far) {
-    for (int off = 32; off > 0; off >>= 1) far = fmaxf(far, __shfl_xor(far, off));
+    far = fmaxf(far, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, far), 0xB1, 0xF, 0xF, true)));
+    far = fmaxf(far, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, far), 0x4E, 0xF, 0xF, true)));
+    far = fmaxf(far, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, far), 0x141, 0xF, 0xF, true)));
+    far = fmaxf(far, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, far), 0x140, 0xF, 0xF, true)));
+    const uint32_t v = __float_as_uint(far);
+    const uint32_t b = max(max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16)),
+                           max((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48)));
     if ((threadIdx.x & 63) == 0) {
-        const uint32_t b = __float_as_uint(far);
-        if (b > __atomic_load_n(far_bits, __ATOMIC_RELAXED)) atomicMax(far_bits, b);
+        uint32_t *stripe = far_bits + ((blockIdx.x + 977u * blockIdx.y) & (FAR_STRIPES - 1));
+        if (b > __atomic_load_n(stripe, __ATOMIC_RELAXED)) atomicMax(stripe, b);
     }
 }
 

@@ -43,7 +43,9 @@ struct GossipArgs {
                               // null when the lattice scale is fixed
     const float *eps_slots;   // device: lattice scale of the codes in each ring slot (one scale per round), or
                               // null when the scale is fixed or per pair
-    uint32_t *far_bits;       // device: float bits of the round's largest |key - decoded partner| (with eps_slots)
+    uint32_t *far_bits;       // device: FAR_STRIPES words, each the float bits of the largest |key - decoded
+                              // partner| reported into it this round (with eps_slots); the round's maximum is
+                              // their maximum
     PrefixStats *prefix_stats; // device: PREFIX_STRIPES entries (multi-resolution registers), or null
     DeviceCounters *counters;
     uint64_t d;
@@ -85,9 +87,11 @@ hipError_t launch_prefix(const GossipArgs &g, const DiagObjective *local, bool i
 constexpr uint32_t PREFIX_TILE = 512;      // coordinates per checksum (one wave tile)
 
 // One lattice scale per round: state[0] = float bits of the coming round's scale, state[1] = float bits of
-// the largest disagreement seen by the round in flight, state[2] = the same of the last round with pairs.
-// Closes a round: next scale = max(pair_scale(2 m), eps / 2) if the round had pairs, written to the next
-// ring slot's entry of eps_slots; clears state[1].
+// the largest disagreement of the last round that had pairs, state[2 .. 2 + FAR_STRIPES) = the stripes the
+// workgroups of the round in flight report their disagreement into (spread so that they do not serialise
+// on one address).  Closes a round: m = maximum of the stripes, next scale = max(pair_scale(2 m), eps / 2)
+// if the round had pairs, written to the next ring slot's entry of eps_slots; clears the stripes.
+constexpr uint32_t FAR_STRIPES = 256;
 hipError_t launch_scale_close(float *eps_slots, uint32_t *state, uint32_t slot_now, uint32_t ring_depth,
                               uint32_t bits, uint32_t npairs, hipStream_t st);
 

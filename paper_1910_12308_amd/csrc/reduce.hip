@@ -113,24 +113,29 @@ hipError_t launch_pair_linf_desc(const float *X, uint64_t d, const PairDesc *pai
 // One lattice scale per round.  After a round: the largest |key - decoded partner| it saw sets the
 // next round's scale, the smallest power of two that puts twice that distance inside the decoding
 // radius, but no less than half the current scale (a round without pairs keeps the scale).
-__global__ void scale_close_kernel(float *eps_slots, uint32_t *state, uint32_t slot_now, uint32_t ring_depth,
-                                   uint32_t bits, uint32_t npairs) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+__global__ __launch_bounds__(FAR_STRIPES) void scale_close_kernel(float *eps_slots, uint32_t *state, uint32_t slot_now,
+                                                                  uint32_t ring_depth, uint32_t bits, uint32_t npairs) {
+    __shared__ uint32_t lds[FAR_STRIPES / 64];
+    uint32_t m = state[2 + threadIdx.x];
+    state[2 + threadIdx.x] = 0u;
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    for (uint32_t w = 1; w < FAR_STRIPES / 64; ++w) m = max(m, lds[w]);
     const float eps = eps_slots[slot_now];
     float next = eps;
     if (npairs) {
-        const float m = __uint_as_float(state[1]);
-        next = fmaxf(pair_scale(2.0f * m, (int)bits), 0.5f * eps);
-        state[2] = state[1];
+        next = fmaxf(pair_scale(2.0f * __uint_as_float(m), (int)bits), 0.5f * eps);
+        state[1] = m;
     }
     state[0] = __float_as_uint(next);
-    state[1] = 0u;
     eps_slots[(slot_now + 1) % ring_depth] = next;
 }
 
 hipError_t launch_scale_close(float *eps_slots, uint32_t *state, uint32_t slot_now, uint32_t ring_depth,
                               uint32_t bits, uint32_t npairs, hipStream_t st) {
-    scale_close_kernel<<<1, 64, 0, st>>>(eps_slots, state, slot_now, ring_depth, bits, npairs);
+    scale_close_kernel<<<1, FAR_STRIPES, 0, st>>>(eps_slots, state, slot_now, ring_depth, bits, npairs);
     return hipGetLastError();
 }
 

@@ -42,7 +42,7 @@ struct swarm_ctx {
     uint32_t *linf_dev = nullptr, *steps_dev = nullptr;   // steps_dev: local steps per node id (geometric law)
     PrefixStats *prefix_stats_dev = nullptr;   // multi-resolution registers: striped escalation counts
     float *eps_slots_dev = nullptr;     // one scale per round: scale of the codes in each ring slot
-    uint32_t *scale_state_dev = nullptr; // [0] next scale, [1] disagreement of the round in flight, [2] of the last
+    uint32_t *scale_state_dev = nullptr; // [0] next scale, [1] disagreement of the last round with pairs, then the stripes
     uint8_t *desc_dev = nullptr;                 // PairDesc[n/2] | singles[n]
     DeviceCounters *counters_dev = nullptr;
     double *partials_dev = nullptr, *gamma_dev = nullptr;
@@ -106,7 +106,7 @@ GossipArgs gossip_args(swarm_t h, uint32_t event, uint32_t slot) {
     a.eps = h->cfg.eps; a.inv_eps = h->inv_eps;
     a.eps_slots = h->eps_slots_dev;
     a.prefix_stats = h->prefix_stats_dev;
-    a.far_bits = h->scale_state_dev ? h->scale_state_dev + 1 : nullptr;
+    a.far_bits = h->scale_state_dev ? h->scale_state_dev + 2 : nullptr;
     return a;
 }
 
@@ -316,12 +316,12 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         }
         if (cfg->scale_policy == SWARM_SCALE_GLOBAL_LINF) {
             const std::vector<float> slots(cfg->stale_max + 1, cfg->eps);
-            uint32_t state[3] = {0u, 0u, 0u};
+            std::vector<uint32_t> state(2 + FAR_STRIPES, 0u);
             std::memcpy(&state[0], &cfg->eps, sizeof(float));
             SWARM_HIP(h, hipMalloc((void **)&h->eps_slots_dev, sizeof(float) * slots.size()));
-            SWARM_HIP(h, hipMalloc((void **)&h->scale_state_dev, sizeof(state)));
+            SWARM_HIP(h, hipMalloc((void **)&h->scale_state_dev, sizeof(uint32_t) * state.size()));
             SWARM_HIP(h, hipMemcpy(h->eps_slots_dev, slots.data(), sizeof(float) * slots.size(), hipMemcpyHostToDevice));
-            SWARM_HIP(h, hipMemcpy(h->scale_state_dev, state, sizeof(state), hipMemcpyHostToDevice));
+            SWARM_HIP(h, hipMemcpy(h->scale_state_dev, state.data(), sizeof(uint32_t) * state.size(), hipMemcpyHostToDevice));
         }
         SWARM_HIP(h, hipMalloc((void **)&h->desc_dev, h->desc_bytes));
         SWARM_HIP(h, hipMalloc((void **)&h->mpairs_dev, sizeof(uint32_t) * 2 * (n / 2)));
@@ -838,14 +838,14 @@ swarm_status swarm_potential(swarm_t h, double *gamma_host, float *mu_dev) {
 
 swarm_status swarm_scale(swarm_t h, float *eps_next, float *disagreement) {
     if (!h) return SWARM_EINVAL;
-    uint32_t state[3] = {0u, 0u, 0u};
+    uint32_t state[2] = {0u, 0u};
     std::memcpy(&state[0], &h->cfg.eps, sizeof(float));
     if (h->scale_state_dev) {
         SWARM_HIP(h, hipStreamSynchronize(h->stream));
         SWARM_HIP(h, hipMemcpy(state, h->scale_state_dev, sizeof(state), hipMemcpyDeviceToHost));
     }
     if (eps_next) std::memcpy(eps_next, &state[0], sizeof(float));
-    if (disagreement) std::memcpy(disagreement, &state[2], sizeof(float));
+    if (disagreement) std::memcpy(disagreement, &state[1], sizeof(float));
     return SWARM_OK;
 }
 
