@@ -46,3 +46,26 @@ def test_product_package_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".hpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
+
+
+def test_header_is_plain_c_and_the_config_struct_matches_the_binding(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own, and the binding's ctypes mirror of
+    swarm_config has the size and field offsets the C compiler gives."""
+    import ctypes
+    import shutil
+    import subprocess
+    import paper_1910_12308_amd as swarm
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    fields = [name for name, _ in swarm._Config._fields_]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "swarm.h"\nint main(void) {\n'
+                   '  printf("%zu\\n", sizeof(swarm_config));\n'
+                   + "".join(f'  printf("%zu\\n", offsetof(swarm_config, {f}));\n' for f in fields)
+                   + "  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert out[0] == ctypes.sizeof(swarm._Config)
+    assert out[1:] == [getattr(swarm._Config, f).offset for f in fields]
