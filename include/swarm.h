@@ -43,7 +43,7 @@ typedef enum {
 } swarm_status;
 
 /* When the local steps reach the exchanged model.  DEFERRED (the paper: the node computes its
- * local gradients, "which it does not yet apply", averages the quantized models, then adds the
+ * local gradients, holds them back, averages the quantized models, then adds the
  * summed update to the average): X is exchanged, W = X - eta h~ lives in a second matrix.
  * INPLACE: the local steps update the exchanged model directly and the averaging acts on the
  * updated models; one matrix, no pending update (W is an alias of X). */
@@ -149,7 +149,7 @@ swarm_status swarm_set_objective_mlp(swarm_t h, uint32_t n_in, uint32_t n_hid, u
 
 /* Local steps (Section 3 "The Communication Procedure"; appendix, definition of
  * h~_i^q): for q = 1..H, w <- w - eta g~_i(w) starting from the node's current model X_i,
- * result stored in W_i and marked pending (computed, "not yet applied").
+ * result stored in W_i and marked pending (computed, applied only after the averaging).
  * nodes: host array of `count` distinct node ids, or NULL for all nodes. */
 swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count);
 

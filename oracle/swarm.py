@@ -2,8 +2,8 @@
 
 Test infrastructure only.  State (columns [k0, k1) of each):
   X     current / communicated model of every node  ("current model" register)
-  W     live copy carrying the local steps not yet applied (the node "computes
-        H local gradient steps, which it does not yet apply")
+  W     live copy carrying the local steps that have been computed but are only
+        applied after the averaging (Section 3, description of an interaction)
   Xhat  model at the node's last initiation (sequential model only)
   ring  S+1 slots of packed codes: slot r mod (S+1) holds Enc(X_r) of every node
 All node models start equal (Algorithm 1, initial models), zero by default.
