@@ -224,6 +224,17 @@ swarm_status swarm_read_models(swarm_t h, uint32_t which, uint32_t node0, uint32
                                uint64_t k0, uint64_t len, float *dst_host);
 swarm_status swarm_write_models(swarm_t h, uint32_t which, uint32_t node0, uint32_t count,
                                 uint64_t k0, uint64_t len, const float *src_host);
+/* Exact resume.  Every random draw is a function of (seed, round or interaction number, ids), so
+ * the model matrices, the registers, the counters, the pending marks and the round counters are the
+ * whole state of a run: a handle created with the same configuration and graph that loads the image
+ * continues bit for bit as the saved one would have (objective data are borrowed and not part of
+ * it: set the objective again).  swarm_state_bytes gives the image size for the handle as it stands;
+ * images are host memory; a load into a handle of another configuration is SWARM_EINVAL.
+ * All three synchronise. */
+swarm_status swarm_state_bytes(swarm_t h, uint64_t *nbytes);
+swarm_status swarm_save_state(swarm_t h, void *dst_host, uint64_t nbytes);
+swarm_status swarm_load_state(swarm_t h, const void *src_host, uint64_t nbytes);
+
 /* Device address of a model matrix (n x d floats, row-major), for zero-copy views. */
 swarm_status swarm_models_ptr(swarm_t h, uint32_t which, float **ptr_dev);
 

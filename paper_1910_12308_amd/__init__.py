@@ -26,6 +26,7 @@ EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set
            "swarm_set_objective_mlp", "swarm_local_steps", "swarm_mark_pending", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
            "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
+           "swarm_state_bytes", "swarm_save_state", "swarm_load_state",
            "swarm_potential", "swarm_pair_linf", "swarm_scale", "swarm_prefix_stats", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
            "swarm_stream_copy", "swarm_stream_mix", "swarm_last_error"]
 
@@ -71,6 +72,9 @@ def load_library():
         "swarm_read_models": [vp, u32, u32, u32, u64, u64, vp],
         "swarm_write_models": [vp, u32, u32, u32, u64, u64, vp],
         "swarm_models_ptr": [vp, u32, P(vp)],
+        "swarm_state_bytes": [vp, P(u64)],
+        "swarm_save_state": [vp, vp, u64],
+        "swarm_load_state": [vp, vp, u64],
         "swarm_read_codes": [vp, u32, u32, u64, u64, vp],
         "swarm_potential": [vp, P(ctypes.c_double), vp],
         "swarm_pair_linf": [vp, vp, u32, vp],
@@ -259,6 +263,18 @@ class Swarm:
         ptr = ctypes.c_void_p()
         self._check(self._lib.swarm_models_ptr(self._h, which, ctypes.byref(ptr)))
         return torch.as_tensor(_DeviceView(ptr.value, (self.n, self.d), self), device="cuda")
+
+    def save_state(self):
+        """The whole state of the run as a host byte array (exact resume with load_state)."""
+        size = ctypes.c_uint64()
+        self._check(self._lib.swarm_state_bytes(self._h, ctypes.byref(size)))
+        image = np.empty(size.value, dtype=np.uint8)
+        self._check(self._lib.swarm_save_state(self._h, image.ctypes.data_as(ctypes.c_void_p), image.size))
+        return image
+
+    def load_state(self, image):
+        image = np.ascontiguousarray(image, dtype=np.uint8)
+        self._check(self._lib.swarm_load_state(self._h, image.ctypes.data_as(ctypes.c_void_p), image.size))
 
     def read_codes(self, node, age=0, byte0=0, length=None):
         length = self.row_bytes - byte0 if length is None else length

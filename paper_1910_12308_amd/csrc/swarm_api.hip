@@ -797,6 +797,110 @@ swarm_status swarm_write_models(swarm_t h, uint32_t which, uint32_t node0, uint3
     return SWARM_OK;
 }
 
+// ---- exact resume -----------------------------------------------------------------------------
+// Every random draw is a function of (seed, round or interaction number, ids), so the models, the
+// registers, the counters and a few integers are the whole state of a run.
+namespace {
+
+struct StateHeader {
+    uint64_t magic, d, seed, round, interactions, bits_communicated, prefix_tile_reads;
+    uint32_t version, n, bits, stale_max, apply_mode, codec, scale_policy, has_snapshots;
+    float eps;
+    uint32_t pad;
+};
+constexpr uint64_t STATE_MAGIC = 0x31657461745377ull;   // "wStatE1" little-endian, zero-padded
+
+struct StatePart { void *dev; size_t bytes; };
+
+// Device blocks of a state image, in order; `snapshots` as in the image being written or read.
+void state_parts(swarm_t h, bool snapshots, std::vector<StatePart> &parts) {
+    const swarm_config &c = h->cfg;
+    const size_t model_bytes = (size_t)c.n * c.d * sizeof(float);
+    parts.clear();
+    parts.push_back({h->X, model_bytes});
+    if (c.apply_mode == SWARM_APPLY_DEFERRED) parts.push_back({h->W, model_bytes});
+    if (snapshots) parts.push_back({h->Xhat, model_bytes});
+    if (c.bits) parts.push_back({h->ring, (size_t)(c.stale_max + 1) * c.n * h->row_bytes});
+    parts.push_back({h->counters_dev, sizeof(DeviceCounters)});
+    if (h->prefix_stats_dev) parts.push_back({h->prefix_stats_dev, sizeof(PrefixStats) * PREFIX_STRIPES});
+    if (h->eps_slots_dev) {
+        parts.push_back({h->eps_slots_dev, sizeof(float) * (c.stale_max + 1)});
+        parts.push_back({h->scale_state_dev, sizeof(uint32_t) * (2 + FAR_STRIPES)});
+    }
+}
+
+uint64_t state_size(swarm_t h, bool snapshots) {
+    uint64_t total = sizeof(StateHeader) + ((h->cfg.n + 7u) & ~7u);
+    std::vector<StatePart> parts;
+    state_parts(h, snapshots, parts);
+    for (const StatePart &p : parts) total += (p.bytes + 7u) & ~(size_t)7u;
+    return total;
+}
+
+}  // namespace
+
+swarm_status swarm_state_bytes(swarm_t h, uint64_t *nbytes) {
+    if (!h || !nbytes) return SWARM_EINVAL;
+    *nbytes = state_size(h, h->Xhat != nullptr);
+    return SWARM_OK;
+}
+
+swarm_status swarm_save_state(swarm_t h, void *dst_host, uint64_t nbytes) {
+    if (!h) return SWARM_EINVAL;
+    const bool snapshots = h->Xhat != nullptr;
+    if (!dst_host || nbytes < state_size(h, snapshots)) return fail(h, SWARM_EINVAL, "state buffer missing or too small");
+    const swarm_config &c = h->cfg;
+    StateHeader hd{};
+    hd.magic = STATE_MAGIC; hd.version = 1;
+    hd.d = c.d; hd.seed = c.seed; hd.n = c.n; hd.bits = c.bits; hd.stale_max = c.stale_max;
+    hd.apply_mode = c.apply_mode; hd.codec = c.codec; hd.scale_policy = c.scale_policy; hd.eps = c.eps;
+    hd.has_snapshots = snapshots;
+    hd.round = h->round; hd.interactions = h->interactions; hd.bits_communicated = h->bits_communicated;
+    hd.prefix_tile_reads = h->prefix_tile_reads;
+    uint8_t *out = (uint8_t *)dst_host;
+    std::memcpy(out, &hd, sizeof(hd));
+    out += sizeof(hd);
+    std::memset(out, 0, (c.n + 7u) & ~7u);
+    std::memcpy(out, h->pending.data(), c.n);
+    out += (c.n + 7u) & ~7u;
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    std::vector<StatePart> parts;
+    state_parts(h, snapshots, parts);
+    for (const StatePart &p : parts) {
+        SWARM_HIP(h, hipMemcpy(out, p.dev, p.bytes, hipMemcpyDeviceToHost));
+        out += (p.bytes + 7u) & ~(size_t)7u;
+    }
+    return SWARM_OK;
+}
+
+swarm_status swarm_load_state(swarm_t h, const void *src_host, uint64_t nbytes) {
+    if (!h) return SWARM_EINVAL;
+    if (!src_host || nbytes < sizeof(StateHeader)) return fail(h, SWARM_EINVAL, "state image missing or truncated");
+    const swarm_config &c = h->cfg;
+    StateHeader hd;
+    std::memcpy(&hd, src_host, sizeof(hd));
+    if (hd.magic != STATE_MAGIC || hd.version != 1) return fail(h, SWARM_EINVAL, "not a state image of this library version");
+    if (hd.n != c.n || hd.d != c.d || hd.bits != c.bits || hd.stale_max != c.stale_max || hd.apply_mode != c.apply_mode ||
+        hd.codec != c.codec || hd.scale_policy != c.scale_policy || hd.seed != c.seed || hd.eps != c.eps)
+        return fail(h, SWARM_EINVAL, "state image belongs to a swarm of another configuration");
+    if (hd.has_snapshots) SWARM_TRY(ensure_snapshots(h));
+    if (nbytes < state_size(h, hd.has_snapshots != 0)) return fail(h, SWARM_EINVAL, "state image truncated");
+    const uint8_t *in = (const uint8_t *)src_host + sizeof(hd);
+    h->pending.assign(in, in + c.n);
+    in += (c.n + 7u) & ~7u;
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    std::vector<StatePart> parts;
+    state_parts(h, hd.has_snapshots != 0, parts);
+    for (const StatePart &p : parts) {
+        SWARM_HIP(h, hipMemcpy(p.dev, in, p.bytes, hipMemcpyHostToDevice));
+        in += (p.bytes + 7u) & ~(size_t)7u;
+    }
+    h->round = hd.round; h->interactions = hd.interactions; h->bits_communicated = hd.bits_communicated;
+    h->prefix_tile_reads = hd.prefix_tile_reads;
+    h->match_round = ~0ull;          // a matching enqueued for the old round counter is of no use now
+    return SWARM_OK;
+}
+
 swarm_status swarm_models_ptr(swarm_t h, uint32_t which, float **ptr_dev) {
     if (!h) return SWARM_EINVAL;
     if (!ptr_dev || which > SWARM_MODELS_SNAP) return fail(h, SWARM_EINVAL, "unknown model matrix");

@@ -883,3 +883,56 @@ def test_row_lengths_around_the_tile_edges(gpu, d):
                     assert np.array_equal(g.read_codes(i), ring_row(c, i)), f"{what}: codes of node {i}, bits {bits}, round {r}"
                 assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"{what}: X, bits {bits}, round {r}")
                 assert g.counters()["decode_failures"] == c.decode_failures
+
+
+@pytest.mark.parametrize("kind", ["fixed", "per-round scale", "prefix", "algorithm 1"])
+def test_saved_state_resumes_bit_for_bit(gpu, kind):
+    """Three steps, save, three more; a fresh handle of the same configuration loads the image and
+    takes the same three steps: models, registers, counters and the scale are identical."""
+    n, d, H, lr, eps = 8, D_RAGGED, 2, 0.1, 2.0 ** -4
+    edges = wl.torus_graph(2, 4)
+    a, cc = wl.diag_quadratic_data(n, d, 9)
+    ad, cd = torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda()
+    sequential = kind == "algorithm 1"
+    bits, S = (16 if kind == "prefix" else 8), (0 if sequential else 2)
+    kw = dict(scale_policy=gpu.SCALE_GLOBAL_LINF if kind == "per-round scale" else gpu.SCALE_FIXED,
+              codec=gpu.CODEC_PREFIX if kind == "prefix" else gpu.CODEC_FIXED)
+
+    def fresh():
+        s = gpu.Swarm(n, d, edges, bits, eps, H, lr, S, 21, **kw)
+        s.set_objective_diag(ad, cd, 0.05)
+        return s
+
+    def step(s, r):
+        if sequential:
+            s.interact(*s.sample_pair())
+        elif r % 2:
+            s.round_fused(None, s.sample_stale())
+        else:
+            s.local_steps([0, 3, 5])                          # leaves pending marks behind when saved mid-way
+            s.gossip_round(None, s.sample_stale())
+
+    first = fresh()
+    first.write_models(gpu.COMM, models(np.random.Generator(np.random.PCG64(21)), n, d, 0.3))
+    for r in range(3):
+        step(first, r)
+    first.local_steps([1, 2]) if not sequential else None      # pending steps are part of the state
+    image = first.save_state()
+    second = fresh()
+    second.load_state(image)
+    for s in (first, second):
+        if not sequential:
+            s.gossip_round(None, s.sample_stale())
+        for r in range(3):
+            step(s, r + 1)
+    for which in (gpu.COMM, gpu.LIVE) + ((gpu.SNAP,) if sequential else ()):
+        assert np.array_equal(first.read_models(which), second.read_models(which))
+    for i in range(n):
+        for age in range(S + 1):
+            assert np.array_equal(first.read_codes(i, age), second.read_codes(i, age))
+    assert first.counters() == second.counters() and first.scale() == second.scale()
+    assert first.prefix_stats() == second.prefix_stats()
+    with pytest.raises(gpu.SwarmError):
+        gpu.Swarm(n, d, edges, bits, eps, H, lr, S, 22, **kw).load_state(image)      # another seed
+    with pytest.raises(gpu.SwarmError):
+        second.load_state(image[:100])
