@@ -279,7 +279,7 @@ class SwarmOracle:
         """One step of Algorithm 1: initiator i, responder j.
             X_i' = (Q(X_i) + Q(X_j)) / 2 - eta h~_i(Xhat_i) ,  X_j' = (Q(X_i) + Q(X_j)) / 2,
         i's snapshot becomes X_i'; j's snapshot and pending steps are untouched."""
-        assert self.S == 0 and j in self.adj[i] and self.scale_policy == "fixed" and self.codec == "fixed"
+        assert self.S == 0 and j in self.adj[i] and self.scale_policy == "fixed"
         t = self.interactions
         if self.H > 0 and self.objective is not None:
             self.local_steps([i], sequential=True)
@@ -289,10 +289,16 @@ class SwarmOracle:
             self.bits_communicated += 2 * self.d * 32
         else:
             zi, zj = self._lattice_point(i, t), self._lattice_point(j, t)
-            self.ring[0][i] = qz.pack(qz.code(zi, self.bits), self.bits)
-            self.ring[0][j] = qz.pack(qz.code(zj, self.bits), self.bits)
+            if self.codec == "prefix":
+                self.ring[0][i], self.ring[0][j] = qz.prefix_register(zi), qz.prefix_register(zj)
+            else:
+                self.ring[0][i] = qz.pack(qz.code(zi, self.bits), self.bits)
+                self.ring[0][j] = qz.pack(qz.code(zj, self.bits), self.bits)
+            before = self.bits_communicated
             zj_seen = self._read(i, j, 0, zj)                 # i reads j's register ...
-            self.bits_communicated += self.d * self.bits      # ... and writes the average back
+            # ... and writes the average back: b bits, or with multi-resolution registers as many as it
+            # read (it knows the distance to j's key now: first case of the proof of Corollary 2.1)
+            self.bits_communicated += self.bits_communicated - before
             avg = (zi + zj_seen) * (0.5 * self.eps)
         self.X[i] = avg + delta
         self.X[j] = avg

@@ -675,3 +675,25 @@ def test_prefix_codec_counts_tiles_that_no_level_confirms():
     o.X[1, 600] += 40000 * eps                               # beyond the 16-bit radius, second tile only
     o.gossip_round([(0, 1)])
     assert o.prefix_unconfirmed == 2 and o.prefix_levels.tolist() == [2, 0, 2] and o.decode_failures == 2
+
+
+def test_algorithm1_with_prefix_registers():
+    """One step of Algorithm 1 where the initiator reads the responder's multi-resolution register:
+    same update as with 8-bit registers where 8 bits decode; the tile that is 24 cells away costs
+    8 bits per coordinate to read and as many to write the average back, the others 4."""
+    n, d, eps = 3, 1024, 2.0 ** -4
+    gen = np.random.Generator(np.random.PCG64(41))
+    X = (gen.standard_normal((1, d)) + gen.uniform(-0.1, 0.1, (n, d))).astype(np.float32)
+    X[1, 512:] += 1.5
+    p = SwarmOracle(n, d, wl.complete_graph(n), 16, eps, 0, 0.0, 0, 4, state_dtype=np.float32, codec="prefix")
+    f = SwarmOracle(n, d, wl.complete_graph(n), 8, eps, 0, 0.0, 0, 4, state_dtype=np.float32)
+    for o in (p, f):
+        o.X[:] = X
+        o.Xhat[:] = X
+        o.W[0] = X[0] + 0.01
+        o.pending[0] = True
+        o.interact(0, 1)
+    assert np.array_equal(p.X, f.X) and np.array_equal(p.Xhat, f.Xhat) and p.decode_failures == 0 == f.decode_failures
+    assert np.array_equal(p.X[0] - np.float32(0.01), p.X[1]) or np.allclose(p.X[0] - 0.01, p.X[1], atol=1e-6)
+    assert p.prefix_levels.tolist() == [1, 1, 0]
+    assert p.bits_communicated == 2 * (512 * 4 + 512 * 8 + 2 * 64) and f.bits_communicated == 2 * d * 8
