@@ -83,7 +83,10 @@ enum { SWARM_SCALE_FIXED = 0, SWARM_SCALE_PAIR_LINF = 1, SWARM_SCALE_GLOBAL_LINF
  * A reader decodes a tile from 4 bits, then 8, then 16, and stops
  * at the first level whose decoded tile has the writer's checksum (the confirmation that the
  * interactive protocol gets from the receiver's reply); a tile that no level confirms keeps the
- * 16-bit decode and is counted.  Needs bits = 16 and the fixed scale; rounds only (not Algorithm 1). */
+ * 16-bit decode and is counted.  Needs bits = 16 and the fixed scale.  In a step of Algorithm 1 the
+ * initiator reads the responder's register this way and writes the average back with as many bits
+ * per tile as the read took (by then it knows its distance to the responder's key: the proof's first
+ * case); bits_communicated counts both. */
 enum { SWARM_CODEC_FIXED = 0, SWARM_CODEC_PREFIX = 1 };
 
 /* Number of local steps per interaction.  CONSTANT: H for every node (the paper's experiments).

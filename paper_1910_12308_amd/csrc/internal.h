@@ -17,7 +17,9 @@ struct DeviceCounters {
 // spread over, so that a round in which every tile escalates does not serialise on one address; the
 // host adds the stripes up.
 struct PrefixStats {
-    unsigned long long tiles[2], coords[2], unconfirmed, pad[3];
+    unsigned long long tiles[2], coords[2], unconfirmed;
+    unsigned long long written_back[2];   // Algorithm 1: coordinates whose average went back with 8 / 16 bits
+    unsigned long long pad;
 };
 constexpr uint32_t PREFIX_STRIPES = 4096;
 
@@ -84,6 +86,8 @@ hipError_t launch_local_diag(const float *X, float *W, const float *a, const flo
 struct DiagObjective;
 hipError_t launch_prefix(const GossipArgs &g, const DiagObjective *local, bool inplace, float lr, int kind, uint32_t rows,
                          hipStream_t st);
+// One step of Algorithm 1 with multi-resolution registers: initiator i reads responder j's register.
+hipError_t launch_prefix_interact(const GossipArgs &g, uint32_t i, uint32_t j, bool has_delta, hipStream_t st);
 constexpr uint32_t PREFIX_TILE = 512;      // coordinates per checksum (one wave tile)
 
 // One lattice scale per round: state[0] = float bits of the coming round's scale, state[1] = float bits of

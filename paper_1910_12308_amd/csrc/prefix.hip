@@ -343,6 +343,63 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_singles_kernel(const Prefix
     report(a.counters, 0, t.clamped);
 }
 
+// One step of Algorithm 1: both registers are written, the initiator i reads j's by prefixes (the
+// lattice point is in registers: same decisions as a read from memory), X_i' = average + (W_i - Xhat_i),
+// X_j' = average, Xhat_i' = X_i'.  The average goes back into j's register with as many bits as the read
+// took (the initiator knows its distance to j's key by then), which only the bit count records.
+__global__ __launch_bounds__(WAVES * 64) void prefix_interact_kernel(const GossipArgs a, uint32_t ni, uint32_t nj, int has_delta) {
+    TileGeometry g;
+    if (!geometry(a.d, WAVES, g)) return;
+    const LaneWeights lw = lane_weights(g.lane);
+    const uint64_t oi = (uint64_t)ni * a.d, oj = (uint64_t)nj * a.d;
+    NodeTile ti, tj;
+    ti.qA = ldg_nt(a.X + oi + g.lA); ti.qB = ldg_nt(a.X + oi + g.lB);
+    tj.qA = ldg_nt(a.X + oj + g.lA); tj.qB = ldg_nt(a.X + oj + g.lB);
+    const f4 zero = {0.f, 0.f, 0.f, 0.f};
+    ti.dA = ti.dB = tj.dA = tj.dB = zero;
+    if (has_delta) {
+        ti.dA = ldg_nt(a.W + oi + g.lA) - ldg_nt(a.Xhat + oi + g.lA);
+        ti.dB = ldg_nt(a.W + oi + g.lB) - ldg_nt(a.Xhat + oi + g.lB);
+    }
+    const LaneRandom ri = row_random(a.seed, ni, a.event, g.tile, g.lane), rj = row_random(a.seed, nj, a.event, g.tile, g.lane);
+    bool cA = false, cB = false;
+    round_float4<16>(ti.qA, ri.a0, ri.a1, a.inv_eps, ti.zA, cA);
+    round_float4<16>(ti.qB, ri.b0, ri.b1, a.inv_eps, ti.zB, cB);
+    round_float4<16>(tj.qA, rj.a0, rj.a1, a.inv_eps, tj.zA, cA);
+    round_float4<16>(tj.qB, rj.b0, rj.b1, a.inv_eps, tj.zB, cB);
+    ti.check = tile_checksum(ti.zA, ti.zB, lw, g.inA, g.inB);
+    tj.check = tile_checksum(tj.zA, tj.zB, lw, g.inA, g.inB);
+    int zjA[4], zjB[4];
+    bool clamped = false, confirmed;
+    const int level = read_prefix<false>(Register{}, tj, ti, a.inv_eps, g.tile, lw, g.lA, g.lB, g.inA, g.inB, zjA, zjB,
+                                         clamped, confirmed);
+    int fails = 0;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) fails += (g.inA && zjA[m] != tj.zA[m]) + (g.inB && zjB[m] != tj.zB[m]);
+    publish(a, ni, ti, g.tile, g.lane, g.kA, g.kB, g.inA, g.inB);
+    publish(a, nj, tj, g.tile, g.lane, g.kA, g.kB, g.inA, g.inB);
+    const float half_eps = 0.5f * a.eps;
+    f4 avgA, avgB;
+    avgA.x = (float)(ti.zA[0] + zjA[0]) * half_eps; avgA.y = (float)(ti.zA[1] + zjA[1]) * half_eps;
+    avgA.z = (float)(ti.zA[2] + zjA[2]) * half_eps; avgA.w = (float)(ti.zA[3] + zjA[3]) * half_eps;
+    avgB.x = (float)(ti.zB[0] + zjB[0]) * half_eps; avgB.y = (float)(ti.zB[1] + zjB[1]) * half_eps;
+    avgB.z = (float)(ti.zB[2] + zjB[2]) * half_eps; avgB.w = (float)(ti.zB[3] + zjB[3]) * half_eps;
+    if (g.inA) { const f4 o = avgA + ti.dA; stg_nt(a.X + oi + g.kA, o); stg_nt(a.Xhat + oi + g.kA, o); stg_nt(a.X + oj + g.kA, avgA); }
+    if (g.inB) { const f4 o = avgB + ti.dB; stg_nt(a.X + oi + g.kB, o); stg_nt(a.Xhat + oi + g.kB, o); stg_nt(a.X + oj + g.kB, avgB); }
+    report_level(a.prefix_stats, level, confirmed, g.tile, a.d, g.lane);
+    if (g.lane == 0 && level > 0) {              // the write-back of the average took the same prefix length
+        const unsigned long long coords = (g.tile + 1) * TILE <= a.d ? TILE : a.d - g.tile * TILE;
+        atomicAdd(&a.prefix_stats[(blockIdx.x + 977u * blockIdx.y) & (PREFIX_STRIPES - 1)].written_back[level - 1], coords);
+    }
+    report(a.counters, fails, (g.inA && cA) || (g.inB && cB) || ((g.inA || g.inB) && clamped));
+}
+
+hipError_t launch_prefix_interact(const GossipArgs &g, uint32_t i, uint32_t j, bool has_delta, hipStream_t st) {
+    const uint64_t tiles = (g.d + TILE - 1) / TILE;
+    prefix_interact_kernel<<<dim3((unsigned)((tiles + WAVES - 1) / WAVES), 1, 1), WAVES * 64, 0, st>>>(g, i, j, has_delta);
+    return hipGetLastError();
+}
+
 template <bool LOCAL, bool INPLACE, bool NOISE>
 static void launch_kind(const PrefixArgs &pa, int kind, dim3 grid, hipStream_t st) {
     if (kind == 0) prefix_pairs_kernel<LOCAL, INPLACE, NOISE><<<grid, WAVES * 64, 0, st>>>(pa);

@@ -703,7 +703,6 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     if (c.stale_max != 0) return fail(h, SWARM_EINVAL, "Algorithm 1 steps need stale_max = 0");
     if (c.apply_mode != SWARM_APPLY_DEFERRED) return fail(h, SWARM_EINVAL, "Algorithm 1 defers the local steps");
     if (c.scale_policy != SWARM_SCALE_FIXED) return fail(h, SWARM_EINVAL, "Algorithm 1 steps use the fixed lattice scale");
-    if (c.codec != SWARM_CODEC_FIXED) return fail(h, SWARM_EINVAL, "Algorithm 1 steps use fixed-width registers");
     if (i >= c.n || j >= c.n || i == j ||
         !std::binary_search(h->edge_keys.begin(), h->edge_keys.end(), edge_key(i, j)))
         return fail(h, SWARM_EINVAL, "responder is not a neighbour of the initiator");
@@ -722,12 +721,19 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     }
     const GossipArgs a = gossip_args(h, (uint32_t)h->interactions, 0);
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
-    SWARM_HIP(h, launch_interact(a, c.bits, i, j, has_delta, h->stream));
+    if (c.codec == SWARM_CODEC_PREFIX) SWARM_HIP(h, launch_prefix_interact(a, i, j, has_delta, h->stream));
+    else SWARM_HIP(h, launch_interact(a, c.bits, i, j, has_delta, h->stream));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
     h->timed_gossip += 1;
     h->pending[i] = 0;
     h->interactions += 1;
-    h->bits_communicated += 2ull * c.d * (c.bits ? c.bits : 32);
+    if (c.codec == SWARM_CODEC_PREFIX) {     // read by prefixes, average written back with as many bits
+        const uint64_t tiles = (c.d + PREFIX_TILE - 1) / PREFIX_TILE;
+        h->bits_communicated += 2ull * (c.d * 4 + 64ull * tiles);
+        h->prefix_tile_reads += tiles;
+    } else {
+        h->bits_communicated += 2ull * c.d * (c.bits ? c.bits : 32);
+    }
     return SWARM_OK;
 }
 
@@ -975,7 +981,11 @@ static swarm_status prefix_totals(swarm_t h, PrefixStats *total) {
     SWARM_HIP(h, hipStreamSynchronize(h->stream));
     SWARM_HIP(h, hipMemcpy(stripes.data(), h->prefix_stats_dev, sizeof(PrefixStats) * PREFIX_STRIPES, hipMemcpyDeviceToHost));
     for (const PrefixStats &s : stripes) {
-        for (int l = 0; l < 2; ++l) { total->tiles[l] += s.tiles[l]; total->coords[l] += s.coords[l]; }
+        for (int l = 0; l < 2; ++l) {
+            total->tiles[l] += s.tiles[l];
+            total->coords[l] += s.coords[l];
+            total->written_back[l] += s.written_back[l];
+        }
         total->unconfirmed += s.unconfirmed;
     }
     return SWARM_OK;
@@ -992,7 +1002,8 @@ swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions,
     if (bits_communicated) {   // escalated tiles read 4 (to 8 bits) or 12 (to 16 bits) more bits per coordinate
         PrefixStats total;
         SWARM_TRY(prefix_totals(h, &total));
-        *bits_communicated = h->bits_communicated + 4ull * total.coords[0] + 12ull * total.coords[1];
+        *bits_communicated = h->bits_communicated + 4ull * (total.coords[0] + total.written_back[0]) +
+                             12ull * (total.coords[1] + total.written_back[1]);
     }
     if (decode_failures) *decode_failures = dc->decode_failures;
     if (dc->range_clamped) return fail(h, SWARM_ERANGE, "|x/eps| reached the clamp 2^29");

@@ -936,3 +936,32 @@ def test_saved_state_resumes_bit_for_bit(gpu, kind):
         gpu.Swarm(n, d, edges, bits, eps, H, lr, S, 22, **kw).load_state(image)      # another seed
     with pytest.raises(gpu.SwarmError):
         second.load_state(image[:100])
+
+
+def test_algorithm1_with_prefix_registers(gpu):
+    """Sequential steps where the initiator reads the responder's multi-resolution register; node 3 sits
+    tens of cells away (8 bits), node 5 hundreds (16 bits).  Registers, models, snapshots, levels and
+    the bits read and written back equal the oracle's."""
+    n, d, H, lr, eps = 6, D_RAGGED, 2, 0.1, 2.0 ** -6
+    edges = wl.complete_graph(n)
+    a, cc = wl.diag_quadratic_data(n, d, 4)
+    g, c = make_both(gpu, n, d, edges, 16, eps, H, lr, 0, seed=63, prefix=True)
+    c.objective = DiagQuadratic(a, cc, 0.05)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
+    gen = np.random.Generator(np.random.PCG64(63))
+    c.X[:] = models(gen, 1, d) + models(gen, n, d, 0.02)
+    c.X[3] += 0.5                                          # 32 cells: beyond 4 bits
+    c.X[5] += 4.0                                          # 256 cells: beyond 8 bits
+    c.Xhat[:] = c.X + models(gen, n, d, 0.01)
+    for t, (i, j) in enumerate([(0, 1), (3, 2), (4, 5), (1, 0), (5, 3), (2, 4)]):
+        g.write_models(gpu.COMM, c.X)
+        g.write_models(gpu.SNAP, c.Xhat)
+        c.interact(i, j)
+        g.interact(i, j)
+        assert np.array_equal(g.read_codes(i), c.ring[0][i]) and np.array_equal(g.read_codes(j), c.ring[0][j])
+        assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"X, t={t}")
+        assert_close(g.read_models(gpu.SNAP), c.Xhat, 2 * TOL_ELEMENTWISE, f"snapshots, t={t}")
+        assert g.prefix_stats() == (c.prefix_levels.tolist(), c.prefix_unconfirmed), f"levels, t={t}"
+        cnt = g.counters()
+        assert cnt["bits_communicated"] == c.bits_communicated and cnt["decode_failures"] == c.decode_failures
+    assert c.prefix_levels[1] > 0 and c.prefix_levels[2] > 0 and g.counters()["interactions"] == 6
