@@ -965,3 +965,65 @@ def test_algorithm1_with_prefix_registers(gpu):
         cnt = g.counters()
         assert cnt["bits_communicated"] == c.bits_communicated and cnt["decode_failures"] == c.decode_failures
     assert c.prefix_levels[1] > 0 and c.prefix_levels[2] > 0 and g.counters()["interactions"] == 6
+
+
+def ring_graph(n):
+    return [(i, (i + 1) % n) for i in range(n)] if n > 2 else [(0, 1)]
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_configurations(gpu, case):
+    """Seeded random draws of everything a round can be configured with -- swarm size, row length,
+    code width, staleness depth, apply mode, step law, scale policy, register format, one pass or two
+    calls, who has pending steps, who is matched -- each checked round by round against the oracle."""
+    gen = np.random.Generator(np.random.PCG64(1000 + case))
+    n = int(gen.integers(2, 10))
+    d = 8 * int(gen.integers(1, 200))
+    bits = int(gen.choice([2, 4, 8, 16]))
+    S = int(gen.integers(0, 4))
+    H = int(gen.integers(1, 4))
+    sigma = float(gen.choice([0.0, 0.05]))
+    inplace = bool(gen.integers(0, 2))
+    geometric = bool(gen.integers(0, 2))
+    prefix = bits == 16 and bool(gen.integers(0, 2))
+    global_scale = bits >= 8 and not prefix and bool(gen.integers(0, 2))
+    # in-place apply in one pass rounds the kernel's own float32 step result, which may differ from the
+    # oracle's in the last bit; that pairing is compared elsewhere (one pass against two calls, bit for bit)
+    one_pass = bool(gen.integers(0, 2)) and not inplace
+    eps = 2.0 ** -int(gen.integers(2, 7))
+    edges = wl.complete_graph(n) if gen.integers(0, 2) else ring_graph(n)
+    a, cc = wl.diag_quadratic_data(n, d, case, shift_sigma=0.2)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, 0.1, S, seed=case, inplace=inplace, geometric=geometric,
+                     global_scale=global_scale, prefix=prefix)
+    c.objective = DiagQuadratic(a, cc, sigma)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), sigma)
+    what = dict(n=n, d=d, bits=bits, S=S, H=H, sigma=sigma, inplace=inplace, geometric=geometric, prefix=prefix,
+                global_scale=global_scale, one_pass=one_pass, eps=eps)
+    base = models(gen, 1, d)
+    for r in range(4):
+        c.X[:] = base + models(gen, n, d, float(gen.choice([0.02, 0.3])))
+        c.pending[:] = False
+        force_state(gpu, g, c)
+        pairs = c.sample_matching()
+        pairs = pairs[: int(gen.integers(0, len(pairs) + 1))]              # sometimes fewer pairs, sometimes none
+        stale = np.minimum(gen.integers(0, S + 1, n), r).astype(np.uint8)
+        if one_pass:
+            c.local_steps()
+            c.gossip_round(pairs, stale)
+            g.round_fused(pairs, stale)
+        else:
+            nodes = sorted(gen.choice(n, int(gen.integers(1, n + 1)), replace=False).tolist())
+            c.local_steps(nodes)
+            g.local_steps(nodes)
+            force_state(gpu, g, c)
+            c.gossip_round(pairs, stale)
+            g.gossip_round(pairs, stale)
+        for i in range(n):
+            assert np.array_equal(g.read_codes(i), ring_row(c, i)), f"{what}: register of node {i}, round {r}"
+        assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"{what}: X after round {r}")
+        cnt = g.counters(raise_on_range=False)
+        assert cnt["decode_failures"] == c.decode_failures and cnt["bits_communicated"] == c.bits_communicated, what
+        if global_scale:
+            assert g.scale() == (float(c.eps_cur), float(c.max_disagreement)), what
+        if prefix:
+            assert g.prefix_stats() == (c.prefix_levels.tolist(), c.prefix_unconfirmed), what
