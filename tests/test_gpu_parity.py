@@ -978,7 +978,7 @@ def test_random_configurations(gpu, case):
     calls, who has pending steps, who is matched -- each checked round by round against the oracle."""
     gen = np.random.Generator(np.random.PCG64(1000 + case))
     n = int(gen.integers(2, 10))
-    d = 8 * int(gen.integers(1, 200))
+    d = 8 * int(gen.integers(1, 200)) if case % 3 else 8 * int(gen.integers(500, 1600))   # a third spans workgroups
     bits = int(gen.choice([2, 4, 8, 16]))
     S = int(gen.integers(0, 4))
     H = int(gen.integers(1, 4))
