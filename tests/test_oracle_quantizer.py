@@ -265,3 +265,47 @@ def test_prefix_read_beyond_sixteen_bits_is_reported():
     zp, lev, conf = qz.prefix_read(qz.prefix_register(z), y, eps)
     assert conf.tolist() == [True, False] and lev.tolist() == [lev[0], 2]
     assert np.array_equal(zp[:512], z[:512]) and zp[700] != z[700] and (zp[700] - z[700]) % 65536 == 0
+
+
+# ---------------------------------------------------------------- properties over arbitrary inputs
+from hypothesis import given, settings, strategies as st
+
+
+@settings(max_examples=200, deadline=None)
+@given(bits=st.sampled_from([2, 4, 8, 16]), e=st.integers(-12, 6), x=st.floats(-1e3, 1e3, width=32),
+       offset=st.floats(-1.0, 1.0), r16=st.integers(0, 65535))
+def test_decode_recovers_the_sender_inside_the_radius_for_any_input(bits, e, x, offset, r16):
+    """Corollary 2.1's precondition in this instantiation: whenever |x - y| <= (2^(b-1) - 5/2) eps the
+    receiver decodes exactly the sender's lattice point, whatever x, eps and the rounding draw."""
+    eps = 2.0 ** e
+    radius = (2 ** (bits - 1) - 2.5) * eps
+    if abs(x) / eps > 2.0 ** 28 or radius <= 0:
+        return
+    x32 = np.float32(x)
+    y32 = np.float32(float(x32) + offset * radius * 0.999)
+    if abs(float(y32) - float(x32)) > radius:
+        return
+    z = qz.stochastic_round(np.array([x32]), eps, np.array([r16]))
+    got = qz.decode(qz.code(z, bits), np.array([y32]), eps, bits)
+    assert got[0] == z[0] and abs(z[0] * eps - float(x32)) < eps * (1 + 1e-6)
+
+
+@settings(max_examples=100, deadline=None)
+@given(seed=st.integers(0, 2 ** 32 - 1), d=st.sampled_from([8, 24, 512, 520, 1032]), spread=st.floats(0.0, 200.0))
+def test_prefix_read_is_exact_whenever_sixteen_bits_reach(seed, d, spread):
+    """Any key within the 16-bit radius of the writer's point decodes exactly, at the smallest level
+    that does, and every tile is confirmed."""
+    eps = 2.0 ** -3
+    gen = np.random.Generator(np.random.PCG64(seed))
+    x = (gen.standard_normal(d) * 5).astype(np.float32)
+    z = qz.stochastic_round(x, eps, gen.integers(0, 65536, d))
+    y = (x + gen.uniform(-spread, spread, d) * eps).astype(np.float32)
+    zp, level, confirmed = qz.prefix_read(qz.prefix_register(z), y, eps)
+    assert np.array_equal(zp, z) and confirmed.all()
+    cells = np.abs(x.astype(np.float64) - y) / eps
+    for t in range(level.size):
+        worst = cells[512 * t:512 * (t + 1)].max()
+        if worst <= 2 ** 3 - 2.5:
+            assert level[t] == 0
+        elif worst <= 2 ** 7 - 2.5:
+            assert level[t] <= 1
