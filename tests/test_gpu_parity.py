@@ -142,13 +142,27 @@ def test_identity_quantizer_round_preserves_the_mean(gpu):
     assert np.array_equal(X[0], X[1]) and np.array_equal(X[4], c.X[4])
 
 
-def test_range_clamp_is_reported(gpu):
-    n, d = 2, 64
-    g, c = make_both(gpu, n, d, wl.complete_graph(n), 8, 2.0 ** -20, 0, 0.0)
-    c.X[:] = 1e6
+@pytest.mark.parametrize("form", ["pairs, fresh reads", "nodes, stale reads", "prefix registers", "unmatched node"])
+def test_range_clamp_is_reported(gpu, form):
+    """|x / eps| beyond 2^29 is clamped and flagged by every kernel form, as in the oracle; the clamped
+    codes and models still agree."""
+    n, d = 3, 64
+    prefix = form == "prefix registers"
+    g, c = make_both(gpu, n, d, wl.complete_graph(n), 16 if prefix else 8, 2.0 ** -20, 0, 0.0, 1, prefix=prefix)
+    c.X[:] = 0.001
     force_state(gpu, g, c)
     c.gossip_round([(0, 1)])
-    g.gossip_round([(0, 1)])
+    g.gossip_round([(0, 1)])                                # round 0: gives round 1 something stale to read
+    assert not c.range_clamped and g.counters()["rounds"] == 1
+    c.X[:] = 0.001
+    c.X[2 if form == "unmatched node" else 0, 5] = 1e6
+    force_state(gpu, g, c)
+    stale = [0, 0, 0] if form == "pairs, fresh reads" else [1, 1, 1]
+    c.gossip_round([(0, 1)], stale)
+    g.gossip_round([(0, 1)], stale)
+    for i in range(n):
+        assert np.array_equal(g.read_codes(i), ring_row(c, i))
+    assert_close(g.read_models(gpu.COMM), c.X, TOL_ELEMENTWISE, form)
     assert c.range_clamped and g.counters(raise_on_range=False)["range_clamped"]
     with pytest.raises(gpu.SwarmError):
         g.counters()
