@@ -1041,3 +1041,33 @@ def test_random_configurations(gpu, case):
             assert g.scale() == (float(c.eps_cur), float(c.max_disagreement)), what
         if prefix:
             assert g.prefix_stats() == (c.prefix_levels.tolist(), c.prefix_unconfirmed), what
+
+
+@pytest.mark.parametrize("one_pass", [False, True])
+def test_many_nodes_few_coordinates(gpu, one_pass):
+    """n = 1024 nodes on a random 6-regular graph, d = 64: hundreds of pairs per launch (grid rows),
+    matching sampled on the device, stale and fresh reads mixed."""
+    n, d, H, lr, bits, eps, S = 1024, 64, 2, 0.1, 8, 2.0 ** -4, 1
+    edges = wl.random_regular_graph(n, 6, 3)
+    a, cc = wl.diag_quadratic_data(n, d, 12, shift_sigma=0.2)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, S, seed=77)
+    c.objective = DiagQuadratic(a, cc, 0.05)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
+    gen = np.random.Generator(np.random.PCG64(77))
+    for r in range(3):
+        c.X[:] = models(gen, 1, d) + models(gen, n, d, 0.05)
+        c.pending[:] = False
+        force_state(gpu, g, c)
+        pairs, stale = c.sample_matching(), c.sample_stale()
+        assert np.array_equal(g.sample_matching(), pairs.astype(np.uint32)) and len(pairs) > 400
+        c.local_steps()
+        c.gossip_round(pairs, stale)
+        if one_pass:
+            g.round_fused(None, stale.astype(np.uint8))
+        else:
+            g.local_steps()
+            g.gossip_round(None, stale.astype(np.uint8))
+        codes = np.stack([g.read_codes(i) for i in range(0, n, 37)])
+        assert np.array_equal(codes, np.stack([ring_row(c, i) for i in range(0, n, 37)]))
+        assert_close(g.read_models(gpu.COMM), c.X, 2 * TOL_ELEMENTWISE, f"X after round {r}")
+    assert g.counters()["interactions"] == c.interactions
