@@ -254,6 +254,20 @@ swarm_status swarm_potential(swarm_t h, double *gamma_host, float *mu_dev);
 swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npairs,
                              float *linf_host);
 
+/* The potential for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same reduction as swarm_potential over a
+ * caller-owned n x d float32 matrix X_dev (row-major, 16-byte aligned, d a positive multiple of 4),
+ * with the per-workgroup partial sums in a fixed 1 MiB device array inside the library instead of a
+ * buffer of a handle.  Needs no handle, allocates nothing, does not synchronise: the kernels are
+ * enqueued on hip_stream, Gamma arrives in gamma_dev (one double, device) and, if mu_dev is not NULL,
+ * the mean model in mu_dev (d floats, device, 16-byte aligned).  d is limited to 134217728 coordinates
+ * (SWARM_EINVAL beyond; text from swarm_last_error(NULL)).  Every call on a GPU shares that GPU's
+ * array: calls that overlap on one GPU (different streams or threads) race and must be serialised by
+ * the caller.  Nothing in the array has to be cleared between calls: a call overwrites every partial
+ * sum it later reads. */
+swarm_status swarm_potential_static(const float *X_dev, uint32_t n, uint64_t d, double *gamma_dev,
+                                    float *mu_dev, void *hip_stream);
+
 /* SWARM_SCALE_GLOBAL_LINF: the scale the next round will use and the largest disagreement
  * max |X_i - decoded partner| of the last round that had pairs (0 before the first).  Other
  * policies: cfg.eps and 0.  Either pointer may be NULL (host memory).  Synchronises. */

@@ -27,7 +27,7 @@ EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set
            "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
            "swarm_state_bytes", "swarm_save_state", "swarm_load_state",
-           "swarm_potential", "swarm_pair_linf", "swarm_scale", "swarm_prefix_stats", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
+           "swarm_potential", "swarm_potential_static", "swarm_pair_linf", "swarm_scale", "swarm_prefix_stats", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
            "swarm_stream_copy", "swarm_stream_mix", "swarm_last_error"]
 
 
@@ -77,6 +77,7 @@ def load_library():
         "swarm_load_state": [vp, vp, u64],
         "swarm_read_codes": [vp, u32, u32, u64, u64, vp],
         "swarm_potential": [vp, P(ctypes.c_double), vp],
+        "swarm_potential_static": [vp, u32, u64, vp, vp, vp],
         "swarm_pair_linf": [vp, vp, u32, vp],
         "swarm_scale": [vp, vp, vp],
         "swarm_prefix_stats": [vp, vp, P(u64)],
@@ -346,6 +347,16 @@ def dequantize(codes, key, eps, bits, stream=None):
     if rc != OK:
         raise SwarmError(rc, lib().swarm_last_error(None).decode())
     return out
+
+
+def potential_static(X, gamma_out, mu=None, stream=None):
+    """Gamma of the n x d device matrix X into the 1-element float64 device tensor gamma_out (and the
+    mean model into mu), through the entry point that allocates nothing.  Asynchronous."""
+    assert X.dim() == 2 and gamma_out.dtype == torch.float64 and gamma_out.numel() == 1
+    rc = lib().swarm_potential_static(_dev_ptr(X, torch.float32), X.shape[0], X.shape[1], _dev_ptr(gamma_out),
+                                      _dev_ptr(mu, torch.float32), _stream_ptr(stream))
+    if rc != OK:
+        raise SwarmError(rc, lib().swarm_last_error(None).decode())
 
 
 def stream_copy(dst, src, stream=None):

@@ -5,6 +5,9 @@
 
 namespace swarm {
 
+// Text returned by swarm_last_error(NULL): failures of calls that have no handle.
+void set_global_error(const char *message);
+
 // Device-side counters shared by the kernels (one per handle).
 struct DeviceCounters {
     unsigned long long decode_failures;

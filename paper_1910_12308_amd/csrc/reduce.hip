@@ -4,8 +4,11 @@
 // Column sums are accumulated in float64 per thread, then staged through LDS per
 // workgroup; the per-workgroup partials are summed by one last workgroup in a fixed
 // order, so the result does not depend on scheduling.
+#include <mutex>
+
 #include "internal.h"
 #include "quant.hpp"
+#include "swarm.h"
 
 namespace swarm {
 
@@ -140,3 +143,58 @@ hipError_t launch_scale_close(float *eps_slots, uint32_t *state, uint32_t slot_n
 }
 
 }  // namespace swarm
+
+// ---- the potential without any allocation ---------------------------------------------------
+// The per-workgroup partial sums of potential_kernel live in a file-scope device array instead
+// of a buffer of the handle.  Every GPU holds its own copy of the array at its own address; the
+// host-side name is only a stand-in, so the address is looked up once per device.
+namespace {
+
+constexpr uint32_t STATIC_PARTIALS = 1u << 17;          // 1 MiB of float64 partial sums per GPU
+constexpr int MAX_DEVICES = 64;
+
+__device__ __align__(256) double scratch[STATIC_PARTIALS];
+
+std::mutex scratch_mutex;
+double *scratch_ptr[MAX_DEVICES];                        // device address of each GPU's copy
+
+hipError_t scratch_address(double **ptr) {
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[device]) {
+        double *p = nullptr;
+        e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        scratch_ptr[device] = p;
+    }
+    *ptr = scratch_ptr[device];
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" swarm_status swarm_potential_static(const float *X_dev, uint32_t n, uint64_t d, double *gamma_dev,
+                                               float *mu_dev, void *hip_stream) {
+    using namespace swarm;
+    if (!X_dev || !gamma_dev || n < 1 || d == 0 || d % 4 != 0 || ((uintptr_t)X_dev & 15u) || ((uintptr_t)gamma_dev & 7u) ||
+        (mu_dev && ((uintptr_t)mu_dev & 15u))) {
+        set_global_error("potential (static scratch): null or misaligned pointer, n = 0, or d not a positive multiple of 4");
+        return SWARM_EINVAL;
+    }
+    if ((d / 4 + RB - 1) / RB > STATIC_PARTIALS) {
+        set_global_error("potential (static scratch): d exceeds 134217728 coordinates");
+        return SWARM_EINVAL;
+    }
+    double *partials = nullptr;
+    hipError_t e = scratch_address(&partials);
+    if (e == hipSuccess)
+        e = launch_potential(X_dev, n, d, mu_dev, partials, potential_partials(d), gamma_dev, (hipStream_t)hip_stream);
+    if (e != hipSuccess) {
+        set_global_error(hipGetErrorString(e));
+        return SWARM_EDEVICE;
+    }
+    return SWARM_OK;
+}

@@ -79,6 +79,12 @@ namespace {
 
 thread_local std::string g_init_error;
 
+}  // namespace
+
+void swarm::set_global_error(const char *message) { g_init_error = message; }
+
+namespace {
+
 swarm_status fail(swarm_t h, swarm_status code, const std::string &msg) {
     if (h) h->err = msg; else g_init_error = msg;
     return code;
