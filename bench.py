@@ -9,12 +9,16 @@ matching, the quantized gossip pass over the matched pairs, and the unmatched no
 updates.  For per-coordinate objectives the library runs all of it in one kernel pass
 (swarm_round_fused, bit-identical to swarm_local_steps + swarm_gossip_round); that is the
 timed step, and the two-call variant is measured after it and reported in the same line.
-Prints ONE JSON line.
+After the headline's timed region the other workload configurations (2, 5, 3, 1 and
+Algorithm 1 at the headline's shape) run a few steps each and are reported in a compact
+"configs" block of the same line.  Prints ONE JSON line.
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
+import tempfile
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -22,9 +26,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense fp32 matrix rate
 # HBM bytes per pair-coordinate from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by the stream-copy
 # calibration (see profiles/), at 4-bit codes with stale reads: key = (kernel, bits, stale).
 MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {("gossip", 4, True): 25.99, ("round", 4, True): 33.99}
+BOX_CPU_SHARE = 16             # host cores a one-GPU machine grants, whatever os.cpu_count() shows
 
 
 def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace=False, prefix=False):
@@ -37,6 +43,12 @@ def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace=
     if prefix:
         return reads + 8 + 2 * (2 + 8 / 512) + stale_fraction * 2 * (0.5 + 8 / 512)
     return reads + 8 + 2 * bits / 8 + stale_fraction * 2 * bits / 8
+
+
+def unmatched_bytes_per_node_coordinate(kernel, bits, inplace=False):
+    """An unmatched node of the one-pass round reads X, a, c and writes X (16 B) and its b-bit code; in the
+    gossip pass it reads X and W and writes X (12 B; 4 B read for the code alone without pending steps)."""
+    return (16 if kernel == "round" else (4 if inplace else 12)) + bits / 8
 
 
 def build_workload(cfg_id, scale_d=None, steps_H=None):
@@ -103,38 +115,82 @@ def stale_plan(cfg, swarm_obj):
     return swarm_obj.sample_stale()
 
 
-def cpu_baseline(cfg, edges, a, c, eps, seconds_target=15.0):
-    """The oracle as it stands, timed on the host: one round on a column window of the same
-    workload, scaled to the full dimension."""
+# ---------------------------------------------------------------------------- the oracle beside it
+def oracle_round_on_window(cfg, edges, a_win, c_win, eps, k0, k1):
+    """Seconds the oracle takes for one full round (local steps + matching + gossip) on columns [k0, k1)."""
     import numpy as np
     from oracle.objectives import DiagQuadratic
     from oracle.swarm import SwarmOracle
     n, d = cfg["n"], cfg["d"]
+    o = SwarmOracle(n, d, edges, cfg["bits"], eps, cfg["H"], cfg["lr"], cfg["stale_max"], 0, k0=k0, k1=k1,
+                    codec=cfg.get("codec", "fixed"))
+    o.objective = DiagQuadratic(a_win, c_win, cfg["sigma"], k0=k0)
+    o.local_steps()
+    o.gossip_round(o.sample_matching())           # round 0 fills the ring so that round 1 can read stale codes
+    t0 = time.perf_counter()
+    o.local_steps()
+    pairs = o.sample_matching()
+    stale = np.minimum(1, o.round) * np.ones(n, dtype=np.int64) if cfg["stale_max"] else None
+    o.gossip_round(pairs, stale)
+    return time.perf_counter() - t0, len(pairs)
+
+
+def cpu_worker(path):
+    """Child process of the all-cores leg: the oracle's round on this worker's column window."""
+    import numpy as np
+    job = np.load(path, allow_pickle=False)
+    cfg = json.loads(str(job["cfg"]))
+    dt, pairs = oracle_round_on_window(cfg, job["edges"], job["a"], job["c"], float(job["eps"]), int(job["k0"]), int(job["k1"]))
+    print(json.dumps({"seconds": dt, "pairs": pairs}))
+
+
+def cpu_baseline(cfg, edges, a, c, eps, seconds_target=15.0):
+    """The oracle as it stands, timed on the host: one round on a column window of the same
+    workload, scaled to the full dimension -- on one core, then with one process per host core, each
+    on a window of its own (the oracle itself stays single-threaded)."""
+    import numpy as np
+    n, d = cfg["n"], cfg["d"]
+    host_cores = os.cpu_count() or 1
     if cfg["objective"] == "mlp":
         return cpu_baseline_mlp(cfg, edges, a, c, eps)
     if cfg["objective"] == "lsq":
         return cpu_baseline_sequential(cfg, edges, a, c, eps)
     width = 1 << 14
-    result = None
     while True:
         k1 = min(width, d - d % 8)
-        o = SwarmOracle(n, d, edges, cfg["bits"], eps, cfg["H"], cfg["lr"], cfg["stale_max"], 0, k0=0, k1=k1,
-                        codec=cfg.get("codec", "fixed"))
-        o.objective = DiagQuadratic(a[:, :k1].cpu().numpy(), c[:, :k1].cpu().numpy(), cfg["sigma"], k0=0)
-        o.local_steps()
-        o.gossip_round(o.sample_matching())           # round 0 fills the ring so that round 1 can read stale codes
-        t0 = time.perf_counter()
-        o.local_steps()
-        pairs = o.sample_matching()
-        stale = np.minimum(1, o.round) * np.ones(n, dtype=np.int64) if cfg["stale_max"] else None
-        o.gossip_round(pairs, stale)
-        dt = time.perf_counter() - t0
-        result = dict(value=len(pairs) / (dt * d / k1), unit="interactions/s", cores=1, kind="oracle",
-                      sample=f"1 full round (local steps + matching + gossip) on columns [0,{k1}) of d={d}, "
-                             f"all {n} nodes, {dt:.2f} s, scaled by d/{k1}")
+        dt, pairs = oracle_round_on_window(cfg, edges, a[:, :k1].cpu().numpy(), c[:, :k1].cpu().numpy(), eps, 0, k1)
         if dt >= seconds_target / 4 or k1 >= d - d % 8 or width >= 1 << 22:
-            return result
+            break
         width *= 4
+    result = dict(value=pairs / (dt * d / k1), unit="interactions/s", cores=1, kind="oracle", host_cores=host_cores,
+                  sample=f"1 full round (local steps + matching + gossip) on columns [0,{k1}) of d={d}, "
+                         f"all {n} nodes, {dt:.2f} s, scaled by d/{k1}")
+    # all cores: one child process per core, each running the same oracle round on the next window of k1 columns
+    workers = max(1, min(host_cores, BOX_CPU_SHARE, (d - d % 8) // k1))
+    if workers > 1:
+        with tempfile.TemporaryDirectory() as tmp:
+            procs = []
+            for w in range(workers):
+                k0w = w * k1
+                path = os.path.join(tmp, f"job{w}.npz")
+                np.savez(path, cfg=json.dumps(cfg), edges=np.asarray(edges), eps=eps, k0=k0w, k1=k0w + k1,
+                         a=a[:, k0w:k0w + k1].cpu().numpy(), c=c[:, k0w:k0w + k1].cpu().numpy())
+                procs.append(path)
+            t0 = time.perf_counter()
+            running = [subprocess.Popen([sys.executable, os.path.abspath(__file__), "--cpu-worker", path],
+                                        stdout=subprocess.PIPE, text=True,
+                                        env=dict(os.environ, OMP_NUM_THREADS="1", OPENBLAS_NUM_THREADS="1"))
+                       for path in procs]
+            outs = [p.communicate()[0] for p in running]
+            wall = time.perf_counter() - t0
+        rounds = [json.loads(o.strip().splitlines()[-1]) for o in outs if o.strip()]
+        if len(rounds) == workers:
+            slowest = max(r["seconds"] for r in rounds)
+            result["all_cores"] = dict(value=pairs / (slowest * d / (workers * k1)), unit="interactions/s", cores=workers,
+                                       sample=f"{workers} processes, each the same round on its own window of {k1} "
+                                              f"columns; slowest {slowest:.2f} s ({wall:.1f} s with start-up), "
+                                              f"scaled by d/{workers * k1}")
+    return result
 
 
 def cpu_baseline_sequential(cfg, edges, A, b, eps):
@@ -147,7 +203,7 @@ def cpu_baseline_sequential(cfg, edges, A, b, eps):
     for _ in range(cfg["steps"]):
         o.step_sequential()
     dt = time.perf_counter() - t0
-    return dict(value=cfg["steps"] / dt, unit="interactions/s", cores=1, kind="oracle",
+    return dict(value=cfg["steps"] / dt, unit="interactions/s", cores=1, kind="oracle", host_cores=os.cpu_count() or 1,
                 sample=f"{cfg['steps']} sequential interactions of Algorithm 1 at full size, {dt:.2f} s")
 
 
@@ -168,11 +224,12 @@ def cpu_baseline_mlp(cfg, edges, means, cdf, eps):
     o.gossip_round([(0, 1)])
     dt = time.perf_counter() - t0
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return dict(value=1.0 / dt, unit="interactions/s", cores=threads, kind="oracle",
+    return dict(value=1.0 / dt, unit="interactions/s", cores=threads, kind="oracle", host_cores=os.cpu_count() or 1,
                 sample=f"2 of {n} nodes: H local MLP steps each (numpy float64 GEMMs, BLAS threads) + 1 pairwise "
                        f"gossip of full rows, {dt:.2f} s; a round of the whole swarm is {n // 2} such units")
 
 
+# ---------------------------------------------------------------------------- timing
 def measure(torch, s, step, steps, warmup):
     """W untimed steps, then exactly `steps` timed ones between two device synchronisations."""
     for _ in range(warmup):
@@ -187,7 +244,7 @@ def measure(torch, s, step, steps, warmup):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     after = s.counters(raise_on_range=False)
-    return dict(dt=dt, times=s.kernel_times(), interactions=after["interactions"] - before["interactions"],
+    return dict(dt=dt, steps=steps, times=s.kernel_times(), interactions=after["interactions"] - before["interactions"],
                 decode_failures=after["decode_failures"] - before["decode_failures"],
                 prefix_tiles=[x - y for x, y in zip(s.prefix_stats()[0], tiles_before)])
 
@@ -208,9 +265,126 @@ def roofline(kernel, name, cfg, m, d, inplace=False):
     return {"kernel": name, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": None if measured is None else measured * d * m["interactions"] / launches,
-            "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE counters, calibrated on the stream copy)",
+            "traffic_unit": "bytes per launch = the per-pair-coordinate constant stored from the rocprofv3 FETCH_SIZE + "
+                            "WRITE_SIZE runs under profiles/ (calibrated on the stream copy) x d x pairs; not counted in this run",
             "achieved_bytes_per_launch": total / launches, "bytes_per_pair_coordinate": per_pc,
             "ms_per_launch": m["times"]["gossip_ms"] / launches}
+
+
+def step_roofline(kernel, cfg, m, d, n, inplace=False):
+    """Every compulsory byte of the step (pairs and unmatched nodes) over the wall time of the step."""
+    bits, S = cfg["bits"], cfg["stale_max"]
+    stale_fraction = {"fixed1": 1.0, "uniform": S / (S + 1.0)}.get(cfg.get("stale"), 0.0)
+    pair_bytes = algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace, cfg.get("codec") == "prefix")
+    unmatched = n * m["steps"] - 2 * m["interactions"]
+    total = d * (pair_bytes * m["interactions"] + unmatched_bytes_per_node_coordinate(kernel, bits, inplace) * unmatched)
+    if kernel == "gossip":
+        total += 16.0 * d * n * m["steps"]       # the stand-alone local steps: read X, a, c, write W
+    achieved = total / m["dt"] / 1e9
+    return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "what": "all compulsory bytes of the step (pairs + unmatched nodes) / ms_per_step"}
+
+
+def make_swarm(swarm, torch, cfg, edges, a, c, eps, args=None, stale_max=None):
+    n, d, bits = cfg["n"], cfg["d"], cfg["bits"]
+    S = cfg["stale_max"] if stale_max is None else stale_max
+    if cfg["objective"] == "mlp":
+        x0 = 0.02 * torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
+        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], S, seed=0, x0=x0)
+        s.set_objective_mlp(cfg["n_in"], cfg["n_hid"], cfg["n_out"], a, c, cfg["data_sigma"], cfg["batch"])
+    elif cfg["objective"] == "lsq":
+        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], 0, seed=0)
+        s.set_objective_lsq(a, c, cfg["m_rows"], cfg["batch"])
+    else:
+        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], S, seed=0,
+                        apply_mode=swarm.INPLACE if args is not None and args.inplace else swarm.DEFERRED,
+                        codec=swarm.CODEC_PREFIX if args is not None and args.prefix else swarm.CODEC_FIXED,
+                        scale_policy=swarm.SCALE_GLOBAL_LINF if args is not None and args.global_scale else swarm.SCALE_FIXED)
+        s.set_objective_diag(a, c, cfg["sigma"])
+    return s
+
+
+def sequential_report(torch, swarm, s, cfg, batch, steps, warmup, compare_single=True):
+    """Algorithm 1: `batch` interactions per swarm_run_sequential call (a step), and, beside it, the same
+    number of interactions as one swarm_sample_pair + swarm_interact per interaction."""
+    n, d, bits = cfg["n"], cfg["d"], cfg["bits"]
+    launches = []
+
+    def step():
+        launches.append(s.run_sequential(batch)[1])
+
+    m = measure(torch, s, step, steps, warmup)
+    per_launch = m["interactions"] / max(1, sum(launches[-steps:]))
+    rep = {"step": f"swarm_run_sequential({batch}): Algorithm 1, interactions on disjoint nodes share a launch",
+           "steps": steps, "ms_per_step": m["dt"] / steps * 1e3, "interactions_per_s": m["interactions"] / m["dt"],
+           "interactions_per_launch": per_launch}
+    if cfg["objective"] == "diag":
+        # per interaction-coordinate: read X_i, X_j, Xhat_i, a_i, c_i (20 B), write X_i', X_j', Xhat_i' (12 B), two codes
+        per_ic = 32.0 + 2 * bits / 8
+        seconds = m["times"]["gossip_ms"] * 1e-3
+        achieved = per_ic * d * m["interactions"] / seconds / 1e9
+        rep["roofline"] = {"kernel": "interact_kernel<local steps inside> (Algorithm 1, many interactions per launch)",
+                           "bound": "hbm", "bytes_per_interaction_coordinate": per_ic, "achieved": achieved,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                           "ms_per_interaction": m["times"]["gossip_ms"] / max(1, m["interactions"])}
+    else:
+        # least squares: 2 * H * batch rows of A per interaction dominate (read twice per step), plus the rows of the pair
+        per_i = cfg["H"] * 2 * cfg["batch"] * d * 4 + 28.0 * d + 16.0 * d
+        achieved = per_i * m["interactions"] / m["dt"] / 1e9
+        rep["roofline"] = {"kernel": "lsq_split_kernel (an initiator's local steps and its interaction in one launch; latency-bound: "
+                                     "a few dozen workgroups per launch, one exchange between them per local step)",
+                           "bound": "hbm", "bytes_per_interaction": per_i, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS}
+    if compare_single:
+        def single():
+            for _ in range(batch):
+                s.interact(*s.sample_pair())
+        m1 = measure(torch, s, single, max(1, steps // 2), 1)
+        rep["one_call_per_interaction"] = {"interactions_per_s": m1["interactions"] / m1["dt"],
+                                           "speedup_of_the_batched_run": (m["interactions"] / m["dt"]) / (m1["interactions"] / m1["dt"])}
+    return rep
+
+
+def compact_config(torch, swarm, cfg_id, steps, warmup):
+    """A few timed steps of another workload configuration, as a compact record."""
+    cfg, edges, a, c = build_workload(cfg_id)
+    eps = eps_for(cfg)
+    n, d, bits = cfg["n"], cfg["d"], cfg["bits"]
+    s = make_swarm(swarm, torch, cfg, edges, a, c, eps)
+    rec = {"workload": f"config {cfg_id}: n={n} d={d} graph={cfg['graph']} {cfg['objective']} H={cfg['H']} bits={bits} "
+                       f"stale_max={cfg['stale_max']} ({cfg.get('stale', 'fresh')}) eps={eps}"}
+    if cfg["mode"] == "sequential":
+        rec.update(sequential_report(torch, swarm, s, cfg, cfg["steps"], steps, warmup))
+    elif cfg["objective"] == "diag":
+        m = measure(torch, s, lambda: s.round_fused(None, stale_plan(cfg, s)), steps, warmup)
+        form = "nodes" if cfg.get("stale") == "fixed1" else "pairs" + ("/nodes by staleness class" if cfg["stale_max"] else "")
+        roof = roofline("round", f"fused_{form}_kernel (one-pass round)", cfg, m, d)
+        rec.update({"step": "one-pass round (swarm_round_fused)", "steps": steps, "ms_per_step": m["dt"] / steps * 1e3,
+                    "interactions_per_s": m["interactions"] / m["dt"],
+                    "roofline": {k: roof[k] for k in ("kernel", "bound", "bytes_per_pair_coordinate", "achieved", "peak", "unit",
+                                                      "frac", "ms_per_launch")},
+                    "step_roofline_frac": step_roofline("round", cfg, m, d, n)["frac"]})
+    else:   # MLP: the local steps are GEMMs on the matrix cores, the gossip pass is the HBM-bound one
+        def step():
+            s.local_steps()
+            s.gossip_round(None, None)
+        m = measure(torch, s, step, steps, warmup)
+        t = m["times"]
+        flops = 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"] * n * cfg["H"] * t["local_calls"]
+        tflops = flops / (t["local_ms"] * 1e-3) / 1e12
+        goss = roofline("gossip", "gossip_pairs_kernel", cfg, m, d)
+        rec.update({"step": "swarm_local_steps (grouped fp32 MFMA GEMMs) + swarm_gossip_round", "steps": steps,
+                    "ms_per_step": m["dt"] / steps * 1e3, "interactions_per_s": m["interactions"] / m["dt"],
+                    "roofline": {"kernel": "mlp_gemm_kernel (5 grouped GEMMs per node and local step, all local-step kernels timed)",
+                                 "bound": "mfma", "flops_per_node_step": 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"],
+                                 "achieved": tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                 "frac": tflops / MFMA_F32_PEAK_TFLOPS, "ms_per_round": t["local_ms"] / max(1, t["local_calls"])},
+                    "gossip_pass": {k: goss[k] for k in ("kernel", "bound", "bytes_per_pair_coordinate", "achieved", "peak", "unit",
+                                                         "frac", "ms_per_launch")}})
+    s.close()
+    del s, a, c
+    torch.cuda.empty_cache()
+    return rec
 
 
 def main():
@@ -221,8 +395,13 @@ def main():
                     help="untimed steps first: the first ~10 launches run up to 15 %% slower (clock ramp)")
     ap.add_argument("--config", type=int, default=4, help="workload configuration (1 to 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the compact runs of the other configurations after the headline's timed region")
+    ap.add_argument("--config-steps", type=int, default=12, help="timed steps of each of the other configurations")
     ap.add_argument("--two-call", action="store_true",
                     help="time swarm_local_steps + swarm_gossip_round as the step instead of the one-pass round")
+    ap.add_argument("--sequential", action="store_true",
+                    help="Algorithm 1 (swarm_run_sequential) at the configuration's shape with fresh reads, instead of rounds")
     ap.add_argument("--inplace", action="store_true",
                     help="in-place apply mode (local steps update the exchanged model; one matrix) instead of the "
                          "paper's deferred apply")
@@ -235,7 +414,10 @@ def main():
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
     ap.add_argument("--H", type=int, default=None,
                     help="override the number of local steps (to find where a kernel turns ALU-bound)")
+    ap.add_argument("--cpu-worker", default=None, help=argparse.SUPPRESS)
     args = ap.parse_args()
+    if args.cpu_worker:
+        return cpu_worker(args.cpu_worker)
     if args.gpus != 1:
         raise SystemExit("bench.py: this build simulates the whole swarm on ONE GPU; --gpus must be 1 "
                          "(no collectives or sharding across GPUs are part of it)")
@@ -251,26 +433,38 @@ def main():
     if args.prefix:
         cfg["codec"], cfg["bits"] = "prefix", 16
     n, d, bits = cfg["n"], cfg["d"], cfg["bits"]
-    if cfg["objective"] == "mlp":
-        x0 = 0.02 * torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
-        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0, x0=x0)
-        s.set_objective_mlp(cfg["n_in"], cfg["n_hid"], cfg["n_out"], a, c, cfg["data_sigma"], cfg["batch"])
-    elif cfg["objective"] == "lsq":
-        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], 0, seed=0)
-        s.set_objective_lsq(a, c, cfg["m_rows"], cfg["batch"])
-    else:
-        s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], cfg["stale_max"], seed=0,
-                        apply_mode=swarm.INPLACE if args.inplace else swarm.DEFERRED,
-                        codec=swarm.CODEC_PREFIX if args.prefix else swarm.CODEC_FIXED,
-                        scale_policy=swarm.SCALE_GLOBAL_LINF if args.global_scale else swarm.SCALE_FIXED)
-        s.set_objective_diag(a, c, cfg["sigma"])
+    sequential = args.sequential or cfg["mode"] == "sequential"
+    s = make_swarm(swarm, torch, cfg, edges, a, c, eps, args, stale_max=0 if sequential else None)
 
-    def step_sequential():
-        s.interact(*s.sample_pair())          # one step of Algorithm 1: initiator's local steps + interaction
+    # clock ramp: a few plain copies before the warm-up steps (not steps of the path, never timed)
+    ramp_src = s.models_view(swarm.COMM)
+    ramp_dst = torch.empty_like(ramp_src[: max(1, n // 4)])
+    for _ in range(20):
+        swarm.stream_copy(ramp_dst, ramp_src[: max(1, n // 4)])
+    torch.cuda.synchronize()
+    del ramp_dst
+
+    workload = (f"config {args.config}: n={n} d={d} graph={cfg['graph']} {cfg['objective']} "
+                f"sigma={cfg.get('sigma', cfg.get('data_sigma'))} H={cfg['H']} lr={cfg['lr']} bits={bits} "
+                f"stale_max={cfg['stale_max']} ({cfg.get('stale', 'fresh')}) eps={eps}")
+    if sequential:
+        batch = cfg.get("steps", 256) if cfg["mode"] == "sequential" else 256
+        rep = sequential_report(torch, swarm, s, cfg, batch, args.steps, args.warmup)
+        out = {"metric": "node-interactions/sec + gossip-avg HBM GB/s (% of peak), n=64 d=25.6M",
+               "value": rep["interactions_per_s"], "unit": "interactions/s", "n_gpus": 1, "steps": args.steps,
+               "warmup": args.warmup, "ms_per_step": rep["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+               "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+               "config": {"workload": workload + " -- Algorithm 1, fresh reads", "step": rep["step"],
+                          "interactions_per_launch": rep["interactions_per_launch"],
+                          **({"one_call_per_interaction": rep["one_call_per_interaction"]}
+                             if "one_call_per_interaction" in rep else {})},
+               "roofline": rep["roofline"]}
+        if not args.no_cpu_baseline and cfg["objective"] == "lsq":
+            out["cpu_baseline"] = cpu_baseline(cfg, edges, a, c, eps)
+        print(json.dumps(out))
+        return
 
     def step_two_calls():
-        if cfg["mode"] == "sequential":
-            return step_sequential()
         s.local_steps()
         s.gossip_round(None, stale_plan(cfg, s))
 
@@ -325,22 +519,26 @@ def main():
         "ms_per_step": main_m["dt"] / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config {args.config}: n={n} d={d} graph={cfg['graph']} {cfg['objective']} "
-                               f"sigma={cfg.get('sigma', cfg.get('data_sigma'))} H={cfg['H']} lr={cfg['lr']} bits={bits} "
-                               f"stale_max={cfg['stale_max']} ({cfg.get('stale', 'fresh')}) eps={eps}",
+        "config": {"workload": workload,
                    "apply_mode": "inplace" if args.inplace else "deferred",
                    **({"scale": "per round (SWARM_SCALE_GLOBAL_LINF)", "eps_after_the_run": s.scale()[0]}
                       if args.global_scale else {}),
                    "step": ("one-pass round (swarm_round_fused)" if use_one_pass
-                            else "swarm_sample_pair + swarm_interact (Algorithm 1)" if cfg["mode"] == "sequential"
                             else "swarm_local_steps + swarm_gossip_round"),
                    "pairs_per_round": main_m["interactions"] / args.steps,
                    "node_updates_per_s": 2.0 * main_m["interactions"] / main_m["dt"],
-                   "decode_failures": main_m["decode_failures"],
+                   # the device counts a decode failure where a FRESH read decodes to another lattice point than the
+                   # sender's; with every read stale there is nothing to compare with on the device
+                   "decode_failures": None if all_stale else main_m["decode_failures"],
+                   **({"decode_failures_note": "not counted: every read is stale"} if all_stale else {}),
+                   "gradient_noise": "16-bit uniforms, one Philox call per 8 normals (the build's choice; with one call "
+                                     "per 4 normals on 24-bit uniforms the same kernel measured about 5 points lower)",
                    **({"registers": "multi-resolution (16-bit planes, prefix reads)",
                        "tile_reads_at_4_8_16_bits": main_m["prefix_tiles"]} if args.prefix else {})},
         "roofline": roof,
     }
+    if cfg["objective"] == "diag":
+        out["step_roofline"] = step_roofline("round" if use_one_pass else "gossip", cfg, main_m, d, n, args.inplace)
     if two_m is not None:
         out["two_call_round"] = two_call_report(two_m)
     if one_m is not None and not use_one_pass:
@@ -373,9 +571,24 @@ def main():
     mix_gbs = (n_read + 1) * stream_bytes * 5 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     out["roofline"]["same_streams_copy_GBps"] = mix_gbs
     out["roofline"]["frac_of_same_streams_copy"] = out["roofline"]["achieved"] / mix_gbs
-    del dst
+    del dst, src
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, edges, a, c, eps)
+    # The other configurations, after the headline's timed region: compact records in the same line.
+    if args.config == 4 and not args.no_configs and not (args.inplace or args.prefix or args.global_scale or args.d or args.H):
+        configs = {}
+        # Algorithm 1 at the headline's shape (fresh reads; the sequential model has no stale partner copies)
+        seq = make_swarm(swarm, torch, cfg, edges, a, c, eps, stale_max=0)
+        rec = sequential_report(torch, swarm, seq, cfg, 256, max(2, args.config_steps // 4), 1)
+        rec["workload"] = workload + " -- Algorithm 1, fresh reads"
+        configs["4-sequential"] = rec
+        seq.close()
+        s.close()
+        del seq, s, a, c
+        torch.cuda.empty_cache()
+        for other in (2, 5, 3, 1):
+            configs[str(other)] = compact_config(torch, swarm, other, args.config_steps, 3)
+        out["configs"] = configs
     print(json.dumps(out))
 
 

@@ -205,6 +205,20 @@ swarm_status swarm_round_fused(swarm_t h, const uint32_t *pairs_host, uint32_t n
  * Xhat_i <- X_i.  Requires stale_max = 0 and DEFERRED apply mode. */
 swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j);
 
+/* The next `count` steps of Algorithm 1, pairs drawn as by swarm_sample_pair, with the result --
+ * models, snapshots, registers, counters -- that `count` calls of swarm_sample_pair + swarm_interact
+ * give, bit for bit.  Interactions on disjoint node sets commute (Section 2, "The Distributed System
+ * Model": the unit of time is one pairwise interaction, and Theta(n) of them can occur in parallel),
+ * so each interaction joins the earliest kernel launch after the last one that touches either of its
+ * nodes, and a launch carries all its interactions as grid rows; no per-interaction host work or
+ * copy remains.  For the diagonal objective (fixed-width codes) the initiator's local steps are
+ * taken inside the interaction kernel and the live copy W is neither written nor read (it keeps its
+ * old contents); for the other objectives they are one more launch per group.
+ * pairs_host: receives the 2*count node ids (initiator, responder) in the order of Algorithm 1, or
+ * NULL.  launches: receives the number of interaction launches, or NULL.  Same requirements as
+ * swarm_interact. */
+swarm_status swarm_run_sequential(swarm_t h, uint32_t count, uint32_t *pairs_host, uint32_t *launches);
+
 /* Algorithm 1's sampling: initiator uniform over nodes, responder uniform over its
  * neighbours, for the current interaction number.  Does not touch the device. */
 swarm_status swarm_sample_pair(swarm_t h, uint32_t *i, uint32_t *j);

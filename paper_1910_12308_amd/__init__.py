@@ -24,7 +24,7 @@ _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_E
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
            "swarm_set_objective_mlp", "swarm_local_steps", "swarm_mark_pending", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
-           "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
+           "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_run_sequential", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
            "swarm_state_bytes", "swarm_save_state", "swarm_load_state",
            "swarm_potential", "swarm_potential_static", "swarm_pair_linf", "swarm_scale", "swarm_prefix_stats", "swarm_counters", "swarm_timing_reset", "swarm_kernel_times",
@@ -66,6 +66,7 @@ def load_library():
         "swarm_gossip_round": [vp, vp, u32, vp],
         "swarm_round_fused": [vp, vp, u32, vp],
         "swarm_interact": [vp, u32, u32],
+        "swarm_run_sequential": [vp, u32, vp, P(u32)],
         "swarm_sample_pair": [vp, P(u32), P(u32)],
         "swarm_quantize": [vp, u64, f32, u32, u64, u32, u32, vp, vp],
         "swarm_dequantize": [vp, vp, u64, f32, u32, vp, vp],
@@ -238,6 +239,14 @@ class Swarm:
 
     def interact(self, i, j):
         self._check(self._lib.swarm_interact(self._h, int(i), int(j)))
+
+    def run_sequential(self, count):
+        """The next `count` steps of Algorithm 1 in batched launches; returns (pairs, number of launches)."""
+        pairs = np.zeros((int(count), 2), dtype=np.uint32)
+        launches = ctypes.c_uint32()
+        self._check(self._lib.swarm_run_sequential(self._h, int(count), pairs.ctypes.data_as(ctypes.c_void_p),
+                                                   ctypes.byref(launches)))
+        return pairs, launches.value
 
     def sample_pair(self):
         i, j = ctypes.c_uint32(), ctypes.c_uint32()

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswarm.so")
 SOURCES = ["swarm_api.hip", "gossip.hip", "local_diag.hip", "local_lsq.hip", "local_mlp.hip",
-           "matching.hip", "reduce.hip", "stream_copy.hip", "fused.hip", "prefix.hip"]
+           "matching.hip", "reduce.hip", "stream_copy.hip", "fused.hip", "prefix.hip", "interact.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include"), "-I", CSRC]

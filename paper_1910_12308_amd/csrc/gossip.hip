@@ -224,53 +224,6 @@ __global__ __launch_bounds__(WAVES * 64) void gossip_singles_kernel(const Gossip
     }
 }
 
-// One step of Algorithm 1: the initiator i averages with responder j, adds the steps it
-// computed at its snapshot, refreshes the snapshot; j receives the plain average.
-template <int BITS>
-__global__ __launch_bounds__(WAVES * 64) void interact_kernel(const GossipArgs a, uint32_t ni, uint32_t nj,
-                                                              int has_delta) {
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
-    const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
-    const bool inA = kA < a.d, inB = kB < a.d;
-    if (tile * TILE >= a.d) return;
-    float *xi = a.X + (uint64_t)ni * a.d, *xj = a.X + (uint64_t)nj * a.d, *hi = a.Xhat + (uint64_t)ni * a.d;
-    const float *wi = a.W + (uint64_t)ni * a.d;
-    const f4 zero = {0.f, 0.f, 0.f, 0.f};
-    const f4 xiA = inA ? ldg_nt(xi + kA) : zero, xiB = inB ? ldg_nt(xi + kB) : zero;
-    const f4 xjA = inA ? ldg_nt(xj + kA) : zero, xjB = inB ? ldg_nt(xj + kB) : zero;
-    f4 dA = zero, dB = zero;
-    if (has_delta) {
-        if (inA) dA = ldg_nt(wi + kA) - ldg_nt(hi + kA);
-        if (inB) dB = ldg_nt(wi + kB) - ldg_nt(hi + kB);
-    }
-    f4 avgA, avgB;
-    if constexpr (BITS > 0) {
-        const LaneRandom ri = row_random(a.seed, ni, a.event, tile, lane);
-        const LaneRandom rj = row_random(a.seed, nj, a.event, tile, lane);
-        bool clamped = false;
-        int fails = 0;
-        int ziA[4], ziB[4], zjA[4], zjB[4];
-        const uint64_t ciA = round_float4<BITS>(xiA, ri.a0, ri.a1, a.inv_eps, ziA, clamped);
-        const uint64_t ciB = round_float4<BITS>(xiB, ri.b0, ri.b1, a.inv_eps, ziB, clamped);
-        const uint64_t cjA = round_float4<BITS>(xjA, rj.a0, rj.a1, a.inv_eps, zjA, clamped);
-        const uint64_t cjB = round_float4<BITS>(xjB, rj.b0, rj.b1, a.inv_eps, zjB, clamped);
-        const float half_eps = 0.5f * a.eps;
-        avgA = averaged<BITS>(ziA, cjA, xiA, zero, a.inv_eps, half_eps, zjA, fails, clamped);
-        avgB = averaged<BITS>(ziB, cjB, xiB, zero, a.inv_eps, half_eps, zjB, fails, clamped);
-        uint8_t *pub_i = a.ring + ni * a.row_bytes, *pub_j = a.ring + nj * a.row_bytes;
-        if (inA) { store_code<BITS>(pub_i, kA / 4, ciA); store_code<BITS>(pub_j, kA / 4, cjA); }
-        if (inB) { store_code<BITS>(pub_i, kB / 4, ciB); store_code<BITS>(pub_j, kB / 4, cjB); }
-        if (!inA) { fails = 0; clamped = false; }
-        report(a.counters, fails, clamped);
-    } else {
-        avgA = 0.5f * (xiA + xjA);
-        avgB = 0.5f * (xiB + xjB);
-    }
-    if (inA) { const f4 o = avgA + dA; stg_nt(xi + kA, o); stg_nt(hi + kA, o); stg_nt(xj + kA, avgA); }
-    if (inB) { const f4 o = avgB + dB; stg_nt(xi + kB, o); stg_nt(hi + kB, o); stg_nt(xj + kB, avgB); }
-}
-
 // Stateless codec kernels (thread = 8 consecutive coordinates = one Philox call).
 template <int BITS>
 __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__ x, uint64_t d, float inv_eps,
@@ -361,20 +314,6 @@ hipError_t launch_gossip_singles(const GossipArgs &a, uint32_t bits, uint32_t ns
         case 4: gossip_singles_kernel<4><<<grid, WAVES * 64, 0, st>>>(a); break;
         case 8: gossip_singles_kernel<8><<<grid, WAVES * 64, 0, st>>>(a); break;
         case 16: gossip_singles_kernel<16><<<grid, WAVES * 64, 0, st>>>(a); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
-hipError_t launch_interact(const GossipArgs &a, uint32_t bits, uint32_t i, uint32_t j, bool has_delta,
-                           hipStream_t st) {
-    const dim3 grid = tile_grid(a.d, 1);
-    switch (bits) {
-        case 0: interact_kernel<0><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
-        case 2: interact_kernel<2><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
-        case 4: interact_kernel<4><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
-        case 8: interact_kernel<8><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
-        case 16: interact_kernel<16><<<grid, WAVES * 64, 0, st>>>(a, i, j, has_delta); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -12,7 +12,7 @@ void set_global_error(const char *message);
 struct DeviceCounters {
     unsigned long long decode_failures;
     unsigned int range_clamped;
-    unsigned int pad;
+    unsigned int barrier_timeouts;   // a workgroup gave up waiting for the others of its node (least-squares split form)
 };
 
 // Multi-resolution registers: tiles read beyond the first plane (to 8 bits, to 16 bits), the coordinates
@@ -69,28 +69,47 @@ struct GossipArgs {
 hipError_t launch_gossip_pairs(const GossipArgs &a, uint32_t bits, int delta_mode, int stale_mode,
                                uint32_t npairs, hipStream_t st);
 hipError_t launch_gossip_singles(const GossipArgs &a, uint32_t bits, uint32_t nsingles, hipStream_t st);
-hipError_t launch_interact(const GossipArgs &a, uint32_t bits, uint32_t i, uint32_t j, bool has_delta,
-                           hipStream_t st);
+// One interaction of Algorithm 1: initiator ni, responder nj, the interaction number that keys its
+// random streams, and flags: bit 0 = the initiator's live copy W carries steps to apply on top of the
+// average, bits 8-15 = the initiator's number of local steps (used when the steps are taken inside the
+// interaction kernel).  16 bytes: one scalar load per workgroup.
+struct SeqDesc {
+    uint32_t ni, nj, event, flags;
+};
+constexpr uint32_t SEQ_HAS_DELTA = 1u;
+// `count` interactions with pairwise disjoint node sets, one grid row each, described by descs_dev
+// (device), or the single interaction `one` when descs_dev is null.  local: take the initiators' local
+// steps of this diagonal objective in registers (from the snapshot, W untouched), or null.
+struct DiagObjective;
+hipError_t launch_interact(const GossipArgs &a, uint32_t bits, const SeqDesc *descs_dev, SeqDesc one, uint32_t count,
+                           const DiagObjective *local, float lr, hipStream_t st);
 hipError_t launch_quantize(const float *x, uint64_t d, float eps, float inv_eps, uint32_t bits,
                            uint64_t seed, uint32_t node, uint32_t event, uint8_t *codes,
                            DeviceCounters *counters, hipStream_t st);
 hipError_t launch_dequantize(const uint8_t *codes, const float *key, uint64_t d, float eps, float inv_eps,
                              uint32_t bits, float *out, hipStream_t st);
 
-// Local steps, diagonal quadratics: nodes == nullptr means rows 0..count-1; steps (device, one
-// word per node id) overrides H when not null.
-hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const uint32_t *nodes,
-                             const uint32_t *steps, uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
+// Which nodes take local steps in one launch, one entry per grid row ("slot"): device arrays of the
+// node id, the number of steps and the event (round or interaction number) that keys the node's
+// random streams.  A null array means: node = slot, H steps, the launch's common event.
+struct LocalSlots {
+    const uint32_t *nodes = nullptr, *steps = nullptr, *events = nullptr;
+};
+
+// Local steps, diagonal quadratics, for `count` slots.
+hipError_t launch_local_diag(const float *X, float *W, const float *a, const float *c, const LocalSlots &slots,
+                             uint32_t count, uint64_t d, uint32_t H, float lr, float sigma, uint64_t seed,
                              uint32_t event, hipStream_t st);
 
 // Round kernels for multi-resolution registers (16-bit code in three planes plus 64-bit tile checksums, read by
 // prefixes).  kind: 0 = pairs with any mix of fresh and stale reads, 1 = pairs whose reads are both stale,
 // 2 = unmatched nodes (rows = their number).  local: objective of the one-pass round, or null.
-struct DiagObjective;
 hipError_t launch_prefix(const GossipArgs &g, const DiagObjective *local, bool inplace, float lr, int kind, uint32_t rows,
                          hipStream_t st);
 // One step of Algorithm 1 with multi-resolution registers: initiator i reads responder j's register.
-hipError_t launch_prefix_interact(const GossipArgs &g, uint32_t i, uint32_t j, bool has_delta, hipStream_t st);
+// `count` interactions with pairwise disjoint node sets (descs_dev, device), or the single one `one`.
+hipError_t launch_prefix_interact(const GossipArgs &g, const SeqDesc *descs_dev, SeqDesc one, uint32_t count,
+                                  hipStream_t st);
 constexpr uint32_t PREFIX_TILE = 512;      // coordinates per checksum (one wave tile)
 
 // One lattice scale per round: state[0] = float bits of the coming round's scale, state[1] = float bits of

@@ -16,6 +16,7 @@
 // 0-31 carry one k index and lanes 32-63 another, and any pairing is valid as long as A and
 // B agree, so lanes 0-31 take k 0..7 of the slab and lanes 32-63 take k 8..15: operands
 // whose k runs contiguously in memory are fetched from LDS with two 128-bit reads.
+#include "internal.h"
 #include "objectives.h"
 #include "philox.hpp"
 
@@ -202,9 +203,10 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
 
 // Labels by inverse CDF: y = #{c : cdf[c] <= u}, u = (word >> 8) 2^-24, limited to n_out - 1.
 __global__ void mlp_labels_kernel(const float *__restrict__ cdf, const uint32_t *__restrict__ nodes,
-                                  uint32_t *__restrict__ labels, uint32_t n_out, uint32_t batch, uint64_t seed,
-                                  uint32_t event, uint32_t q) {
+                                  const uint32_t *__restrict__ events, uint32_t *__restrict__ labels, uint32_t n_out,
+                                  uint32_t batch, uint64_t seed, uint32_t event, uint32_t q) {
     const uint32_t slot = blockIdx.x, node = nodes ? nodes[slot] : slot;
+    if (events) event = events[slot];
     for (uint32_t s = threadIdx.x; s < batch; s += blockDim.x) {
         const Words4 w = stream(seed, TAG_LABEL, q, node, event, s >> 2);
         const uint32_t word = (s & 3u) == 0 ? w.w0 : (s & 3u) == 1 ? w.w1 : (s & 3u) == 2 ? w.w2 : w.w3;
@@ -222,10 +224,12 @@ __global__ void mlp_labels_kernel(const float *__restrict__ cdf, const uint32_t 
 // Features: x[s] = means[y_s] + sigma N(0, I); one Philox call per float4.
 __global__ __launch_bounds__(256) void mlp_features_kernel(const float *__restrict__ means,
                                                            const uint32_t *__restrict__ nodes,
+                                                           const uint32_t *__restrict__ events,
                                                            const uint32_t *__restrict__ labels, float *__restrict__ x,
                                                            uint32_t n_in, uint32_t batch, float sigma, uint64_t seed,
                                                            uint32_t event, uint32_t q) {
     const uint32_t slot = blockIdx.y, node = nodes ? nodes[slot] : slot;
+    if (events) event = events[slot];
     const uint64_t f = (uint64_t)blockIdx.x * 256 + threadIdx.x;       // float4 index within the batch
     if (f * 4 >= (uint64_t)batch * n_in) return;
     const uint32_t s = (uint32_t)(f * 4 / n_in), k = (uint32_t)(f * 4 % n_in);
@@ -311,18 +315,19 @@ static void gemm(const GemmArgs &g, uint32_t count, hipStream_t st) {
     mlp_gemm_kernel<A_KC, B_KC, EPI><<<grid, 256, 0, st>>>(g);
 }
 
-hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, const uint32_t *nodes,
+hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, const LocalSlots &slots,
                             uint32_t count, uint32_t n, uint64_t d, uint32_t H, float lr, uint64_t seed,
                             uint32_t event, hipStream_t st) {
     (void)n;
+    const uint32_t *nodes = slots.nodes;          // the number of steps is constant for this objective
     if (count == 0) return hipSuccess;
     const uint32_t I = o.n_in, Hd = o.n_hid, O = o.n_out, Bt = o.batch;
     const uint64_t off_b1 = (uint64_t)Hd * I, off_w2 = off_b1 + Hd, off_b2 = off_w2 + (uint64_t)O * Hd;
     for (uint32_t q = 0; q < H; ++q) {
         const float *src = q == 0 ? base : W;
-        mlp_labels_kernel<<<count, 128, 0, st>>>(o.cdf, nodes, o.labels, O, Bt, seed, event, q);
+        mlp_labels_kernel<<<count, 128, 0, st>>>(o.cdf, nodes, slots.events, o.labels, O, Bt, seed, event, q);
         mlp_features_kernel<<<dim3((unsigned)(((uint64_t)Bt * I / 4 + 255) / 256), count), 256, 0, st>>>(
-            o.means, nodes, o.labels, o.x, I, Bt, o.data_sigma, seed, event, q);
+            o.means, nodes, slots.events, o.labels, o.x, I, Bt, o.data_sigma, seed, event, q);
         GemmArgs g{};
         g.nodes = nodes; g.lr = lr;
         // hid = relu(x W1^T + b1):  M = batch, N = hid, K = in

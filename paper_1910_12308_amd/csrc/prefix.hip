@@ -347,9 +347,12 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_singles_kernel(const Prefix
 // lattice point is in registers: same decisions as a read from memory), X_i' = average + (W_i - Xhat_i),
 // X_j' = average, Xhat_i' = X_i'.  The average goes back into j's register with as many bits as the read
 // took (the initiator knows its distance to j's key by then), which only the bit count records.
-__global__ __launch_bounds__(WAVES * 64) void prefix_interact_kernel(const GossipArgs a, uint32_t ni, uint32_t nj, int has_delta) {
+__global__ __launch_bounds__(WAVES * 64) void prefix_interact_kernel(const GossipArgs a, const SeqDesc *descs, const SeqDesc one) {
     TileGeometry g;
     if (!geometry(a.d, WAVES, g)) return;
+    const SeqDesc sd = descs ? descs[blockIdx.y] : one;          // one grid row per interaction
+    const uint32_t ni = sd.ni, nj = sd.nj;
+    const bool has_delta = sd.flags & SEQ_HAS_DELTA;
     const LaneWeights lw = lane_weights(g.lane);
     const uint64_t oi = (uint64_t)ni * a.d, oj = (uint64_t)nj * a.d;
     NodeTile ti, tj;
@@ -361,7 +364,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_interact_kernel(const Gossi
         ti.dA = ldg_nt(a.W + oi + g.lA) - ldg_nt(a.Xhat + oi + g.lA);
         ti.dB = ldg_nt(a.W + oi + g.lB) - ldg_nt(a.Xhat + oi + g.lB);
     }
-    const LaneRandom ri = row_random(a.seed, ni, a.event, g.tile, g.lane), rj = row_random(a.seed, nj, a.event, g.tile, g.lane);
+    const LaneRandom ri = row_random(a.seed, ni, sd.event, g.tile, g.lane), rj = row_random(a.seed, nj, sd.event, g.tile, g.lane);
     bool cA = false, cB = false;
     round_float4<16>(ti.qA, ri.a0, ri.a1, a.inv_eps, ti.zA, cA);
     round_float4<16>(ti.qB, ri.b0, ri.b1, a.inv_eps, ti.zB, cB);
@@ -394,9 +397,11 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_interact_kernel(const Gossi
     report(a.counters, fails, (g.inA && cA) || (g.inB && cB) || ((g.inA || g.inB) && clamped));
 }
 
-hipError_t launch_prefix_interact(const GossipArgs &g, uint32_t i, uint32_t j, bool has_delta, hipStream_t st) {
+hipError_t launch_prefix_interact(const GossipArgs &g, const SeqDesc *descs_dev, SeqDesc one, uint32_t count,
+                                  hipStream_t st) {
+    if (count == 0) return hipSuccess;
     const uint64_t tiles = (g.d + TILE - 1) / TILE;
-    prefix_interact_kernel<<<dim3((unsigned)((tiles + WAVES - 1) / WAVES), 1, 1), WAVES * 64, 0, st>>>(g, i, j, has_delta);
+    prefix_interact_kernel<<<dim3((unsigned)((tiles + WAVES - 1) / WAVES), count, 1), WAVES * 64, 0, st>>>(g, descs_dev, one);
     return hipGetLastError();
 }
 

@@ -21,6 +21,8 @@ using namespace swarm;
 namespace {
 
 constexpr int DESC_SLOTS = 4;   // pinned staging slots for per-round metadata
+constexpr uint32_t SEQ_CHUNK = 1u << 15;                              // interactions of Algorithm 1 staged per upload
+constexpr size_t SEQ_ENTRY_BYTES = sizeof(swarm::SeqDesc) + 3 * sizeof(uint32_t);
 
 enum ObjectiveKind { OBJ_NONE = 0, OBJ_DIAG, OBJ_LSQ, OBJ_MLP };
 
@@ -39,7 +41,12 @@ struct swarm_ctx {
     float *X = nullptr, *W = nullptr, *Xhat = nullptr;
     uint8_t *ring = nullptr;
     uint32_t *edges_dev = nullptr, *prio_dev = nullptr, *counts_dev = nullptr, *nodes_dev = nullptr;
-    uint32_t *linf_dev = nullptr, *steps_dev = nullptr;   // steps_dev: local steps per node id (geometric law)
+    uint32_t *linf_dev = nullptr, *steps_dev = nullptr;   // steps_dev: local steps per slot of a launch (geometric law)
+    // batches of Algorithm 1: per interaction a descriptor, the initiator, its step count and its event
+    uint8_t *seq_dev = nullptr, *seq_host = nullptr;      // capacity seq_cap interactions each (seq_host pinned)
+    uint32_t seq_cap = 0;
+    hipEvent_t seq_free = nullptr;                        // the last upload from seq_host has completed
+    bool timing_armed = false;                            // HIP events around the passes: off until swarm_timing_reset
     PrefixStats *prefix_stats_dev = nullptr;   // multi-resolution registers: striped escalation counts
     float *eps_slots_dev = nullptr;     // one scale per round: scale of the codes in each ring slot
     uint32_t *scale_state_dev = nullptr; // [0] next scale, [1] disagreement of the last round with pairs, then the stripes
@@ -138,7 +145,7 @@ constexpr uint32_t MAX_TIMED_CALLS = 1024;
 
 // Record the start (which = 0) or stop (which = 1) event of timed call number `call`.
 swarm_status record_timing(swarm_t h, std::vector<hipEvent_t> &events, uint32_t call, int which) {
-    if (call >= MAX_TIMED_CALLS) return SWARM_OK;
+    if (!h->timing_armed || call >= MAX_TIMED_CALLS) return SWARM_OK;
     while (events.size() < 2 * (size_t)(call + 1)) {
         hipEvent_t e = nullptr;
         SWARM_HIP(h, hipEventCreate(&e));
@@ -185,47 +192,53 @@ uint32_t draw_steps(const swarm_config &c, uint32_t node, uint32_t event) {
     return k;
 }
 
-// Per-node step counts of this event on the device (one word per node id), or null when constant.
-swarm_status upload_steps(swarm_t h, uint32_t event, const uint32_t **steps_dev) {
+// Step counts of this event on the device, one word per slot of the launch (slot k = node ids[k], or
+// node k when ids is null), or null when the number of steps is constant.
+swarm_status upload_steps(swarm_t h, uint32_t event, const uint32_t *ids, uint32_t count, const uint32_t **steps_dev) {
     *steps_dev = nullptr;
     if (h->cfg.steps_law == SWARM_STEPS_CONSTANT) return SWARM_OK;
     uint8_t *slot = nullptr;
     unsigned slot_index = 0;
     SWARM_TRY(acquire_desc(h, &slot, &slot_index));
     uint32_t *dst = (uint32_t *)slot;
-    for (uint32_t i = 0; i < h->cfg.n; ++i) dst[i] = draw_steps(h->cfg, i, event);
-    SWARM_HIP(h, hipMemcpyAsync(h->steps_dev, slot, sizeof(uint32_t) * h->cfg.n, hipMemcpyHostToDevice, h->stream));
+    for (uint32_t k = 0; k < count; ++k) dst[k] = draw_steps(h->cfg, ids ? ids[k] : k, event);
+    SWARM_HIP(h, hipMemcpyAsync(h->steps_dev, slot, sizeof(uint32_t) * count, hipMemcpyHostToDevice, h->stream));
     SWARM_HIP(h, hipEventRecord(h->desc_free[slot_index], h->stream));
     *steps_dev = h->steps_dev;
     return SWARM_OK;
 }
 
-swarm_status run_local_steps(swarm_t h, const float *base, const uint32_t *nodes_dev, uint32_t count,
-                             uint32_t event) {
+// Enqueue the local-step kernels of the objective for `count` slots.
+swarm_status launch_local(swarm_t h, const float *base, const LocalSlots &slots, uint32_t count, uint32_t event) {
     const swarm_config &c = h->cfg;
     hipError_t e = hipSuccess;
-    const uint32_t *steps = nullptr;
-    if (h->kind == OBJ_MLP && c.steps_law != SWARM_STEPS_CONSTANT)
-        return fail(h, SWARM_ESTATE, "the MLP objective takes a constant number of local steps");
-    SWARM_TRY(upload_steps(h, event, &steps));
     switch (h->kind) {
         case OBJ_DIAG:
-            e = launch_local_diag(base, h->W, h->diag.a, h->diag.c, nodes_dev, steps, count, c.d, c.H, c.lr,
-                                  h->diag.sigma, c.seed, event, h->stream);
+            e = launch_local_diag(base, h->W, h->diag.a, h->diag.c, slots, count, c.d, c.H, c.lr, h->diag.sigma, c.seed,
+                                  event, h->stream);
             break;
         case OBJ_LSQ:
-            e = launch_local_lsq(base, h->W, h->lsq, nodes_dev, steps, count, c.d, c.H, c.lr, c.seed, event,
-                                 h->stream);
+            e = launch_local_lsq(base, h->W, h->lsq, slots, h->counters_dev, count, c.d, c.H, c.lr, c.seed, event, h->stream);
             break;
         case OBJ_MLP:
-            e = launch_local_mlp(base, h->W, h->mlp, nodes_dev, count, c.n, c.d, c.H, c.lr, c.seed, event,
-                                 h->stream);
+            e = launch_local_mlp(base, h->W, h->mlp, slots, count, c.n, c.d, c.H, c.lr, c.seed, event, h->stream);
             break;
         default:
             return fail(h, SWARM_ESTATE, "no objective set");
     }
     SWARM_HIP(h, e);
     return SWARM_OK;
+}
+
+// ids: host list of the nodes in nodes_dev (already uploaded), or null for all nodes.
+swarm_status run_local_steps(swarm_t h, const float *base, const uint32_t *ids, const uint32_t *nodes_dev, uint32_t count,
+                             uint32_t event) {
+    if (h->kind == OBJ_MLP && h->cfg.steps_law != SWARM_STEPS_CONSTANT)
+        return fail(h, SWARM_ESTATE, "the MLP objective takes a constant number of local steps");
+    LocalSlots slots;
+    slots.nodes = nodes_dev;
+    SWARM_TRY(upload_steps(h, event, ids, count, &slots.steps));
+    return launch_local(h, base, slots, count, event);
 }
 
 }  // namespace
@@ -387,6 +400,9 @@ swarm_status swarm_destroy(swarm_t h) {
     if (h->match_host) (void)hipHostFree(h->match_host);
     if (h->match_ready) (void)hipEventDestroy(h->match_ready);
     if (h->scalar_host) (void)hipHostFree(h->scalar_host);
+    if (h->seq_dev) (void)hipFree(h->seq_dev);
+    if (h->seq_host) (void)hipHostFree(h->seq_host);
+    if (h->seq_free) (void)hipEventDestroy(h->seq_free);
     for (hipEvent_t e : h->ev_gossip) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->ev_local) (void)hipEventDestroy(e);
     delete h;
@@ -409,6 +425,9 @@ swarm_status swarm_set_objective_lsq(swarm_t h, const float *A_dev, const float 
     free_lsq(h->lsq);
     h->lsq = LsqObjective{};
     h->lsq.A = A_dev; h->lsq.b = b_dev; h->lsq.m_rows = m_rows; h->lsq.batch = batch;
+    const hipError_t e = alloc_lsq(h->lsq, h->cfg.d, h->cfg.n);
+    if (e != hipSuccess) return fail(h, e == hipErrorOutOfMemory ? SWARM_ENOMEM : SWARM_EDEVICE,
+                                     std::string("least-squares exchange buffers: ") + hipGetErrorString(e));
     h->kind = OBJ_LSQ;
     return SWARM_OK;
 }
@@ -452,7 +471,7 @@ swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count)
         count = n;
     }
     SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 0));
-    SWARM_TRY(run_local_steps(h, h->X, nodes_dev, count, (uint32_t)h->round));
+    SWARM_TRY(run_local_steps(h, h->X, nodes, nodes_dev, count, (uint32_t)h->round));
     SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 1));
     h->timed_local += 1;
     if (h->cfg.apply_mode == SWARM_APPLY_INPLACE) return SWARM_OK;   // already applied: nothing is pending
@@ -720,15 +739,16 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     if (c.H > 0 && h->kind != OBJ_NONE) {
         SWARM_TRY(upload_nodes(h, &i, 1));
         SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 0));
-        SWARM_TRY(run_local_steps(h, h->Xhat, h->nodes_dev, 1, (uint32_t)h->interactions));
+        SWARM_TRY(run_local_steps(h, h->Xhat, &i, h->nodes_dev, 1, (uint32_t)h->interactions));
         SWARM_TRY(record_timing(h, h->ev_local, h->timed_local, 1));
         h->timed_local += 1;
         has_delta = true;
     }
     const GossipArgs a = gossip_args(h, (uint32_t)h->interactions, 0);
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
-    if (c.codec == SWARM_CODEC_PREFIX) SWARM_HIP(h, launch_prefix_interact(a, i, j, has_delta, h->stream));
-    else SWARM_HIP(h, launch_interact(a, c.bits, i, j, has_delta, h->stream));
+    const SeqDesc one{i, j, (uint32_t)h->interactions, has_delta ? SEQ_HAS_DELTA : 0u};
+    if (c.codec == SWARM_CODEC_PREFIX) SWARM_HIP(h, launch_prefix_interact(a, nullptr, one, 1, h->stream));
+    else SWARM_HIP(h, launch_interact(a, c.bits, nullptr, one, 1, nullptr, c.lr, h->stream));
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
     h->timed_gossip += 1;
     h->pending[i] = 0;
@@ -740,6 +760,130 @@ swarm_status swarm_interact(swarm_t h, uint32_t i, uint32_t j) {
     } else {
         h->bits_communicated += 2ull * c.d * (c.bits ? c.bits : 32);
     }
+    return SWARM_OK;
+}
+
+// Per-interaction staging of a batch: [SeqDesc | initiator | steps | event] x capacity.
+static swarm_status ensure_sequence_buffers(swarm_t h, uint32_t count) {
+    if (count <= h->seq_cap) return SWARM_OK;
+    count = std::max(count, std::min(SEQ_CHUNK, 1024u));
+    SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    if (h->seq_dev) { (void)hipFree(h->seq_dev); h->seq_dev = nullptr; }
+    if (h->seq_host) { (void)hipHostFree(h->seq_host); h->seq_host = nullptr; }
+    h->seq_cap = 0;
+    const size_t bytes = (size_t)count * SEQ_ENTRY_BYTES;
+    SWARM_HIP(h, hipMalloc((void **)&h->seq_dev, bytes));
+    SWARM_HIP(h, hipHostMalloc((void **)&h->seq_host, bytes, hipHostMallocDefault));
+    if (!h->seq_free) {
+        SWARM_HIP(h, hipEventCreateWithFlags(&h->seq_free, hipEventDisableTiming));
+        SWARM_HIP(h, hipEventRecord(h->seq_free, h->stream));
+    }
+    h->seq_cap = count;
+    return SWARM_OK;
+}
+
+swarm_status swarm_run_sequential(swarm_t h, uint32_t count, uint32_t *pairs_host, uint32_t *launches) {
+    if (!h) return SWARM_EINVAL;
+    const swarm_config &c = h->cfg;
+    if (launches) *launches = 0;
+    if (c.stale_max != 0) return fail(h, SWARM_EINVAL, "Algorithm 1 steps need stale_max = 0");
+    if (c.apply_mode != SWARM_APPLY_DEFERRED) return fail(h, SWARM_EINVAL, "Algorithm 1 defers the local steps");
+    if (c.scale_policy != SWARM_SCALE_FIXED) return fail(h, SWARM_EINVAL, "Algorithm 1 steps use the fixed lattice scale");
+    if (h->kind == OBJ_MLP && c.steps_law != SWARM_STEPS_CONSTANT)
+        return fail(h, SWARM_ESTATE, "the MLP objective takes a constant number of local steps");
+    if (count == 0) return SWARM_OK;
+    for (const std::vector<uint32_t> &nb : h->adj)
+        if (nb.empty()) return fail(h, SWARM_ESTATE, "a node has no neighbour");
+    SWARM_TRY(ensure_snapshots(h));
+    const bool with_steps = c.H > 0 && h->kind != OBJ_NONE;
+    // the diagonal objective is per-coordinate: its steps are taken inside the interaction kernel
+    const bool steps_inside = with_steps && h->kind == OBJ_DIAG && c.codec == SWARM_CODEC_FIXED;
+    // small least-squares models: one workgroup runs an initiator's steps and then its interaction
+    const bool lsq_inside = with_steps && h->kind == OBJ_LSQ && c.codec == SWARM_CODEC_FIXED && h->lsq.part != nullptr;
+    const uint64_t tiles = (c.d + PREFIX_TILE - 1) / PREFIX_TILE;
+    const GossipArgs a = gossip_args(h, 0, 0);
+    uint32_t total_launches = 0;
+    SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
+    std::vector<uint32_t> level_of, last_level(c.n), order, level_start;
+    for (uint32_t done = 0; done < count;) {
+        const uint32_t m = std::min(count - done, SEQ_CHUNK);
+        SWARM_TRY(ensure_sequence_buffers(h, m));
+        // 1. the pairs Algorithm 1 draws next, and the earliest launch each interaction can join: one
+        //    after the last launch that touches either of its nodes (interactions on disjoint nodes commute).
+        level_of.assign(m, 0);
+        std::fill(last_level.begin(), last_level.end(), 0u);
+        std::vector<SeqDesc> drawn(m);
+        uint32_t levels = 0;
+        for (uint32_t t = 0; t < m; ++t) {
+            const uint32_t event = (uint32_t)(h->interactions + t);
+            const Words4 w = stream(c.seed, TAG_PICK, 0, 0, event, 0);
+            const uint32_t i = scaled_index(w.w0, c.n);
+            const std::vector<uint32_t> &nb = h->adj[i];
+            const uint32_t j = nb[scaled_index(w.w1, (uint32_t)nb.size())];
+            const bool has_delta = with_steps || h->pending[i];
+            h->pending[i] = 0;
+            const uint32_t steps = with_steps ? draw_steps(c, i, event) : 0u;
+            drawn[t] = SeqDesc{i, j, event, (has_delta ? SEQ_HAS_DELTA : 0u) | (steps << 8)};
+            const uint32_t level = std::max(last_level[i], last_level[j]) + 1;
+            last_level[i] = last_level[j] = level;
+            level_of[t] = level - 1;
+            levels = std::max(levels, level);
+            if (pairs_host) { pairs_host[2 * (size_t)(done + t)] = i; pairs_host[2 * (size_t)(done + t) + 1] = j; }
+        }
+        // 2. interactions grouped by launch, in their own order inside a launch
+        level_start.assign(levels + 1, 0);
+        for (uint32_t t = 0; t < m; ++t) level_start[level_of[t] + 1] += 1;
+        for (uint32_t l = 0; l < levels; ++l) level_start[l + 1] += level_start[l];
+        order.assign(level_start.begin(), level_start.end() - 1);
+        SWARM_HIP(h, hipEventSynchronize(h->seq_free));
+        SeqDesc *descs = (SeqDesc *)h->seq_host;
+        uint32_t *ids = (uint32_t *)(h->seq_host + (size_t)h->seq_cap * sizeof(SeqDesc));
+        uint32_t *steps = ids + h->seq_cap, *events = steps + h->seq_cap;
+        for (uint32_t t = 0; t < m; ++t) {
+            const uint32_t at = order[level_of[t]]++;
+            descs[at] = drawn[t];
+            ids[at] = drawn[t].ni;
+            steps[at] = drawn[t].flags >> 8;
+            events[at] = drawn[t].event;
+        }
+        SWARM_HIP(h, hipMemcpyAsync(h->seq_dev, h->seq_host, (size_t)h->seq_cap * SEQ_ENTRY_BYTES, hipMemcpyHostToDevice,
+                                    h->stream));
+        SWARM_HIP(h, hipEventRecord(h->seq_free, h->stream));
+        const SeqDesc *descs_dev = (const SeqDesc *)h->seq_dev;
+        const uint32_t *ids_dev = (const uint32_t *)(h->seq_dev + (size_t)h->seq_cap * sizeof(SeqDesc));
+        // 3. one launch per group (preceded by the initiators' local steps where they are a kernel of their own)
+        for (uint32_t l = 0; l < levels; ++l) {
+            const uint32_t off = level_start[l], width = level_start[l + 1] - off;
+            if (lsq_inside) {
+                SWARM_HIP(h, launch_lsq_interact(a, c.bits, descs_dev + off, width, h->lsq, c.lr, h->stream));
+                continue;
+            }
+            if (with_steps && !steps_inside) {
+                LocalSlots slots;
+                slots.nodes = ids_dev + off;
+                slots.steps = c.steps_law == SWARM_STEPS_CONSTANT ? nullptr : ids_dev + h->seq_cap + off;
+                slots.events = ids_dev + 2 * (size_t)h->seq_cap + off;
+                SWARM_TRY(launch_local(h, h->Xhat, slots, width, 0));
+            }
+            if (c.codec == SWARM_CODEC_PREFIX)
+                SWARM_HIP(h, launch_prefix_interact(a, descs_dev + off, SeqDesc{}, width, h->stream));
+            else
+                SWARM_HIP(h, launch_interact(a, c.bits, descs_dev + off, SeqDesc{}, width, steps_inside ? &h->diag : nullptr,
+                                             c.lr, h->stream));
+        }
+        total_launches += levels;
+        h->interactions += m;
+        if (c.codec == SWARM_CODEC_PREFIX) {
+            h->bits_communicated += (uint64_t)m * 2ull * (c.d * 4 + 64ull * tiles);
+            h->prefix_tile_reads += (uint64_t)m * tiles;
+        } else {
+            h->bits_communicated += (uint64_t)m * 2ull * c.d * (c.bits ? c.bits : 32);
+        }
+        done += m;
+    }
+    SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
+    h->timed_gossip += 1;
+    if (launches) *launches = total_launches;
     return SWARM_OK;
 }
 
@@ -1012,6 +1156,8 @@ swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions,
                              12ull * (total.coords[1] + total.written_back[1]);
     }
     if (decode_failures) *decode_failures = dc->decode_failures;
+    if (dc->barrier_timeouts)
+        return fail(h, SWARM_EDEVICE, "least-squares local steps: a workgroup timed out waiting for the others of its node");
     if (dc->range_clamped) return fail(h, SWARM_ERANGE, "|x/eps| reached the clamp 2^29");
     return SWARM_OK;
 }
@@ -1048,6 +1194,7 @@ swarm_status swarm_stream_mix(void *dst_dev, const void *src_dev, uint64_t strea
 swarm_status swarm_timing_reset(swarm_t h) {
     if (!h) return SWARM_EINVAL;
     h->timed_gossip = h->timed_local = 0;
+    h->timing_armed = true;
     return SWARM_OK;
 }
 
