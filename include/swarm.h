@@ -39,7 +39,8 @@ typedef enum {
     SWARM_ENOMEM = 2,   /* device or host allocation failed                               */
     SWARM_EDEVICE = 3,  /* a HIP call failed                                              */
     SWARM_ESTATE = 4,   /* call not valid in the handle's state (e.g. no objective set)   */
-    SWARM_ERANGE = 5    /* reported by swarm_counters: |x/eps| reached the clamp 2^29     */
+    SWARM_ERANGE = 5    /* reported by swarm_counters: |x/eps| reached the clamp 2^29, or a
+                           coordinate was not a number                                    */
 } swarm_status;
 
 /* When the local steps reach the exchanged model.  DEFERRED (the paper: the node computes its
@@ -101,9 +102,10 @@ enum { SWARM_MODELS_COMM = 0,  /* X: current / communicated models              
 
 /* Problem statement (Section 2; Section 3 "Sequential model"; Corollary 2.1 parameters). */
 typedef struct {
-    uint32_t n;             /* number of nodes, >= 2                                       */
+    uint32_t n;             /* number of nodes, 2 .. 4096 (the round's matching runs in one
+                               workgroup that keeps the node states in its local memory)   */
     uint64_t d;             /* model dimension, a positive multiple of 8                   */
-    uint32_t n_edges;       /* edges of the undirected simple graph G                      */
+    uint32_t n_edges;       /* edges of the undirected simple graph G, at most 2^20          */
     const uint32_t *edges;  /* host, 2*n_edges endpoints (u, v), u != v; copied at init    */
     uint32_t bits;          /* b: code width, one of 0 (Q = identity, Corollary 4.2),
                                2, 4, 8, 16                                                 */
@@ -298,26 +300,6 @@ swarm_status swarm_prefix_stats(swarm_t h, uint64_t *tiles, uint64_t *unconfirme
  * Returns SWARM_ERANGE if the clamp was reached since init.  Synchronises. */
 swarm_status swarm_counters(swarm_t h, uint64_t *rounds, uint64_t *interactions,
                             uint64_t *bits_communicated, uint64_t *decode_failures);
-
-/* Timing aid: the library brackets the fused gossip pass of every swarm_gossip_round /
- * swarm_interact and the kernels of every swarm_local_steps with HIP events on the
- * handle's stream (up to 1024 calls of each kind between resets; later calls are not
- * recorded).  swarm_kernel_times synchronises and returns the summed device milliseconds
- * and the number of recorded calls since the last swarm_timing_reset. */
-swarm_status swarm_timing_reset(swarm_t h);
-swarm_status swarm_kernel_times(swarm_t h, double *gossip_ms, uint32_t *gossip_calls,
-                                double *local_ms, uint32_t *local_calls);
-
-/* Measurement aid: plain streaming copy of nbytes (a multiple of 16, at most 2^36) between
- * device buffers on the given stream -- the copy rate the gossip pass is compared with. */
-swarm_status swarm_stream_copy(void *dst_dev, const void *src_dev, uint64_t nbytes, void *hip_stream);
-
-/* Measurement aid: the same streaming access with n_read concurrent read streams (consecutive
- * blocks of stream_bytes in src_dev) summed into n_write write streams (consecutive blocks in
- * dst_dev; write stream w holds the sum plus w).  Shapes (n_read, n_write): (2,1), (3,1), (2,2),
- * (4,2), (6,2); others return SWARM_EINVAL.  stream_bytes a multiple of 16. */
-swarm_status swarm_stream_mix(void *dst_dev, const void *src_dev, uint64_t stream_bytes, uint32_t n_read,
-                              uint32_t n_write, void *hip_stream);
 
 const char *swarm_last_error(swarm_t h);
 

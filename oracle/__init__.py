@@ -43,5 +43,8 @@ Pin status per function (what each is checked against, other than itself):
                            from a wrong starting scale; stale read across a scale change by hand
   apply_mode "inplace"     X_i' = (w_i + w_j)/2 with w the closed-form local-step result
   potential                definition, and the Laplacian inequality of the appendix
+  potential_hat            three nodes by hand; Gamma-hat <= 2A + 2B of the appendix along a run,
+                           with the models and means at each node's last initiation tracked apart
+  lattice_coordinate       clamp values; what is not a number is flagged and saturates
   whole trajectories       parity unpinned beyond the invariants above
 """

@@ -23,9 +23,13 @@ def inv_eps_of(eps):
 
 
 def lattice_coordinate(x, eps):
-    """t = clamp(x * (1/eps)) in float32, and whether the clamp was active."""
-    t = np.asarray(x, dtype=F32) * inv_eps_of(eps)
-    clamped = np.abs(t) > CLAMP
+    """t = clamp(x * (1/eps)) in float32, and whether the clamp was active.  A coordinate that is
+    not a number has no lattice point: it is flagged like an overflow and sent as the lower end of
+    the clamp, so that a diverged model cannot pass for a finite one unnoticed."""
+    with np.errstate(invalid="ignore", over="ignore"):
+        t = np.asarray(x, dtype=F32) * inv_eps_of(eps)
+        clamped = ~(np.abs(t) <= CLAMP)
+    t = np.where(np.isnan(t), -CLAMP, t)
     return np.clip(t, -CLAMP, CLAMP).astype(F32), clamped
 
 

@@ -116,10 +116,9 @@ __device__ __forceinline__ NodeTile prepare(const PrefixArgs &pa, uint32_t node,
         t.qA = INPLACE ? wA : xA; t.qB = INPLACE ? wB : xB;
         t.dA = INPLACE ? zero : wA - xA; t.dB = INPLACE ? zero : wB - xB;
     } else {
-        f4 wA = xA, wB = xB;
-        if (pending) { wA = ldg_nt(a.W + on + lA); wB = ldg_nt(a.W + on + lB); }
         t.qA = xA; t.qB = xB;
-        t.dA = wA - xA; t.dB = wB - xB;          // zero when nothing is pending
+        t.dA = zero; t.dB = zero;
+        if (pending) { t.dA = ldg_nt(a.W + on + lA) - xA; t.dB = ldg_nt(a.W + on + lB) - xB; }
     }
     const LaneRandom r = row_random(a.seed, node, a.event, tile, lane);
     bool clampedA = false, clampedB = false;

@@ -11,9 +11,11 @@ namespace swarm {
 
 constexpr float LATTICE_CLAMP = 536870912.0f;   // 2^29: keeps z_i + z_j' inside int32
 
+// A coordinate that is not a number is flagged like an overflow and takes the lower end of the clamp
+// (fmaxf returns its other operand), so that a diverged model cannot pass for a finite one unnoticed.
 __device__ __forceinline__ float lattice_coord(float x, float inv_eps, bool &clamped) {
     const float t = x * inv_eps;
-    clamped |= fabsf(t) > LATTICE_CLAMP;
+    clamped |= !(fabsf(t) <= LATTICE_CLAMP);
     return fminf(fmaxf(t, -LATTICE_CLAMP), LATTICE_CLAMP);
 }
 

@@ -3,6 +3,7 @@
 // this directory; the host code below only validates arguments, keeps the small
 // per-round metadata (pairs, unmatched nodes, staleness, pending marks) and enqueues.
 #include "swarm.h"
+#include "swarm_bench.h"
 
 #include <algorithm>
 #include <cmath>
@@ -141,6 +142,7 @@ swarm_status ensure_snapshots(swarm_t h) {
     return SWARM_OK;
 }
 
+static_assert(MATCHING_MAX_NODES <= SINGLE_NODE_MASK, "node ids must fit the unmatched-node entries");
 constexpr uint32_t MAX_TIMED_CALLS = 1024;
 
 // Record the start (which = 0) or stop (which = 1) event of timed call number `call`.
@@ -273,7 +275,6 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
     if (cfg->codec > SWARM_CODEC_PREFIX) return fail(nullptr, SWARM_EINVAL, "unknown codec");
     if (cfg->codec == SWARM_CODEC_PREFIX && (cfg->bits != 16 || cfg->scale_policy != SWARM_SCALE_FIXED))
         return fail(nullptr, SWARM_EINVAL, "multi-resolution registers need bits = 16 and the fixed lattice scale");
-    if (cfg->n > SINGLE_NODE_MASK) return fail(nullptr, SWARM_EINVAL, "n exceeds 65535");
     if (cfg->n_edges == 0 || !cfg->edges) return fail(nullptr, SWARM_EINVAL, "graph has no edges");
     if (cfg->n_edges > MATCHING_MAX_EDGES) return fail(nullptr, SWARM_EINVAL, "too many edges");
 
@@ -891,6 +892,8 @@ swarm_status swarm_quantize(const float *x_dev, uint64_t d, float eps, uint32_t 
                             uint32_t event, void *codes_dev, void *hip_stream) {
     if (!x_dev || !codes_dev || d == 0 || d % 8 != 0 || !valid_bits(bits) || !(eps > 0.f))
         return fail(nullptr, SWARM_EINVAL, "quantize: bad argument");
+    if (((uintptr_t)x_dev & 15u) || ((uintptr_t)codes_dev & 7u))
+        return fail(nullptr, SWARM_EINVAL, "quantize: x_dev must be 16-byte aligned and codes_dev 8-byte aligned");
     const hipError_t e = launch_quantize(x_dev, d, eps, 1.0f / eps, bits, seed, node, event, (uint8_t *)codes_dev,
                                          nullptr, (hipStream_t)hip_stream);
     return e == hipSuccess ? SWARM_OK : fail(nullptr, SWARM_EDEVICE, hipGetErrorString(e));
@@ -900,6 +903,8 @@ swarm_status swarm_dequantize(const void *codes_dev, const float *key_dev, uint6
                               float *out_dev, void *hip_stream) {
     if (!codes_dev || !key_dev || !out_dev || d == 0 || d % 8 != 0 || !valid_bits(bits) || !(eps > 0.f))
         return fail(nullptr, SWARM_EINVAL, "dequantize: bad argument");
+    if (((uintptr_t)key_dev & 15u) || ((uintptr_t)out_dev & 15u) || ((uintptr_t)codes_dev & 7u))
+        return fail(nullptr, SWARM_EINVAL, "dequantize: key_dev and out_dev must be 16-byte aligned and codes_dev 8-byte aligned");
     const hipError_t e = launch_dequantize((const uint8_t *)codes_dev, key_dev, d, eps, 1.0f / eps, bits, out_dev,
                                            (hipStream_t)hip_stream);
     return e == hipSuccess ? SWARM_OK : fail(nullptr, SWARM_EDEVICE, hipGetErrorString(e));
@@ -1051,6 +1056,8 @@ swarm_status swarm_load_state(swarm_t h, const void *src_host, uint64_t nbytes) 
         SWARM_HIP(h, hipMemcpy(p.dev, in, p.bytes, hipMemcpyHostToDevice));
         in += (p.bytes + 7u) & ~(size_t)7u;
     }
+    if (!hd.has_snapshots && h->Xhat)     // saved before any step of Algorithm 1: the snapshots still equalled the models
+        SWARM_HIP(h, hipMemcpy(h->Xhat, h->X, (size_t)c.n * c.d * sizeof(float), hipMemcpyDeviceToDevice));
     h->round = hd.round; h->interactions = hd.interactions; h->bits_communicated = hd.bits_communicated;
     h->prefix_tile_reads = hd.prefix_tile_reads;
     h->match_round = ~0ull;          // a matching enqueued for the old round counter is of no use now

@@ -5,6 +5,11 @@ import numpy as np
 from oracle.swarm import SwarmOracle
 
 TOL_ELEMENTWISE = 1e-6     # averaging and elementwise updates (float32 path vs float64 oracle)
+# Where float32 local steps feed the averaging there are two float32 stages between the uploaded state and
+# the compared model: the H steps (each update w <- w - eta g rounds once, relative 6e-8 each, and the
+# gradient's own roundings enter scaled by eta <= 0.1) and then delta = w - x and average + delta (two more
+# roundings).  Each stage stays within the 1e-6 bound on its own; their sum is compared at twice that.
+TOL_TWO_STAGE = 2 * TOL_ELEMENTWISE
 TOL_GEMM = 1e-4            # GEMM-based gradients
 
 

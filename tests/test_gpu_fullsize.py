@@ -9,7 +9,7 @@ import torch
 import workloads as wl
 from oracle.objectives import DiagQuadratic, MixtureMLP
 from oracle.swarm import SwarmOracle
-from helpers import TOL_ELEMENTWISE, TOL_GEMM, assert_close
+from helpers import TOL_ELEMENTWISE, TOL_TWO_STAGE, TOL_GEMM, assert_close
 
 pytestmark = pytest.mark.gpu
 
@@ -92,7 +92,7 @@ def test_diag_configs_full_size_sampled_windows(gpu, cfg_id, eps, mode):
             for node in (0, n // 3, n - 1):
                 got = register_window(g, gpu, node, k0, width, bits, prefix, d)
                 assert np.array_equal(got, o.ring[r % (S + 1)][node]), f"codes window {k0} node {node} round {r}"
-            assert_close(g.read_models(gpu.COMM, k0=k0, length=width), o.X, 2 * TOL_ELEMENTWISE,
+            assert_close(g.read_models(gpu.COMM, k0=k0, length=width), o.X, TOL_TWO_STAGE,
                          f"X window {k0} round {r}")
     cnt = g.counters()
     assert cnt["rounds"] == 4 and cnt["interactions"] == oracles[0].interactions

@@ -6,7 +6,7 @@ import torch
 
 import workloads as wl
 from oracle.objectives import DiagQuadratic, LeastSquares
-from helpers import TOL_ELEMENTWISE, TOL_GEMM, assert_close, make_both
+from helpers import TOL_ELEMENTWISE, TOL_TWO_STAGE, TOL_GEMM, assert_close, make_both
 
 pytestmark = pytest.mark.gpu
 
@@ -116,7 +116,7 @@ def test_one_launch_of_disjoint_interactions_against_the_oracle(gpu, kind):
     one launch on the device -- against the oracle taking them one after the other.  Nothing the
     device quantizes depends on its own float32 local steps here, so codes are bit-exact."""
     g, _, c = build(gpu, kind, seed=31 + len(kind))
-    tol = TOL_GEMM if kind == "least squares" else 2 * TOL_ELEMENTWISE
+    tol = TOL_GEMM if kind == "least squares" else TOL_TWO_STAGE
     widths = []
     for rep in range(6):
         g.write_models(gpu.COMM, c.X)

@@ -9,17 +9,26 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "swarm.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(swarm_[a-z_0-9]+)\s*\(", text)))
+HEADERS = ["swarm.h", "swarm_bench.h"]
+
+
+def declared_symbols(headers=HEADERS):
+    names = set()
+    for header in headers:
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(swarm_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_calls_of_the_interaction():
-    names = declared_symbols()
+    names = declared_symbols(["swarm.h"])
     for must in ["swarm_init", "swarm_local_steps", "swarm_gossip_round", "swarm_quantize", "swarm_dequantize",
-                 "swarm_read_models", "swarm_interact", "swarm_sample_matching", "swarm_potential"]:
+                 "swarm_read_models", "swarm_interact", "swarm_run_sequential", "swarm_sample_matching", "swarm_potential"]:
         assert must in names
+    # the measurement aids are kept out of the product header
+    for aid in ["swarm_stream_copy", "swarm_stream_mix", "swarm_timing_reset", "swarm_kernel_times"]:
+        assert aid not in names and aid in declared_symbols(["swarm_bench.h"])
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -59,7 +68,7 @@ def test_header_is_plain_c_and_the_config_struct_matches_the_binding(tmp_path):
         pytest.skip("no C compiler")
     fields = [name for name, _ in swarm._Config._fields_]
     src = tmp_path / "layout.c"
-    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "swarm.h"\nint main(void) {\n'
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "swarm.h"\n#include "swarm_bench.h"\nint main(void) {\n'
                    '  printf("%zu\\n", sizeof(swarm_config));\n'
                    + "".join(f'  printf("%zu\\n", offsetof(swarm_config, {f}));\n' for f in fields)
                    + "  return 0;\n}\n")

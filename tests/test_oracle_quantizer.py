@@ -112,6 +112,12 @@ def test_negative_lattice_points_use_twos_complement_residues():
 def test_clamp_flag_and_bound():
     t, clamped = qz.lattice_coordinate(np.array([1e12, -1e12, 1.0], dtype=np.float32), 1e-3)
     assert clamped.tolist() == [True, True, False]
+    # what is not a number is flagged too and takes the lower end of the clamp; infinities saturate
+    t, clamped = qz.lattice_coordinate(np.array([np.nan, np.inf, -np.inf, 0.5], dtype=np.float32), 0.5)
+    assert clamped.tolist() == [True, True, True, False]
+    assert t.tolist() == [-2.0 ** 29, 2.0 ** 29, -2.0 ** 29, 1.0]
+    z = qz.stochastic_round(np.array([np.nan, np.inf], dtype=np.float32), 0.5, np.zeros(2, dtype=np.uint32))
+    assert z.tolist() == [-2 ** 29, 2 ** 29]
     assert abs(t[0]) == 2.0 ** 29 and abs(t[1]) == 2.0 ** 29
     z = qz.stochastic_round(np.array([1e12], dtype=np.float32), 1e-3, [7])
     assert int(z[0]) == 2 ** 29

@@ -197,7 +197,38 @@ def test_algorithm1_snapshot_and_responder_rules():
     for _ in range(2):
         w1 = w1 - np.float64(np.float32(0.1)) * a[1] * (w1 - c[1])
     assert np.allclose(o.X[1], (avg + X[2]) / 2 + (w1 - X[1]))
-    assert np.isfinite(o.potential_hat())
+
+
+def test_potential_of_the_snapshots_by_hand_and_against_its_bound():
+    """Gamma-hat = sum_i |Xhat_i - mu|^2 with mu the mean of the CURRENT models (appendix, "Potential
+    Functions").  By hand on three nodes; then the appendix's inequality Gamma-hat <= 2 A + 2 B along a
+    run, A = sum_i |X^i - mu|^2 and B = sum_i |mu_now - mu_then|^2 taken when node i last initiated."""
+    o = make(3, 8, wl.complete_graph(3))
+    o.X[:] = np.array([1.0, 2.0, 6.0])[:, None]          # mean 3 in every coordinate
+    o.Xhat[:] = np.array([0.0, 2.0, 4.0])[:, None]
+    assert o.potential_hat() == pytest.approx(8 * (9 + 1 + 1))
+    assert o.potential() == pytest.approx(8 * (4 + 1 + 9))
+    gen = np.random.Generator(np.random.PCG64(12))
+    n, d = 6, 16
+    a = gen.uniform(0.5, 2, (n, d)).astype(np.float32)
+    c = gen.standard_normal((n, d)).astype(np.float32)
+    o = make(n, d, wl.complete_graph(n), H=2, lr=0.1, seed=4, X=gen.standard_normal((n, d)))
+    o.objective = DiagQuadratic(a, c, 0.05)
+    then_x = [o.X[i].copy() for i in range(n)]            # X^i and mu at node i's last initiation (the start, before any)
+    then_mu = [o.mean() for _ in range(n)]
+    strict = 0
+    for t in range(60):
+        i, _ = o.step_sequential()
+        then_x[i], then_mu[i] = o.X[i].copy(), o.mean()
+        assert all(np.array_equal(o.Xhat[k], then_x[k]) for k in range(n))
+        mu = o.mean()
+        A = sum(((then_x[k] - then_mu[k]) ** 2).sum() for k in range(n))
+        B = sum(((mu - then_mu[k]) ** 2).sum() for k in range(n))
+        direct = sum(((then_x[k] - mu) ** 2).sum() for k in range(n))
+        assert o.potential_hat() == pytest.approx(direct, rel=1e-12)
+        assert o.potential_hat() <= 2 * A + 2 * B + 1e-12
+        strict += o.potential_hat() != pytest.approx(o.potential(), rel=1e-6)
+    assert strict > 30                                      # the snapshots really lag behind the current models
 
 
 def test_staleness_clock_second_moment_bound():
