@@ -16,6 +16,13 @@ constexpr int TILE = 512;          // coordinates per wave
 #endif
 constexpr int WAVES = SWARM_GOSSIP_WAVES;   // waves per workgroup
 
+// Tile index of this wave as a scalar: the wave number is the same in every lane, and reading it from the
+// first lane lets row bases and tile offsets live in scalar registers.
+__device__ __forceinline__ uint64_t wave_tile(uint32_t waves_per_group) {
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    return (uint64_t)blockIdx.x * waves_per_group + wave;
+}
+
 __device__ __forceinline__ f4 ldg_nt(const float *p) { return __builtin_nontemporal_load((const f4 *)p); }
 __device__ __forceinline__ void stg_nt(float *p, f4 v) { __builtin_nontemporal_store(v, (f4 *)p); }
 __device__ __forceinline__ uint32_t swap_with_neighbour(uint32_t v) {
@@ -84,7 +91,7 @@ __device__ __forceinline__ f4 averaged(const int z_own[4], uint64_t partner_code
         const int zp = decode_near<BITS>((uint32_t)(partner_code >> (m * BITS)) & MASK,
                                          key_cell(k[m], inv_eps, clamped));
         if (z_true) fails += (zp != z_true[m]);
-        o[m] = (float)(z_own[m] + zp) * half_eps + dl[m];
+        o[m] = fmaf((float)(z_own[m] + zp), half_eps, dl[m]);
     }
     return f4{o[0], o[1], o[2], o[3]};
 }

@@ -16,7 +16,7 @@ namespace swarm {
 template <int BITS, int LOCAL>
 __global__ __launch_bounds__(WAVES * 64) void interact_kernel(const InteractArgs ia) {
     const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t tile = wave_tile(WAVES);
     if (tile * TILE >= ia.g.d) return;
     const SeqDesc sd = ia.descs ? ia.descs[blockIdx.y] : ia.one;      // uniform: one scalar load
     interact_tile<BITS, LOCAL>(ia, sd, tile, lane);

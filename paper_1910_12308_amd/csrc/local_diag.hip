@@ -15,7 +15,7 @@ __global__ __launch_bounds__(WAVES * 64) void local_diag_kernel(const float *__r
                                                                 const LocalSlots slots, uint64_t d, uint32_t H,
                                                                 float lr, float sigma, uint64_t seed, uint32_t event) {
     const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t tile = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t tile = wave_tile(WAVES);
     if (tile * TILE >= d) return;
     const uint64_t kA = tile * TILE + 4ull * lane, kB = kA + TILE / 2;
     const bool inA = kA < d, inB = kB < d;

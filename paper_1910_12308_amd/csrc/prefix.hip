@@ -234,10 +234,10 @@ __device__ __forceinline__ void finish(const GossipArgs &a, uint32_t node, const
                                        uint64_t kA, uint64_t kB, bool inA, bool inB) {
     const float half_eps = 0.5f * a.eps;
     float *x = a.X + (uint64_t)node * a.d;
-    const f4 oA = {(float)(t.zA[0] + zpA[0]) * half_eps + t.dA.x, (float)(t.zA[1] + zpA[1]) * half_eps + t.dA.y,
-                   (float)(t.zA[2] + zpA[2]) * half_eps + t.dA.z, (float)(t.zA[3] + zpA[3]) * half_eps + t.dA.w};
-    const f4 oB = {(float)(t.zB[0] + zpB[0]) * half_eps + t.dB.x, (float)(t.zB[1] + zpB[1]) * half_eps + t.dB.y,
-                   (float)(t.zB[2] + zpB[2]) * half_eps + t.dB.z, (float)(t.zB[3] + zpB[3]) * half_eps + t.dB.w};
+    const f4 oA = {fmaf((float)(t.zA[0] + zpA[0]), half_eps, t.dA.x), fmaf((float)(t.zA[1] + zpA[1]), half_eps, t.dA.y),
+                   fmaf((float)(t.zA[2] + zpA[2]), half_eps, t.dA.z), fmaf((float)(t.zA[3] + zpA[3]), half_eps, t.dA.w)};
+    const f4 oB = {fmaf((float)(t.zB[0] + zpB[0]), half_eps, t.dB.x), fmaf((float)(t.zB[1] + zpB[1]), half_eps, t.dB.y),
+                   fmaf((float)(t.zB[2] + zpB[2]), half_eps, t.dB.z), fmaf((float)(t.zB[3] + zpB[3]), half_eps, t.dB.w)};
     if (inA) stg_nt(x + kA, oA);
     if (inB) stg_nt(x + kB, oB);
 }
@@ -249,7 +249,7 @@ struct TileGeometry {
 };
 __device__ __forceinline__ bool geometry(uint64_t d, int waves, TileGeometry &g) {
     g.lane = threadIdx.x & 63u;
-    g.tile = (uint64_t)blockIdx.x * waves + (threadIdx.x >> 6);
+    g.tile = wave_tile(waves);
     if (g.tile * TILE >= d) return false;
     g.kA = g.tile * TILE + 4ull * g.lane;
     g.kB = g.kA + TILE / 2;

@@ -20,12 +20,15 @@ __device__ __forceinline__ float lattice_coord(float x, float inv_eps, bool &cla
 }
 
 // z = floor(t) + [r16 + 1/2 < frac(t) 2^16]: P(up) is within 2^-17 of frac(t).
+// The comparison is taken as r16 < frac(t) 2^16 - 1/2: both sides are exact in float32 (frac has at most 24
+// significant bits below 1, the scaling is a power of two and 1/2 is a multiple of the spacing up to 2^16), so
+// the decision is the same.  frac(t) = t - floor(t) is exact except for tiny negative t, where the
+// subtraction rounds to 1 and the hardware fraction stays one step below: either way every r16 rounds up.
 __device__ __forceinline__ int stochastic_round(float x, float inv_eps, uint32_t r16, bool &clamped) {
     const float t = lattice_coord(x, inv_eps, clamped);
-    const float f = floorf(t);
-    const float frac = t - f;
-    const int up = ((float)r16 + 0.5f) < frac * 65536.0f;
-    return (int)f + up;
+    const float frac = __builtin_amdgcn_fractf(t);
+    const int up = (float)r16 < fmaf(frac, 65536.0f, -0.5f);
+    return (int)floorf(t) + up;
 }
 
 // Lattice cell of the key (round to nearest, ties to even).
