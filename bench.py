@@ -27,6 +27,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense fp32 matrix rate
+MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 matrix rate
 # HBM bytes per pair-coordinate from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by the stream-copy
 # calibration (see profiles/), at 4-bit codes with stale reads: key = (kernel, bits, stale).
 MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {("gossip", 4, True): 25.99, ("round", 4, True): 33.99}
@@ -292,6 +293,8 @@ def make_swarm(swarm, torch, cfg, edges, a, c, eps, args=None, stale_max=None):
         x0 = 0.02 * torch.randn(d, device="cuda", generator=torch.Generator(device="cuda").manual_seed(1))
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], S, seed=0, x0=x0)
         s.set_objective_mlp(cfg["n_in"], cfg["n_hid"], cfg["n_out"], a, c, cfg["data_sigma"], cfg["batch"])
+        if args is not None and args.mlp_bf16x3:
+            s.set_mlp_arithmetic(swarm.MLP_BF16X3)
     elif cfg["objective"] == "lsq":
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], 0, seed=0)
         s.set_objective_lsq(a, c, cfg["m_rows"], cfg["batch"])
@@ -368,19 +371,36 @@ def compact_config(torch, swarm, cfg_id, steps, warmup):
         def step():
             s.local_steps()
             s.gossip_round(None, None)
+        flops_node_step = 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"]
+        # weights read by the three forward/backward GEMMs and read + written by the two updating ones, per node and step
+        weight_bytes_node_step = 4.0 * (2 + 3 + 2) * cfg["n_in"] * cfg["n_hid"]
+
+        def local_steps_record(m, peak, what):
+            t = m["times"]
+            calls = max(1, t["local_calls"])
+            tflops = flops_node_step * n * cfg["H"] * calls / (t["local_ms"] * 1e-3) / 1e12
+            return {"kernel": what, "bound": "mfma", "flops_per_node_step": flops_node_step, "achieved": tflops, "peak": peak,
+                    "unit": "TFLOP/s", "frac": tflops / peak, "ms_per_round": t["local_ms"] / calls,
+                    "weight_traffic_GBps": weight_bytes_node_step * n * cfg["H"] * calls / (t["local_ms"] * 1e-3) / 1e9}
+
         m = measure(torch, s, step, steps, warmup)
-        t = m["times"]
-        flops = 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"] * n * cfg["H"] * t["local_calls"]
-        tflops = flops / (t["local_ms"] * 1e-3) / 1e12
         goss = roofline("gossip", "gossip_pairs_kernel", cfg, m, d)
         rec.update({"step": "swarm_local_steps (grouped fp32 MFMA GEMMs) + swarm_gossip_round", "steps": steps,
                     "ms_per_step": m["dt"] / steps * 1e3, "interactions_per_s": m["interactions"] / m["dt"],
-                    "roofline": {"kernel": "mlp_gemm_kernel (5 grouped GEMMs per node and local step, all local-step kernels timed)",
-                                 "bound": "mfma", "flops_per_node_step": 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"],
-                                 "achieved": tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                 "frac": tflops / MFMA_F32_PEAK_TFLOPS, "ms_per_round": t["local_ms"] / max(1, t["local_calls"])},
+                    "roofline": local_steps_record(m, MFMA_F32_PEAK_TFLOPS,
+                                                   "mlp_gemm_kernel (5 grouped float32 GEMMs per node and local step, all "
+                                                   "local-step kernels timed)"),
                     "gossip_pass": {k: goss[k] for k in ("kernel", "bound", "bytes_per_pair_coordinate", "achieved", "peak", "unit",
                                                          "frac", "ms_per_launch")}})
+        # the same steps with every product taken as three bf16 products (float32 accumulation): against a third of
+        # the dense bf16 rate, and against HBM for the weights it has to move
+        s.set_mlp_arithmetic(swarm.MLP_BF16X3)
+        m3 = measure(torch, s, step, steps, warmup)
+        r3 = local_steps_record(m3, MFMA_BF16_PEAK_TFLOPS / 3.0,
+                                "mlp_gemm3_kernel (the same GEMMs as hi*hi + hi*lo + lo*hi on the bf16 matrix cores)")
+        r3["hbm_frac_of_weight_traffic"] = r3["weight_traffic_GBps"] / HBM_PEAK_GBS
+        rec["bf16x3"] = {"ms_per_step": m3["dt"] / steps * 1e3, "interactions_per_s": m3["interactions"] / m3["dt"],
+                         "roofline": r3}
     s.close()
     del s, a, c
     torch.cuda.empty_cache()
@@ -411,6 +431,8 @@ def main():
     ap.add_argument("--global-scale", action="store_true",
                     help="one lattice scale per round, set from the disagreement the previous round reported "
                          "(needs a configuration with at least 8-bit codes)")
+    ap.add_argument("--mlp-bf16x3", action="store_true",
+                    help="MLP objective: GEMMs as three bf16 products per term instead of float32 matrix instructions")
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
     ap.add_argument("--H", type=int, default=None,
                     help="override the number of local steps (to find where a kernel turns ALU-bound)")
@@ -502,6 +524,7 @@ def main():
             flops = 5 * 2.0 * cfg["batch"] * cfg["n_in"] * cfg["n_hid"] * n * cfg["H"] * t["local_calls"]
             rep["local_steps_mfma_f32_TFLOPs"] = flops / (t["local_ms"] * 1e-3) / 1e12
             rep["local_steps_mfma_frac_of_157.3"] = rep["local_steps_mfma_f32_TFLOPs"] / 157.3
+            rep["local_steps_arithmetic"] = "three bf16 products per term" if args.mlp_bf16x3 else "float32 matrix instructions"
         elif t["local_ms"] > 0:
             rep["local_steps_GBps"] = 16.0 * d * n * t["local_calls"] / (t["local_ms"] * 1e-3) / 1e9
             rep["local_steps_frac_of_hbm_peak"] = rep["local_steps_GBps"] / HBM_PEAK_GBS

@@ -152,6 +152,16 @@ swarm_status swarm_set_objective_mlp(swarm_t h, uint32_t n_in, uint32_t n_hid, u
                                      const float *class_means_dev, const float *label_cdf_dev,
                                      float data_sigma, uint32_t batch);
 
+/* How the GEMMs of the MLP objective's local steps are computed.  FP32 (default): float32 matrix
+ * instructions, float32 accumulation.  BF16X3: every float32 operand x is split into hi = bf16(x) and
+ * lo = bf16(x - hi) on the fly and a product a b is taken as a_hi b_hi + a_hi b_lo + a_lo b_hi on the
+ * bf16 matrix cores, float32 accumulation; the dropped terms are below 2^-16 |a b| per product, well
+ * inside the 1e-4 bound of the GEMM-based gradients, and the local steps run at the speed of their
+ * memory traffic instead of the float32 matrix rate.  Models, activations and updates stay float32 in
+ * memory.  Call after swarm_set_objective_mlp (SWARM_ESTATE otherwise). */
+enum { SWARM_MLP_FP32 = 0, SWARM_MLP_BF16X3 = 1 };
+swarm_status swarm_set_mlp_arithmetic(swarm_t h, uint32_t arithmetic);
+
 /* Local steps (Section 3 "The Communication Procedure"; appendix, definition of
  * h~_i^q): for q = 1..H, w <- w - eta g~_i(w) starting from the node's current model X_i,
  * result stored in W_i and marked pending (computed, applied only after the averaging).

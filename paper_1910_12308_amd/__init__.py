@@ -20,10 +20,11 @@ DEFERRED, INPLACE = 0, 1
 CONSTANT, GEOMETRIC = 0, 1
 SCALE_FIXED, SCALE_PAIR_LINF, SCALE_GLOBAL_LINF = 0, 1, 2
 CODEC_FIXED, CODEC_PREFIX = 0, 1
+MLP_FP32, MLP_BF16X3 = 0, 1
 _STATUS = {1: "SWARM_EINVAL", 2: "SWARM_ENOMEM", 3: "SWARM_EDEVICE", 4: "SWARM_ESTATE", 5: "SWARM_ERANGE"}
 
 EXPORTS = ["swarm_init", "swarm_destroy", "swarm_set_objective_diag", "swarm_set_objective_lsq",
-           "swarm_set_objective_mlp", "swarm_local_steps", "swarm_mark_pending", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
+           "swarm_set_objective_mlp", "swarm_set_mlp_arithmetic", "swarm_local_steps", "swarm_mark_pending", "swarm_sample_matching", "swarm_sample_stale", "swarm_sample_steps",
            "swarm_gossip_round", "swarm_round_fused", "swarm_interact", "swarm_run_sequential", "swarm_sample_pair", "swarm_quantize", "swarm_dequantize",
            "swarm_read_models", "swarm_write_models", "swarm_models_ptr", "swarm_read_codes",
            "swarm_state_bytes", "swarm_save_state", "swarm_load_state",
@@ -58,6 +59,7 @@ def load_library():
         "swarm_set_objective_diag": [vp, vp, vp, f32],
         "swarm_set_objective_lsq": [vp, vp, vp, u32, u32],
         "swarm_set_objective_mlp": [vp, u32, u32, u32, vp, vp, f32, u32],
+        "swarm_set_mlp_arithmetic": [vp, u32],
         "swarm_local_steps": [vp, vp, u32],
         "swarm_mark_pending": [vp, vp, u32],
         "swarm_sample_matching": [vp, vp, P(u32)],
@@ -185,6 +187,10 @@ class Swarm:
                                                       _dev_ptr(class_means, torch.float32),
                                                       _dev_ptr(label_cdf, torch.float32), float(data_sigma),
                                                       int(batch)))
+
+    def set_mlp_arithmetic(self, arithmetic):
+        """MLP_FP32 (default) or MLP_BF16X3 (three bf16 products per term, float32 accumulation)."""
+        self._check(self._lib.swarm_set_mlp_arithmetic(self._h, int(arithmetic)))
 
     # ---- the interaction -------------------------------------------------------------
     def local_steps(self, nodes=None):

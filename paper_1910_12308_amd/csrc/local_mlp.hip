@@ -40,7 +40,21 @@ struct GemmArgs {
     uint32_t a_by_node, b_by_node, c_by_node, aux_by_node;
     uint32_t M, N, K, lda, ldb, ldc, ldaux;
     float lr;
+    uint32_t tiles_n, tiles_m, groups;   // workgroups of the launch: tiles_n x tiles_m per slot, total = their product x slots
 };
+
+// Which tile a workgroup computes.  The hardware deals consecutive workgroup ids round-robin over the 8
+// dies (XCDs), each with its own L2; the tiles of one node share that node's activations (and nothing
+// with other nodes), so the ids are renumbered to put all tiles of a node on one die, one after the
+// other: die x takes the x-th eighth of the (node, tile) list.  Ids past the end of the list do nothing.
+struct TileId { uint32_t slot, tile_m, tile_n; bool valid; };
+__device__ __forceinline__ TileId tile_of_workgroup(const GemmArgs &g) {
+    constexpr uint32_t DIES = 8;
+    const uint32_t chunk = (g.groups + DIES - 1) / DIES;
+    const uint32_t q = (blockIdx.x % DIES) * chunk + blockIdx.x / DIES;
+    const uint32_t per_slot = g.tiles_n * g.tiles_m, r = q % per_slot;
+    return TileId{q / per_slot, r / g.tiles_n, r % g.tiles_n, q < g.groups};
+}
 
 // Load a 128 x 16 slab of an operand whose k index is contiguous in memory: P[row * ld + k].
 __device__ __forceinline__ void fetch_kc(const float *P, uint32_t ld, uint32_t row0, uint32_t rows, uint32_t k0,
@@ -86,19 +100,99 @@ __device__ __forceinline__ void operand(const float *lds, uint32_t row, uint32_t
     }
 }
 
+// Epilogues that need a tile of another matrix (the weights to update, the ReLU mask source) request it
+// before the K loop, so that its HBM latency hides behind the MFMAs instead of serialising compute phase
+// and memory phase.  Tiles that lie wholly inside the matrix (all of them when M and N are multiples of
+// 128) take straight-line loads and stores; the guarded path serves ragged edges.
+template <int EPI>
+__device__ __forceinline__ void prefetch_aux(const GemmArgs &g, const float *aux, uint32_t m0, uint32_t n0, uint32_t wm,
+                                             uint32_t wn, uint32_t half, uint32_t r32, bool full_tile, float pre[2][2][16]) {
+    if (!(EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE)) return;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const uint32_t n = n0 + wn + 32 * ni + r32;
+            const uint32_t mb = m0 + wm + 32 * mi + 4 * half;
+            if (full_tile) {      // uniform base per value (wm, wn are scalars) plus the lane's own 32-bit offset
+                const uint32_t lane_off = 4 * half * g.ldaux + r32;
+                const float *base = aux + (uint64_t)(m0 + wm + 32 * mi) * g.ldaux + n0 + wn + 32 * ni;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float *src = base + (uint64_t)(8 * (v >> 2) + (v & 3)) * g.ldaux + lane_off;
+                    // weights about to be replaced are touched once: keep them out of the way of the cached activations
+                    pre[mi][ni][v] = EPI == EPI_SGD_UPDATE ? __builtin_nontemporal_load(src) : *src;
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t m = mb + 8 * (v >> 2) + (v & 3);
+                    pre[mi][ni][v] = (n < g.N && m < g.M) ? aux[(uint64_t)m * g.ldaux + n] : 0.f;
+                }
+            }
+        }
+}
+
+// Accumulator layout of a 32x32 block (every 32x32 MFMA shape): register v of lane l holds row
+// 8*(v/4) + 4*(l/32) + v%4, column l%32.
+// LATE: the tile of the other matrix was not requested ahead of the K loop and is read here.
+template <int EPI, bool LATE = false>
+__device__ __forceinline__ void epilogue(const GemmArgs &g, float *C, const float *aux, f16v acc[2][2], uint32_t m0,
+                                         uint32_t n0, uint32_t wm, uint32_t wn, uint32_t half, uint32_t r32, bool full_tile,
+                                         float pre[2][2][16]) {
+    if (LATE) prefetch_aux<EPI>(g, aux, m0, n0, wm, wn, half, r32, full_tile, pre);
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+            const uint32_t n = n0 + wn + 32 * ni + r32;
+            const uint32_t mb = m0 + wm + 32 * mi + 4 * half;
+            float bias = 0.f;
+            if ((EPI == EPI_BIAS_RELU || EPI == EPI_BIAS) && n < g.N) bias = aux[n];
+            float out[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float c = acc[mi][ni][v];
+                if (EPI == EPI_BIAS_RELU) c = fmaxf(c + bias, 0.f);
+                if (EPI == EPI_BIAS) c = c + bias;
+                if (EPI == EPI_RELU_MASK) c = pre[mi][ni][v] > 0.f ? c : 0.f;
+                if (EPI == EPI_SGD_UPDATE) c = fmaf(-g.lr, c, pre[mi][ni][v]);
+                out[v] = c;
+            }
+            if (full_tile) {
+                const uint32_t lane_off = 4 * half * g.ldc + r32;
+                float *base = C + (uint64_t)(m0 + wm + 32 * mi) * g.ldc + n0 + wn + 32 * ni;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float *dst = base + (uint64_t)(8 * (v >> 2) + (v & 3)) * g.ldc + lane_off;
+                    if (EPI == EPI_SGD_UPDATE) __builtin_nontemporal_store(out[v], dst); else *dst = out[v];
+                }
+            } else if (n < g.N) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const uint32_t m = mb + 8 * (v >> 2) + (v & 3);
+                    if (m < g.M) C[(uint64_t)m * g.ldc + n] = out[v];
+                }
+            }
+        }
+}
+
 // C (M x N) = op(A) op(B) with A_KC: A stored [m][k] else [k][m]; B_KC: B stored [n][k] else [k][n].
 template <bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
     constexpr int A_TILE = A_KC ? TM * LDK : TK * LDR, B_TILE = B_KC ? TN * LDK : TK * LDR;
     __shared__ __attribute__((aligned(16))) float lds_a[2][A_TILE];
     __shared__ __attribute__((aligned(16))) float lds_b[2][B_TILE];
-    const uint32_t slot = blockIdx.z, node = g.nodes ? g.nodes[slot] : slot;
+    const TileId id = tile_of_workgroup(g);
+    if (!id.valid) return;
+    const uint32_t slot = id.slot, node = g.nodes ? g.nodes[slot] : slot;
     const float *A = g.A + (g.a_by_node ? node : slot) * g.strideA;
     const float *B = g.B + (g.b_by_node ? node : slot) * g.strideB;
     float *C = g.C + (g.c_by_node ? node : slot) * g.strideC;
     const float *aux = g.aux + (g.aux_by_node ? node : slot) * g.strideAux;
-    const uint32_t m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, half = lane >> 5, r32 = lane & 31u;
+    const uint32_t m0 = id.tile_m * TM, n0 = id.tile_n * TN;
+    const uint32_t lane = threadIdx.x & 63u, half = lane >> 5, r32 = lane & 31u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // scalar: bases stay uniform
     const uint32_t wm = (wave >> 1) * 64, wn = (wave & 1u) * 64;
 
     f16v acc[2][2];
@@ -109,34 +203,9 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    // Epilogues that need a tile of another matrix (the weights to update, the ReLU mask source)
-    // request it before the K loop, so that its HBM latency hides behind the MFMAs instead of
-    // serialising compute phase and memory phase.
-    constexpr bool PREFETCH_AUX = EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE;
-    // Tiles that lie wholly inside the matrix (all of them when M and N are multiples of 128)
-    // take straight-line loads and stores; the guarded path serves ragged edges.
     const bool full_tile = m0 + TM <= g.M && n0 + TN <= g.N;
     float pre[2][2][16];
-    if (PREFETCH_AUX) {
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) {
-                const uint32_t n = n0 + wn + 32 * ni + r32;
-                const uint32_t mb = m0 + wm + 32 * mi + 4 * half;
-                if (full_tile) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        pre[mi][ni][v] = aux[(uint64_t)(mb + 8 * (v >> 2) + (v & 3)) * g.ldaux + n];
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const uint32_t m = mb + 8 * (v >> 2) + (v & 3);
-                        pre[mi][ni][v] = (n < g.N && m < g.M) ? aux[(uint64_t)m * g.ldaux + n] : 0.f;
-                    }
-                }
-            }
-    }
+    prefetch_aux<EPI>(g, aux, m0, n0, wm, wn, half, r32, full_tile, pre);
 
     f4 ra[2], rb[2];
     auto fetch = [&](uint32_t k0) {
@@ -169,36 +238,230 @@ __global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
         if (s + 1 < slabs) stash(cur ^ 1);
         __syncthreads();
     }
-    // Accumulator layout of the 32x32 block: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    epilogue<EPI>(g, C, aux, acc, m0, n0, wm, wn, half, r32, full_tile, pre);
+}
+
+// ---- the same GEMMs as three bf16 products -----------------------------------------------------------
+// Every float32 operand x is split into hi = bf16(x) and lo = bf16(x - hi) while its slab is staged into
+// LDS, and a product a b is taken as a_hi b_hi + a_hi b_lo + a_lo b_hi on the bf16 matrix cores with
+// float32 accumulation (the dropped terms are below 2^-16 |a b|).  The bf16 pipes run 16 times the
+// float32 rate, so even at three products per term the GEMMs stop being bound by the matrix cores and
+// follow the weights' memory traffic instead.
+// LDS layout of a 128 x 32 operand slab, for hi and for lo: [k / 8][row][8 bf16], 16 bytes per (octet,
+// row), so that the 32x32x16 MFMA's operand (lane l: row l % 32, k = 8 (l / 32) .. + 7) is one 128-bit
+// read with consecutive lanes on consecutive 16-byte words; the octet planes are padded so that the staging
+// writes of k-contiguous operands are free of bank conflicts too.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+constexpr int TK3 = 32;                             // K slab of the bf16 kernels: whole 128-byte lines per operand row
+constexpr int OCTS = TK3 / 8;                       // octets of k per slab
+constexpr int OCT_ROWS = TM + 8;                    // rows per octet plane: successive octets half the banks apart, so the
+                                                    // 8-byte staging writes of a wave (8 rows x 4 octets x 2 halves) hit
+                                                    // every bank exactly twice
+constexpr int SLAB_WORDS = OCTS * OCT_ROWS;         // 16-byte words of one operand slab (hi or lo)
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{a, b}, bf16x2));
+}
+// hi and lo halves of two floats, packed (first float in the low half).
+__device__ __forceinline__ void split2(float a, float b, uint32_t &hi, uint32_t &lo) {
+    hi = pack_bf16(a, b);
+    const float ha = __uint_as_float(hi << 16), hb = __uint_as_float(hi & 0xFFFF0000u);
+    lo = pack_bf16(a - ha, b - hb);
+}
+
+// k-contiguous operand P[row * ld + k]: a thread takes 4 consecutive k of four rows.  The lane's part of
+// the four addresses (row * ld + its k offset, 32 bits) is computed once per tile; per slab only the uniform
+// base moves.  Rows past the matrix edge re-read its last row: they only feed outputs that are never stored.
+struct LaneKc { uint32_t off[4]; };
+__device__ __forceinline__ LaneKc lane_kc(uint32_t ld, uint32_t row0, uint32_t rows) {
+    const uint32_t t = threadIdx.x;
+    LaneKc o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o.off[i] = min(row0 + (t >> 3) + 32 * i, rows - 1) * ld + 4 * (t & 7);
+    return o;
+}
+// STREAM: the operand is a weight matrix read once per launch (non-temporal), not a cached activation.
+template <bool STREAM>
+__device__ __forceinline__ void fetch3_kc(const float *P, const LaneKc &o, uint32_t k0, f4 r[4]) {
+    const float *base = P + k0;                                        // uniform
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        r[i] = STREAM ? __builtin_nontemporal_load((const f4 *)(base + o.off[i])) : *(const f4 *)(base + o.off[i]);
+}
+__device__ __forceinline__ void stash3_kc(u4 *hi, u4 *lo, const f4 r[4]) {
+    const uint32_t t = threadIdx.x, oct = (t & 7) >> 1, part = t & 1;      // k = 4 (t & 7) = 8 oct + 4 part
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t row = (t >> 3) + 32 * i;
+        uint32_t h0, l0, h1, l1;
+        split2(r[i].x, r[i].y, h0, l0);
+        split2(r[i].z, r[i].w, h1, l1);
+        uint2 *ph = (uint2 *)(hi + oct * OCT_ROWS + row) + part, *pl = (uint2 *)(lo + oct * OCT_ROWS + row) + part;
+        *ph = uint2{h0, h1};
+        *pl = uint2{l0, l1};
+    }
+}
+// row-contiguous operand P[k * ld + row]: a thread takes one row and the 8 k of two octets (scalar loads,
+// consecutive lanes on consecutive rows), so that it writes whole 16-byte words.  The octet is the same for
+// the whole wave, so each load is a uniform base plus the lane's row.
+template <bool STREAM>
+__device__ __forceinline__ void fetch3_rc(const float *P, uint32_t ld, uint32_t row, uint32_t wave, uint32_t k0,
+                                          float r[2][8]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t oct = (wave >> 1) + 2 * i;
+        const float *base = P + (uint64_t)(k0 + 8 * oct) * ld;          // uniform
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            r[i][j] = STREAM ? __builtin_nontemporal_load(base + (uint64_t)j * ld + row) : base[(uint64_t)j * ld + row];
+    }
+}
+__device__ __forceinline__ void stash3_rc(u4 *hi, u4 *lo, const float r[2][8]) {
+    const uint32_t t = threadIdx.x, row = t & 127;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t oct = (t >> 7) + 2 * i;
+        uint32_t h[4], l[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) split2(r[i][2 * j], r[i][2 * j + 1], h[j], l[j]);
+        hi[oct * OCT_ROWS + row] = u4{h[0], h[1], h[2], h[3]};
+        lo[oct * OCT_ROWS + row] = u4{l[0], l[1], l[2], l[3]};
+    }
+}
+
+// Scheduling hint for one pipeline iteration: one matrix instruction, then a few vector instructions, 24
+// times over (a 32x32x16 instruction keeps the matrix pipe busy for 32 cycles, a vector instruction issues
+// in 4).
+__device__ __forceinline__ void interleave_matrix_and_vector() {
+#pragma unroll
+    for (int i = 0; i < 24; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // matrix
+        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);    // vector ALU
+    }
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256, 2) void mlp_gemm3_kernel(const GemmArgs g) {
+    __shared__ u4 lds[2][4][SLAB_WORDS];            // buffer x {A hi, A lo, B hi, B lo}
+    const TileId id = tile_of_workgroup(g);
+    if (!id.valid) return;
+    const uint32_t slot = id.slot, node = g.nodes ? g.nodes[slot] : slot;
+    const float *A = g.A + (g.a_by_node ? node : slot) * g.strideA;
+    const float *B = g.B + (g.b_by_node ? node : slot) * g.strideB;
+    float *C = g.C + (g.c_by_node ? node : slot) * g.strideC;
+    const float *aux = g.aux + (g.aux_by_node ? node : slot) * g.strideAux;
+    const uint32_t m0 = id.tile_m * TM, n0 = id.tile_n * TN;
+    const uint32_t lane = threadIdx.x & 63u, half = lane >> 5, r32 = lane & 31u;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // scalar: bases stay uniform
+    const uint32_t wm = (wave >> 1) * 64, wn = (wave & 1u) * 64;
+
+    f16v acc[2][2];
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            const uint32_t n = n0 + wn + 32 * ni + r32;
-            const uint32_t mb = m0 + wm + 32 * mi + 4 * half;
-            float bias = 0.f;
-            if ((EPI == EPI_BIAS_RELU || EPI == EPI_BIAS) && n < g.N) bias = aux[n];
-            float out[16];
+        for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float c = acc[mi][ni][v];
-                if (EPI == EPI_BIAS_RELU) c = fmaxf(c + bias, 0.f);
-                if (EPI == EPI_BIAS) c = c + bias;
-                if (EPI == EPI_RELU_MASK) c = pre[mi][ni][v] > 0.f ? c : 0.f;
-                if (EPI == EPI_SGD_UPDATE) c = fmaf(-g.lr, c, pre[mi][ni][v]);
-                out[v] = c;
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    const bool full_tile = m0 + TM <= g.M && n0 + TN <= g.N;
+    // The weights an update needs are requested ahead of the K loop (its few slabs come from cache, the tile
+    // from memory); the ReLU mask is a cached activation and is read in the epilogue, which leaves the
+    // registers to the operand pipeline.
+    constexpr bool AUX_AHEAD = EPI == EPI_SGD_UPDATE;
+    float pre[2][2][16];
+    if (AUX_AHEAD) prefetch_aux<EPI>(g, aux, m0, n0, wm, wn, half, r32, full_tile, pre);
+
+    // Operand slabs travel two iterations ahead of their use: global memory -> registers (stage s + 2),
+    // registers -> LDS as bf16 hi / lo (stage s + 1), LDS -> matrix cores (stage s).  One slab in flight per
+    // workgroup does not cover the memory latency at two workgroups per compute unit.
+    struct Stage { f4 ka[4], kb[4]; float ra[2][8], rb[2][8]; };
+    const uint32_t uwave = wave;
+    const LaneKc lane_a = lane_kc(g.lda, m0, g.M), lane_b = lane_kc(g.ldb, n0, g.N);
+    const uint32_t row_a = min(m0 + (threadIdx.x & 127u), g.M - 1), row_b = min(n0 + (threadIdx.x & 127u), g.N - 1);
+    auto fetch = [&](uint32_t k0, Stage &r) {
+        // in the forward and backward products B is a weight matrix; in the updates both operands are activations
+        constexpr bool B_STREAM = EPI != EPI_SGD_UPDATE;
+        if (A_KC) fetch3_kc<false>(A, lane_a, k0, r.ka); else fetch3_rc<false>(A, g.lda, row_a, uwave, k0, r.ra);
+        if (B_KC) fetch3_kc<B_STREAM>(B, lane_b, k0, r.kb); else fetch3_rc<B_STREAM>(B, g.ldb, row_b, uwave, k0, r.rb);
+    };
+    auto stash = [&](int buf, const Stage &r) {
+        if (A_KC) stash3_kc(lds[buf][0], lds[buf][1], r.ka); else stash3_rc(lds[buf][0], lds[buf][1], r.ra);
+        if (B_KC) stash3_kc(lds[buf][2], lds[buf][3], r.kb); else stash3_rc(lds[buf][2], lds[buf][3], r.rb);
+    };
+    auto multiply = [&](int cur) {
+#pragma unroll
+        for (int ks = 0; ks < TK3 / 16; ++ks) {      // one 32x32x16 step per pair of octets
+            bf16x8 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const uint32_t w = (2 * ks + half) * OCT_ROWS + wm + 32 * mi + r32;
+                ah[mi] = __builtin_bit_cast(bf16x8, lds[cur][0][w]);
+                al[mi] = __builtin_bit_cast(bf16x8, lds[cur][1][w]);
             }
-            if (full_tile) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) C[(uint64_t)(mb + 8 * (v >> 2) + (v & 3)) * g.ldc + n] = out[v];
-            } else if (n < g.N) {
+            for (int ni = 0; ni < 2; ++ni) {
+                const uint32_t w = (2 * ks + half) * OCT_ROWS + wn + 32 * ni + r32;
+                bh[ni] = __builtin_bit_cast(bf16x8, lds[cur][2][w]);
+                bl[ni] = __builtin_bit_cast(bf16x8, lds[cur][3][w]);
+            }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const uint32_t m = mb + 8 * (v >> 2) + (v & 3);
-                    if (m < g.M) C[(uint64_t)m * g.ldc + n] = out[v];
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni) {
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[mi], bh[ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[mi], bl[ni], acc[mi][ni], 0, 0, 0);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[mi], bh[ni], acc[mi][ni], 0, 0, 0);
                 }
-            }
         }
+    };
+    const uint32_t slabs = g.K / TK3;
+    if (AUX_AHEAD) {                                 // registers hold the weight tile: one slab ahead
+        Stage next;
+        fetch(0, next);
+        stash(0, next);
+        __syncthreads();
+        for (uint32_t s = 0; s < slabs; ++s) {
+            const int cur = s & 1;
+            if (s + 1 < slabs) fetch((s + 1) * TK3, next);
+            multiply(cur);
+            if (s + 1 < slabs) stash(cur ^ 1, next);
+            __syncthreads();
+        }
+    } else {
+        Stage even, odd;                             // slab s waits in `even` when s is even, else in `odd`
+        fetch(0, even);
+        if (slabs > 1) fetch(TK3, odd);
+        stash(0, even);
+        __syncthreads();
+        // iteration s: request slab s + 2 into the registers slab s has just left, multiply slab s, stage slab s + 1.
+        // In the steady state the conversion of slab s + 1 (vector ALU, its data arrived an iteration ago) is
+        // issued between the matrix instructions of slab s, which would otherwise run one after the other
+        // with the vector ALU idle, and then the other way round.
+        uint32_t s = 0;
+        for (; s + 3 < slabs; s += 2) {
+            fetch((s + 2) * TK3, even);
+            multiply(0);
+            stash(1, odd);
+            interleave_matrix_and_vector();
+            __syncthreads();
+            fetch((s + 3) * TK3, odd);
+            multiply(1);
+            stash(0, even);
+            interleave_matrix_and_vector();
+            __syncthreads();
+        }
+        for (; s < slabs; ++s) {                     // the last slabs: nothing left to request
+            const bool to_even = (s & 1u) != 0;      // slab s + 1 waits in `even` when s is odd
+            if (s + 2 < slabs) { if (to_even) fetch((s + 2) * TK3, odd); else fetch((s + 2) * TK3, even); }
+            multiply(s & 1);
+            if (s + 1 < slabs) { if (to_even) stash(0, even); else stash(1, odd); }
+            __syncthreads();
+        }
+    }
+    epilogue<EPI, !AUX_AHEAD>(g, C, aux, acc, m0, n0, wm, wn, half, r32, full_tile, pre);
 }
 
 // Labels by inverse CDF: y = #{c : cdf[c] <= u}, u = (word >> 8) 2^-24, limited to n_out - 1.
@@ -310,9 +573,13 @@ void free_mlp(MlpObjective &o) {
 }
 
 template <bool A_KC, bool B_KC, int EPI>
-static void gemm(const GemmArgs &g, uint32_t count, hipStream_t st) {
-    const dim3 grid((g.N + TN - 1) / TN, (g.M + TM - 1) / TM, count);
-    mlp_gemm_kernel<A_KC, B_KC, EPI><<<grid, 256, 0, st>>>(g);
+static void gemm(GemmArgs g, uint32_t count, bool split, hipStream_t st) {
+    g.tiles_n = (g.N + TN - 1) / TN;
+    g.tiles_m = (g.M + TM - 1) / TM;
+    g.groups = g.tiles_n * g.tiles_m * count;
+    const dim3 grid(8 * ((g.groups + 7) / 8), 1, 1);          // a whole number of turns over the dies
+    if (split) mlp_gemm3_kernel<A_KC, B_KC, EPI><<<grid, 256, 0, st>>>(g);
+    else mlp_gemm_kernel<A_KC, B_KC, EPI><<<grid, 256, 0, st>>>(g);
 }
 
 hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, const LocalSlots &slots,
@@ -336,14 +603,14 @@ hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, 
         g.C = o.hid; g.strideC = (uint64_t)Bt * Hd; g.c_by_node = 0; g.ldc = Hd;
         g.aux = src + off_b1; g.strideAux = d; g.aux_by_node = 1; g.ldaux = 0;
         g.M = Bt; g.N = Hd; g.K = I;
-        gemm<true, true, EPI_BIAS_RELU>(g, count, st);
+        gemm<true, true, EPI_BIAS_RELU>(g, count, o.bf16x3, st);
         // logits = hid W2^T + b2:  M = batch, N = out, K = hid
         g.A = o.hid; g.strideA = (uint64_t)Bt * Hd; g.lda = Hd;
         g.B = src + off_w2; g.ldb = Hd;
         g.C = o.dlogits; g.strideC = (uint64_t)Bt * O; g.ldc = O;
         g.aux = src + off_b2;
         g.M = Bt; g.N = O; g.K = Hd;
-        gemm<true, true, EPI_BIAS>(g, count, st);
+        gemm<true, true, EPI_BIAS>(g, count, o.bf16x3, st);
         mlp_softmax_grad_kernel<<<dim3(Bt, count), 256, 0, st>>>(o.dlogits, o.labels, O, Bt);
         // dpre = (dlogits W2) * [hid > 0]:  M = batch, N = hid, K = out;  W2 stored [k][n]
         g.A = o.dlogits; g.strideA = (uint64_t)Bt * O; g.lda = O;
@@ -351,14 +618,14 @@ hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, 
         g.C = o.dhid; g.strideC = (uint64_t)Bt * Hd; g.ldc = Hd;
         g.aux = o.hid; g.strideAux = (uint64_t)Bt * Hd; g.aux_by_node = 0; g.ldaux = Hd;
         g.M = Bt; g.N = Hd; g.K = O;
-        gemm<true, false, EPI_RELU_MASK>(g, count, st);
+        gemm<true, false, EPI_RELU_MASK>(g, count, o.bf16x3, st);
         // W2 <- W2 - eta dlogits^T hid:  M = out, N = hid, K = batch;  both operands stored [k][row]
         g.A = o.dlogits; g.strideA = (uint64_t)Bt * O; g.a_by_node = 0; g.lda = O;
         g.B = o.hid; g.strideB = (uint64_t)Bt * Hd; g.b_by_node = 0; g.ldb = Hd;
         g.C = W + off_w2; g.strideC = d; g.c_by_node = 1; g.ldc = Hd;
         g.aux = src + off_w2; g.strideAux = d; g.aux_by_node = 1; g.ldaux = Hd;
         g.M = O; g.N = Hd; g.K = Bt;
-        gemm<false, false, EPI_SGD_UPDATE>(g, count, st);
+        gemm<false, false, EPI_SGD_UPDATE>(g, count, o.bf16x3, st);
         mlp_bias_kernel<<<dim3((O + 255) / 256, count), 256, 0, st>>>(o.dlogits, src, W, nodes, O, Bt, d, off_b2, lr);
         // W1 <- W1 - eta dpre^T x:  M = hid, N = in, K = batch
         g.A = o.dhid; g.strideA = (uint64_t)Bt * Hd; g.lda = Hd;
@@ -366,7 +633,7 @@ hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, 
         g.C = W; g.ldc = I;
         g.aux = src; g.ldaux = I;
         g.M = Hd; g.N = I; g.K = Bt;
-        gemm<false, false, EPI_SGD_UPDATE>(g, count, st);
+        gemm<false, false, EPI_SGD_UPDATE>(g, count, o.bf16x3, st);
         mlp_bias_kernel<<<dim3((Hd + 255) / 256, count), 256, 0, st>>>(o.dhid, src, W, nodes, Hd, Bt, d, off_b1, lr);
     }
     return hipGetLastError();

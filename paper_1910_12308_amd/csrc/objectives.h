@@ -28,6 +28,7 @@ struct MlpObjective {
     float *x = nullptr, *hid = nullptr, *dlogits = nullptr, *dhid = nullptr;
     uint32_t *labels = nullptr;
     uint32_t n_nodes = 0;
+    bool bf16x3 = false;            // GEMMs as three bf16 products per term instead of float32 matrix instructions
 };
 
 // Whole round in one pass (local steps + quantized gossip) for the diagonal objective; bits in {2,4,8,16}.

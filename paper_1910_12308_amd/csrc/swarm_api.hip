@@ -453,6 +453,14 @@ swarm_status swarm_set_objective_mlp(swarm_t h, uint32_t n_in, uint32_t n_hid, u
     return SWARM_OK;
 }
 
+swarm_status swarm_set_mlp_arithmetic(swarm_t h, uint32_t arithmetic) {
+    if (!h) return SWARM_EINVAL;
+    if (h->kind != OBJ_MLP) return fail(h, SWARM_ESTATE, "the MLP objective is not set");
+    if (arithmetic > SWARM_MLP_BF16X3) return fail(h, SWARM_EINVAL, "unknown MLP arithmetic");
+    h->mlp.bf16x3 = arithmetic == SWARM_MLP_BF16X3;
+    return SWARM_OK;
+}
+
 swarm_status swarm_local_steps(swarm_t h, const uint32_t *nodes, uint32_t count) {
     if (!h) return SWARM_EINVAL;
     if (h->kind == OBJ_NONE) return fail(h, SWARM_ESTATE, "no objective set");

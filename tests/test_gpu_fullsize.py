@@ -101,7 +101,8 @@ def test_diag_configs_full_size_sampled_windows(gpu, cfg_id, eps, mode):
     assert np.isfinite(g.potential()) and g.potential() > 0
 
 
-def test_mlp_config_full_size_sampled_nodes(gpu):
+@pytest.mark.parametrize("arithmetic", ["float32", "three bf16 products"])
+def test_mlp_config_full_size_sampled_nodes(gpu, arithmetic):
     """n = 256 nodes, 1024-4096-1024 perceptron (d = 8.4 M), batch 128, H = 2, 8-bit codes: the oracle
     recomputes the local steps of two whole nodes and one matched pair of the gossip round."""
     cfg = wl.CONFIGS[3]
@@ -114,6 +115,8 @@ def test_mlp_config_full_size_sampled_nodes(gpu):
     g = gpu.Swarm(n, d, edges, bits, eps, H, lr, 0, seed)
     g.set_objective_mlp(cfg["n_in"], cfg["n_hid"], cfg["n_out"], torch.from_numpy(means).cuda(),
                         torch.from_numpy(cdf).cuda(), cfg["data_sigma"], cfg["batch"])
+    if arithmetic != "float32":
+        g.set_mlp_arithmetic(gpu.MLP_BF16X3)
     g.models_view(gpu.COMM).normal_(0.0, 0.02, generator=gen)
     torch.cuda.synchronize()
     pairs = g.sample_matching()

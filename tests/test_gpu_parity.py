@@ -403,8 +403,9 @@ def test_round_mode_free_running_matches_statistically(gpu, mode):
 
 
 # ------------------------------------------------------------------ MLP local steps (MFMA GEMMs)
+@pytest.mark.parametrize("arithmetic", ["float32", "three bf16 products"])
 @pytest.mark.parametrize("shape", [(64, 96, 32, 32), (256, 384, 128, 128)])
-def test_local_steps_mlp(gpu, shape):
+def test_local_steps_mlp(gpu, shape, arithmetic):
     """Two local steps of the two-layer perceptron on the Gaussian mixture: data generation,
     forward, softmax-CE gradient, backward GEMMs and fused SGD updates against the float64 oracle."""
     from oracle.objectives import MixtureMLP
@@ -416,6 +417,8 @@ def test_local_steps_mlp(gpu, shape):
     g, c = make_both(gpu, n, d, wl.complete_graph(n), 8, 2.0 ** -8, H, lr, 0, seed=21)
     c.objective = MixtureMLP(n_in, n_hid, n_out, means, cdf, 0.5, batch)
     g.set_objective_mlp(n_in, n_hid, n_out, torch.from_numpy(means).cuda(), torch.from_numpy(cdf).cuda(), 0.5, batch)
+    if arithmetic != "float32":
+        g.set_mlp_arithmetic(gpu.MLP_BF16X3)
     gen = np.random.Generator(np.random.PCG64(5))
     c.X[:] = models(gen, n, d, 0.1)
     force_state(gpu, g, c)
