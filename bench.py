@@ -302,7 +302,8 @@ def make_swarm(swarm, torch, cfg, edges, a, c, eps, args=None, stale_max=None):
         s = swarm.Swarm(n, d, edges, bits, eps, cfg["H"], cfg["lr"], S, seed=0,
                         apply_mode=swarm.INPLACE if args is not None and args.inplace else swarm.DEFERRED,
                         codec=swarm.CODEC_PREFIX if args is not None and args.prefix else swarm.CODEC_FIXED,
-                        scale_policy=swarm.SCALE_GLOBAL_LINF if args is not None and args.global_scale else swarm.SCALE_FIXED)
+                        scale_policy=(swarm.SCALE_GLOBAL_LINF if args is not None and args.global_scale else
+                                      swarm.SCALE_PAIR_LINF if args is not None and args.pair_scale else swarm.SCALE_FIXED))
         s.set_objective_diag(a, c, cfg["sigma"])
     return s
 
@@ -431,6 +432,9 @@ def main():
     ap.add_argument("--global-scale", action="store_true",
                     help="one lattice scale per round, set from the disagreement the previous round reported "
                          "(needs a configuration with at least 8-bit codes)")
+    ap.add_argument("--pair-scale", action="store_true",
+                    help="every matched pair uses its own lattice scale from a pre-pass over its two models "
+                         "(SWARM_SCALE_PAIR_LINF; fresh reads, two-call round only)")
     ap.add_argument("--mlp-bf16x3", action="store_true",
                     help="MLP objective: GEMMs as three bf16 products per term instead of float32 matrix instructions")
     ap.add_argument("--d", type=int, default=None, help="override the model dimension (debugging only)")
@@ -498,6 +502,7 @@ def main():
     # timed step unless --two-call is given.  The other variant is measured after the timed region and
     # reported beside it.
     one_pass_ok = cfg["objective"] == "diag"
+    one_pass_ok = one_pass_ok and not args.pair_scale       # the per-pair scale needs the pre-pass of the two-call round
     use_one_pass = one_pass_ok and not args.two_call
     main_m = measure(torch, s, step_one_pass if use_one_pass else step_two_calls, args.steps, args.warmup)
     other_m = None
@@ -546,6 +551,8 @@ def main():
                    "apply_mode": "inplace" if args.inplace else "deferred",
                    **({"scale": "per round (SWARM_SCALE_GLOBAL_LINF)", "eps_after_the_run": s.scale()[0]}
                       if args.global_scale else {}),
+                   **({"scale": "per pair (SWARM_SCALE_PAIR_LINF): pair_linf_kernel pre-pass, 8 B per pair-coordinate, "
+                                "inside the timed gossip bracket"} if args.pair_scale else {}),
                    "step": ("one-pass round (swarm_round_fused)" if use_one_pass
                             else "swarm_local_steps + swarm_gossip_round"),
                    "pairs_per_round": main_m["interactions"] / args.steps,
@@ -598,7 +605,8 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, edges, a, c, eps)
     # The other configurations, after the headline's timed region: compact records in the same line.
-    if args.config == 4 and not args.no_configs and not (args.inplace or args.prefix or args.global_scale or args.d or args.H):
+    if args.config == 4 and not args.no_configs and not (args.inplace or args.prefix or args.global_scale or args.pair_scale
+                                                         or args.d or args.H):
         configs = {}
         # Algorithm 1 at the headline's shape (fresh reads; the sequential model has no stale partner copies)
         seq = make_swarm(swarm, torch, cfg, edges, a, c, eps, stale_max=0)

@@ -119,20 +119,25 @@ __device__ __forceinline__ f4 averaged_mixed(const int z_own[4], uint64_t partne
     return f4{o[0], o[1], o[2], o[3]};
 }
 
-// Largest disagreement of the wave into the stripe of its workgroup (float bits order like the floats:
-// all >= 0).  Row maxima through DPP, the four rows through lane reads; the plain load only filters.
+// Maximum of a non-negative float over the wave, as its bit pattern (non-negative floats order like their
+// bits): row maxima through DPP, the four rows through lane reads.  The same scalar in every lane.
+__device__ __forceinline__ uint32_t wave_max_bits(float v) {
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true)));
+    const uint32_t b = __float_as_uint(v);
+    return max(max((uint32_t)__builtin_amdgcn_readlane((int)b, 0), (uint32_t)__builtin_amdgcn_readlane((int)b, 16)),
+               max((uint32_t)__builtin_amdgcn_readlane((int)b, 32), (uint32_t)__builtin_amdgcn_readlane((int)b, 48)));
+}
+// One lane raises *word to the wave's maximum if it is larger; the plain load only filters.
+__device__ __forceinline__ void raise_to(uint32_t *word, uint32_t bits) {
+    if ((threadIdx.x & 63) == 0 && bits > __atomic_load_n(word, __ATOMIC_RELAXED)) atomicMax(word, bits);
+}
+
+// Largest disagreement of the wave into the stripe of its workgroup.
 __device__ __forceinline__ void report_far(uint32_t *far_bits, float far) {
-    far = fmaxf(far, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, far), 0xB1, 0xF, 0xF, true)));
-    far = fmaxf(far, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, far), 0x4E, 0xF, 0xF, true)));
-    far = fmaxf(far, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, far), 0x141, 0xF, 0xF, true)));
-    far = fmaxf(far, __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, far), 0x140, 0xF, 0xF, true)));
-    const uint32_t v = __float_as_uint(far);
-    const uint32_t b = max(max((uint32_t)__builtin_amdgcn_readlane((int)v, 0), (uint32_t)__builtin_amdgcn_readlane((int)v, 16)),
-                           max((uint32_t)__builtin_amdgcn_readlane((int)v, 32), (uint32_t)__builtin_amdgcn_readlane((int)v, 48)));
-    if ((threadIdx.x & 63) == 0) {
-        uint32_t *stripe = far_bits + ((blockIdx.x + 977u * blockIdx.y) & (FAR_STRIPES - 1));
-        if (b > __atomic_load_n(stripe, __ATOMIC_RELAXED)) atomicMax(stripe, b);
-    }
+    raise_to(far_bits + ((blockIdx.x + 977u * blockIdx.y) & (FAR_STRIPES - 1)), wave_max_bits(far));
 }
 
 // Scales of one read under the per-round policy (eps_slots not null), else the fixed ones.

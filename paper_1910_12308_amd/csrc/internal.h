@@ -44,8 +44,8 @@ struct GossipArgs {
     uint8_t *ring;            // (S+1) x n x row_bytes packed codes
     const PairDesc *pairs;    // device: one per matched pair
     const uint32_t *singles;  // device: unmatched nodes (node id | SINGLE_PENDING)
-    const uint32_t *pair_linf; // device: bits of max_k |X_i - X_j| per pair (same order as pairs), or
-                              // null when the lattice scale is fixed
+    const uint32_t *pair_linf; // device: PAIR_STRIPES words per pair (same order as pairs) whose maximum is the bit
+                              // pattern of max_k |X_i - X_j|, or null when the lattice scale is fixed
     const float *eps_slots;   // device: lattice scale of the codes in each ring slot (one scale per round), or
                               // null when the scale is fixed or per pair
     uint32_t *far_bits;       // device: FAR_STRIPES words, each the float bits of the largest |key - decoded
@@ -121,13 +121,15 @@ constexpr uint32_t FAR_STRIPES = 256;
 hipError_t launch_scale_close(float *eps_slots, uint32_t *state, uint32_t slot_now, uint32_t ring_depth,
                               uint32_t bits, uint32_t npairs, hipStream_t st);
 
-// Reductions.
+// Reductions.  The per-pair distance is the maximum of PAIR_STRIPES words: the workgroups of a pair spread
+// their atomic maxima over them (thousands of atomics on one word queue up at its memory channel).
+constexpr uint32_t PAIR_STRIPES = 64;
 hipError_t launch_potential(const float *X, uint32_t n, uint64_t d, float *mu, double *partials,
                             uint32_t npartials, double *gamma_out, hipStream_t st);
 uint32_t potential_partials(uint64_t d);
 hipError_t launch_pair_linf(const float *X, uint64_t d, const uint32_t *pairs, uint32_t npairs,
                             uint32_t *linf_bits, hipStream_t st);
-// Same reduction over pair descriptors; linf_bits must be zero on entry.
+// Same reduction over pair descriptors.  For both: linf_bits holds npairs x PAIR_STRIPES words, zero on entry.
 hipError_t launch_pair_linf_desc(const float *X, uint64_t d, const PairDesc *pairs, uint32_t npairs,
                                  uint32_t *linf_bits, hipStream_t st);
 

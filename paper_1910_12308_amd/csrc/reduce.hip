@@ -6,13 +6,11 @@
 // order, so the result does not depend on scheduling.
 #include <mutex>
 
-#include "internal.h"
-#include "quant.hpp"
+#include "gossip_common.hpp"
 #include "swarm.h"
 
 namespace swarm {
 
-typedef float f4 __attribute__((ext_vector_type(4)));
 constexpr int RB = 256;
 
 __device__ __forceinline__ double block_sum(double v, double *lds) {
@@ -64,27 +62,40 @@ __global__ __launch_bounds__(RB) void sum_partials_kernel(const double *__restri
     if (threadIdx.x == 0) *out = s;
 }
 
-// Non-negative floats order like their bit patterns, so atomicMax on the bits is exact
-// and order-independent.
+// Distance of the two models of a pair in the maximum norm: the same wave tiles and 128-bit non-temporal
+// loads as the gossip pass that follows (8 bytes per pair-coordinate, nothing written but one word per
+// pair).  Non-negative floats order like their bit patterns, so atomicMax on the bits is exact and
+// order-independent; the waves of a workgroup meet in LDS and one lane issues at most one atomic (thousands
+// of waves hitting the same word directly spend more time queueing at its memory channel than reading).
 template <bool DESC>
-__global__ __launch_bounds__(RB) void pair_linf_kernel(const float *__restrict__ X, uint64_t d,
-                                                       const uint32_t *__restrict__ pairs,
-                                                       uint32_t *__restrict__ linf_bits) {
-    __shared__ float lds[RB / 64];
+__global__ __launch_bounds__(WAVES * 64) void pair_linf_kernel(const float *__restrict__ X, uint64_t d,
+                                                               const uint32_t *__restrict__ pairs,
+                                                               uint32_t *__restrict__ linf_bits) {
+    __shared__ uint32_t wave_max[WAVES];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint64_t tile = wave_tile(WAVES);
+    uint32_t bits = 0u;
+    if (tile * TILE < d) {
     // DESC: pairs are 16-byte descriptors (node ids in the first two words), else packed id pairs
     const uint32_t ni = pairs[(DESC ? 4 : 2) * blockIdx.y], nj = pairs[(DESC ? 4 : 2) * blockIdx.y + 1];
-    const uint64_t f = (uint64_t)blockIdx.x * RB + threadIdx.x;
-    float m = 0.f;
-    if (f * 4 < d) {
-        const f4 a = *(const f4 *)(X + (uint64_t)ni * d + f * 4), b = *(const f4 *)(X + (uint64_t)nj * d + f * 4);
-        m = fmaxf(fmaxf(fabsf(a.x - b.x), fabsf(a.y - b.y)), fmaxf(fabsf(a.z - b.z), fabsf(a.w - b.w)));
+    const uint64_t base = tile * TILE;
+    const uint32_t cA = 4u * lane, cB = cA + TILE / 2;
+    const bool inA = base + cA < d, inB = base + cB < d;
+    const uint32_t last = (uint32_t)min((uint64_t)(TILE - 4), d - 4 - base);      // past the row end: its last float4 again
+    const uint32_t oA = inA ? cA : last, oB = inB ? cB : last;
+    const float *xi = X + (uint64_t)ni * d + base, *xj = X + (uint64_t)nj * d + base;
+    const f4 a0 = ldg_nt(xi + oA), b0 = ldg_nt(xj + oA), a1 = ldg_nt(xi + oB), b1 = ldg_nt(xj + oB);
+    const f4 e0 = a0 - b0, e1 = a1 - b1;
+    const float m = fmaxf(fmaxf(fmaxf(fabsf(e0.x), fabsf(e0.y)), fmaxf(fabsf(e0.z), fabsf(e0.w))),
+                          fmaxf(fmaxf(fabsf(e1.x), fabsf(e1.y)), fmaxf(fabsf(e1.z), fabsf(e1.w))));
+    bits = wave_max_bits(m);
     }
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = m;
+    if (lane == 0) wave_max[wave] = bits;
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int w = 1; w < RB / 64; ++w) m = fmaxf(m, lds[w]);
-        atomicMax(linf_bits + blockIdx.y, __float_as_uint(m));
+#pragma unroll
+        for (int w = 1; w < WAVES; ++w) bits = max(bits, wave_max[w]);
+        raise_to(linf_bits + blockIdx.y * PAIR_STRIPES + (blockIdx.x & (PAIR_STRIPES - 1)), bits);
     }
 }
 
@@ -100,16 +111,18 @@ hipError_t launch_potential(const float *X, uint32_t n, uint64_t d, float *mu, d
 hipError_t launch_pair_linf(const float *X, uint64_t d, const uint32_t *pairs, uint32_t npairs,
                             uint32_t *linf_bits, hipStream_t st) {
     if (npairs == 0) return hipSuccess;
-    const dim3 grid((unsigned)((d / 4 + RB - 1) / RB), npairs, 1);
-    pair_linf_kernel<false><<<grid, RB, 0, st>>>(X, d, pairs, linf_bits);
+    const uint64_t tiles = (d + TILE - 1) / TILE;
+    const dim3 grid((unsigned)((tiles + WAVES - 1) / WAVES), npairs, 1);
+    pair_linf_kernel<false><<<grid, WAVES * 64, 0, st>>>(X, d, pairs, linf_bits);
     return hipGetLastError();
 }
 
 hipError_t launch_pair_linf_desc(const float *X, uint64_t d, const PairDesc *pairs, uint32_t npairs,
                                  uint32_t *linf_bits, hipStream_t st) {
     if (npairs == 0) return hipSuccess;
-    const dim3 grid((unsigned)((d / 4 + RB - 1) / RB), npairs, 1);
-    pair_linf_kernel<true><<<grid, RB, 0, st>>>(X, d, (const uint32_t *)pairs, linf_bits);
+    const uint64_t tiles = (d + TILE - 1) / TILE;
+    const dim3 grid((unsigned)((tiles + WAVES - 1) / WAVES), npairs, 1);
+    pair_linf_kernel<true><<<grid, WAVES * 64, 0, st>>>(X, d, (const uint32_t *)pairs, linf_bits);
     return hipGetLastError();
 }
 

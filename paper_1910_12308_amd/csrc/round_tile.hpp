@@ -275,7 +275,11 @@ __device__ __forceinline__ void round_pairs_body(const RoundArgs &ra) {
     const PairDesc pd = ra.g.pairs[blockIdx.y];                    // uniform: one scalar load
     float eps = ra.g.eps, inv_eps = ra.g.inv_eps;
     if (ra.g.pair_linf) {                                          // the pair's own scale from its distance
-        eps = pair_scale(__uint_as_float(ra.g.pair_linf[blockIdx.y]), BITS);
+        const uint32_t *stripes = ra.g.pair_linf + blockIdx.y * PAIR_STRIPES;      // uniform: scalar loads
+        uint32_t bits = 0u;
+#pragma unroll
+        for (uint32_t k = 0; k < PAIR_STRIPES; ++k) bits = max(bits, stripes[k]);
+        eps = pair_scale(__uint_as_float(bits), BITS);
         inv_eps = 1.0f / eps;
     }
     if (tile * TILE + TILE <= ra.g.d) round_pair_tile<BITS, SRC, STALE, INPLACE, true>(ra, pd, tile, lane, eps, inv_eps);

@@ -328,7 +328,7 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         SWARM_HIP(h, hipMalloc((void **)&h->prio_dev, sizeof(uint32_t) * cfg->n_edges));
         SWARM_HIP(h, hipMalloc((void **)&h->counts_dev, sizeof(uint32_t) * 2));
         SWARM_HIP(h, hipMalloc((void **)&h->nodes_dev, sizeof(uint32_t) * n));
-        SWARM_HIP(h, hipMalloc((void **)&h->linf_dev, sizeof(uint32_t) * (n / 2)));
+        SWARM_HIP(h, hipMalloc((void **)&h->linf_dev, sizeof(uint32_t) * PAIR_STRIPES * (n / 2)));
         SWARM_HIP(h, hipMalloc((void **)&h->steps_dev, sizeof(uint32_t) * n));
         if (cfg->codec == SWARM_CODEC_PREFIX) {
             SWARM_HIP(h, hipMalloc((void **)&h->prefix_stats_dev, sizeof(PrefixStats) * PREFIX_STRIPES));
@@ -677,7 +677,7 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
         SWARM_HIP(h, launch_prefix(a, local, inplace, c.lr, 2, nsingles, h->stream));
     } else {
         if (pair_scale_policy && npairs) {   // distance of every pair first, then each pair quantizes at its own scale
-            SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * npairs, h->stream));
+            SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * PAIR_STRIPES * npairs, h->stream));
             SWARM_HIP(h, launch_pair_linf_desc(h->X, c.d, a.pairs, npairs, h->linf_dev, h->stream));
         }
         {
@@ -690,7 +690,7 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
                 else
                     SWARM_HIP(h, launch_gossip_pairs(ga, c.bits, delta_mode, group_mode[gidx], count, h->stream));
                 ga.pairs += count;
-                if (ga.pair_linf) ga.pair_linf += count;
+                if (ga.pair_linf) ga.pair_linf += (size_t)count * PAIR_STRIPES;
             }
         }
         SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 1));
@@ -1131,10 +1131,15 @@ swarm_status swarm_pair_linf(swarm_t h, const uint32_t *pairs_host, uint32_t npa
     for (uint32_t k = 0; k < 2 * npairs; ++k)
         if (pairs_host[k] >= h->cfg.n) return fail(h, SWARM_EINVAL, "pair endpoint out of range");
     SWARM_TRY(upload_nodes(h, pairs_host, 2 * npairs));
-    SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * npairs, h->stream));
+    SWARM_HIP(h, hipMemsetAsync(h->linf_dev, 0, sizeof(uint32_t) * PAIR_STRIPES * npairs, h->stream));
     SWARM_HIP(h, launch_pair_linf(h->X, h->cfg.d, h->nodes_dev, npairs, h->linf_dev, h->stream));
-    SWARM_HIP(h, hipMemcpyAsync(linf_host, h->linf_dev, sizeof(uint32_t) * npairs, hipMemcpyDeviceToHost, h->stream));
+    std::vector<uint32_t> stripes((size_t)npairs * PAIR_STRIPES);
+    SWARM_HIP(h, hipMemcpyAsync(stripes.data(), h->linf_dev, sizeof(uint32_t) * stripes.size(), hipMemcpyDeviceToHost, h->stream));
     SWARM_HIP(h, hipStreamSynchronize(h->stream));
+    for (uint32_t p = 0; p < npairs; ++p) {          // non-negative floats order like their bit patterns
+        const uint32_t bits = *std::max_element(stripes.begin() + (size_t)p * PAIR_STRIPES, stripes.begin() + (size_t)(p + 1) * PAIR_STRIPES);
+        std::memcpy(linf_host + p, &bits, sizeof(float));
+    }
     return SWARM_OK;
 }
 
