@@ -20,9 +20,10 @@ __device__ __forceinline__ float lattice_coord(float x, float inv_eps, bool &cla
 }
 
 // z = floor(t) + [r16 + 1/2 < frac(t) 2^16]: P(up) is within 2^-17 of frac(t).
-// The comparison is taken as r16 < frac(t) 2^16 - 1/2: both sides are exact in float32 (frac has at most 24
-// significant bits below 1, the scaling is a power of two and 1/2 is a multiple of the spacing up to 2^16), so
-// the decision is the same.  frac(t) = t - floor(t) is exact except for tiny negative t, where the
+// The comparison is taken as r16 < frac(t) 2^16 - 1/2 with one fused multiply-add, whose rounding cannot
+// change the decision: the scaling is a power of two; for frac(t) 2^16 >= 1/2 the difference keeps the
+// operand's last bit at a smaller magnitude, so it is exact; below 1/2 it is negative however it rounds,
+// and no r16 is below it.  frac(t) = t - floor(t) is exact except for tiny negative t, where the
 // subtraction rounds to 1 and the hardware fraction stays one step below: either way every r16 rounds up.
 __device__ __forceinline__ int stochastic_round(float x, float inv_eps, uint32_t r16, bool &clamped) {
     const float t = lattice_coord(x, inv_eps, clamped);
