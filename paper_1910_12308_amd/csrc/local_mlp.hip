@@ -258,9 +258,9 @@ typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
 constexpr int TK3 = 32;                             // K slab of the bf16 kernels: whole 128-byte lines per operand row
 constexpr int OCTS = TK3 / 8;                       // octets of k per slab
-constexpr int OCT_ROWS = TM + 8;                    // rows per octet plane: successive octets half the banks apart, so the
-                                                    // 8-byte staging writes of a wave (8 rows x 4 octets x 2 halves) hit
-                                                    // every bank exactly twice
+constexpr int OCT_ROWS = TM + 4;                    // rows per octet plane: successive octets a quarter of the banks
+                                                    // apart, so the 8-byte staging writes of half a wave (4 rows x 4
+                                                    // octets x 2 halves) cover all 64 banks once
 constexpr int SLAB_WORDS = OCTS * OCT_ROWS;         // 16-byte words of one operand slab (hi or lo)
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
