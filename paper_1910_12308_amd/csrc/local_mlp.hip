@@ -16,6 +16,7 @@
 // 0-31 carry one k index and lanes 32-63 another, and any pairing is valid as long as A and
 // B agree, so lanes 0-31 take k 0..7 of the slab and lanes 32-63 take k 8..15: operands
 // whose k runs contiguously in memory are fetched from LDS with two 128-bit reads.
+#include <type_traits>
 #include "internal.h"
 #include "objectives.h"
 #include "philox.hpp"
@@ -40,6 +41,11 @@ struct GemmArgs {
     uint32_t a_by_node, b_by_node, c_by_node, aux_by_node;
     uint32_t M, N, K, lda, ldb, ldc, ldaux;
     float lr;
+    // EPI_RELU_MASK only, and only when one tile covers all rows (M <= 128): dst = src - lr * column sums of C, per node
+    // (the bias gradient of the hidden layer is the column sum of the matrix this GEMM produces); null = not wanted
+    const float *colsum_src;
+    float *colsum_dst;
+    uint64_t strideColsum;
     uint32_t tiles_n, tiles_m, groups;   // workgroups of the launch: tiles_n x tiles_m per slot, total = their product x slots
 };
 
@@ -47,24 +53,55 @@ struct GemmArgs {
 // dies (XCDs), each with its own L2; the tiles of one node share that node's activations (and nothing
 // with other nodes), so the ids are renumbered to put all tiles of a node on one die, one after the
 // other: die x takes the x-th eighth of the (node, tile) list.  Ids past the end of the list do nothing.
-struct TileId { uint32_t slot, tile_m, tile_n; bool valid; };
-__device__ __forceinline__ TileId tile_of_workgroup(const GemmArgs &g) {
+struct Tile { const float *A, *B, *aux, *colsum_src; float *C, *colsum_dst; uint32_t m0, n0; bool valid; };
+__device__ __forceinline__ Tile tile_of_id(const GemmArgs &g, uint32_t id) {
     constexpr uint32_t DIES = 8;
     const uint32_t chunk = (g.groups + DIES - 1) / DIES;
-    const uint32_t q = (blockIdx.x % DIES) * chunk + blockIdx.x / DIES;
+    const uint32_t q = (id % DIES) * chunk + id / DIES;
+    Tile t{};
+    t.valid = id / DIES < chunk && q < g.groups;
+    if (!t.valid) return t;
     const uint32_t per_slot = g.tiles_n * g.tiles_m, r = q % per_slot;
-    return TileId{q / per_slot, r / g.tiles_n, r % g.tiles_n, q < g.groups};
+    const uint32_t slot = q / per_slot, node = g.nodes ? g.nodes[slot] : slot;
+    t.A = g.A + (g.a_by_node ? node : slot) * g.strideA;
+    t.B = g.B + (g.b_by_node ? node : slot) * g.strideB;
+    t.C = g.C + (g.c_by_node ? node : slot) * g.strideC;
+    t.aux = g.aux + (g.aux_by_node ? node : slot) * g.strideAux;
+    t.colsum_src = g.colsum_dst ? g.colsum_src + node * g.strideColsum : nullptr;
+    t.colsum_dst = g.colsum_dst ? g.colsum_dst + node * g.strideColsum : nullptr;
+    t.m0 = (r / g.tiles_n) * TM;
+    t.n0 = (r % g.tiles_n) * TN;
+    return t;
+}
+
+// Global accesses are written as a uniform address plus the lane's 32-bit byte offset (plus a small
+// constant), the form the load and store instructions take directly (scalar base, vector offset).  The
+// marker keeps the uniform part in scalar registers: without it the compiler adds the lane's offset to
+// the base once and then carries 64-bit per-lane addresses, two vector registers and two vector adds
+// per access, and the registers it recycles for them make loads wait for one another.
+#define SWARM_GLOBAL __attribute__((address_space(1)))      // device memory, as opposed to a generic address
+template <typename T>
+__device__ __forceinline__ SWARM_GLOBAL T *uniform(T *p) {
+    SWARM_GLOBAL T *q = (SWARM_GLOBAL T *)p;
+    asm volatile("" : "+s"(q));
+    return q;
+}
+template <typename T>
+__device__ __forceinline__ SWARM_GLOBAL T *at_bytes(SWARM_GLOBAL T *p, uint32_t bytes) {
+    typedef typename std::conditional<std::is_const<T>::value, const char, char>::type Byte;
+    return (SWARM_GLOBAL T *)((SWARM_GLOBAL Byte *)p + bytes);
 }
 
 // Load a 128 x 16 slab of an operand whose k index is contiguous in memory: P[row * ld + k].
 __device__ __forceinline__ void fetch_kc(const float *P, uint32_t ld, uint32_t row0, uint32_t rows, uint32_t k0,
                                          f4 r[2]) {
     const uint32_t t = threadIdx.x;
+    SWARM_GLOBAL const float *base = (SWARM_GLOBAL const float *)(P + k0);   // measured: no gain from the marker here
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         // rows past the matrix edge re-read its last row: they only feed outputs that are never stored
         const uint32_t row = min(row0 + (t >> 2) + 64 * i, rows - 1);
-        r[i] = *(const f4 *)(P + (uint64_t)row * ld + k0 + 4 * (t & 3));
+        r[i] = *(SWARM_GLOBAL const f4 *)at_bytes(base, 4 * (row * ld + 4 * (t & 3)));
     }
 }
 __device__ __forceinline__ void stash_kc(float *lds, const f4 r[2]) {
@@ -73,13 +110,15 @@ __device__ __forceinline__ void stash_kc(float *lds, const f4 r[2]) {
     for (int i = 0; i < 2; ++i) *(f4 *)(lds + ((t >> 2) + 64 * i) * LDK + 4 * (t & 3)) = r[i];
 }
 // Load a 16 x 128 slab of an operand whose row (m or n) index is contiguous: P[k * ld + row].
+// A thread's k is k0 + (t >> 5) + 8 i = k0 + 2 wave + 8 i (uniform) + the lane's half.
 __device__ __forceinline__ void fetch_rc(const float *P, uint32_t ld, uint32_t row0, uint32_t rows, uint32_t k0,
-                                         f4 r[2]) {
-    const uint32_t t = threadIdx.x;
+                                         uint32_t wave, f4 r[2]) {
+    const uint32_t t = threadIdx.x, row = min(row0 + 4 * (t & 31), rows - 4);
+    const uint32_t lane_bytes = 4 * (((t >> 5) & 1u) * ld + row);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const uint32_t k = k0 + (t >> 5) + 8 * i, row = min(row0 + 4 * (t & 31), rows - 4);
-        r[i] = *(const f4 *)(P + (uint64_t)k * ld + row);
+        SWARM_GLOBAL const float *base = uniform(P + (uint64_t)(k0 + 2 * wave + 8 * i) * ld);
+        r[i] = *(SWARM_GLOBAL const f4 *)at_bytes(base, lane_bytes);
     }
 }
 __device__ __forceinline__ void stash_rc(float *lds, const f4 r[2]) {
@@ -101,46 +140,74 @@ __device__ __forceinline__ void operand(const float *lds, uint32_t row, uint32_t
 }
 
 // Epilogues that need a tile of another matrix (the weights to update, the ReLU mask source) request it
-// before the K loop, so that its HBM latency hides behind the MFMAs instead of serialising compute phase
-// and memory phase.  Tiles that lie wholly inside the matrix (all of them when M and N are multiples of
-// 128) take straight-line loads and stores; the guarded path serves ragged edges.
-template <int EPI>
-__device__ __forceinline__ void prefetch_aux(const GemmArgs &g, const float *aux, uint32_t m0, uint32_t n0, uint32_t wm,
-                                             uint32_t wn, uint32_t half, uint32_t r32, bool full_tile, float pre[2][2][16]) {
-    if (!(EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE)) return;
+// during the K loop, so that its HBM latency hides behind the MFMAs instead of serialising compute phase
+// and memory phase.  The 64 values a lane needs are requested in PARTS equal parts, part c after the
+// operand fetch of iteration c: loads return in order, so a request for the whole tile ahead of the loop
+// would hold back every operand slab behind it until the tile has arrived (and leave memory idle for
+// the rest of the loop).  Tiles that lie wholly inside the matrix (all of them when M and N are
+// multiples of 128) take straight-line loads and stores; the guarded path serves ragged edges.
+struct AuxPos { const float *aux; uint32_t m0, n0, wm, wn, half, r32; bool full_tile; };
+constexpr int AUX_PARTS = 8;     // part c = 4 mi + (v / 4): four consecutive rows, both column blocks
+
+// Row group `part` (0..7) of the lane's values into the registers of row group DEST.  The caller passes
+// part == DEST; the addresses are computed from the run-time value, so that they are formed when the
+// part is requested (one uniform base, the lane's 32-bit offset, small constants) and not, for all
+// 64 values, ahead of the loop that spreads the requests.
+template <int EPI, int DEST>
+__device__ __forceinline__ void prefetch_aux_rows(const GemmArgs &g, const AuxPos p, uint32_t part, float pre[2][2][16]) {
+    constexpr int mi = DEST >> 2, vq = DEST & 3;
+    const uint32_t row0 = p.m0 + p.wm + 32 * (part >> 2) + 8 * (part & 3u);            // uniform
+    if (p.full_tile) {
+        const uint32_t lane_bytes = 4 * (4 * p.half * g.ldaux + p.r32);
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+        for (int j = 0; j < 4; ++j) {
+            SWARM_GLOBAL const float *row = uniform(p.aux + (uint64_t)(row0 + j) * g.ldaux + p.n0 + p.wn);
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) {
-            const uint32_t n = n0 + wn + 32 * ni + r32;
-            const uint32_t mb = m0 + wm + 32 * mi + 4 * half;
-            if (full_tile) {      // uniform base per value (wm, wn are scalars) plus the lane's own 32-bit offset
-                const uint32_t lane_off = 4 * half * g.ldaux + r32;
-                const float *base = aux + (uint64_t)(m0 + wm + 32 * mi) * g.ldaux + n0 + wn + 32 * ni;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float *src = base + (uint64_t)(8 * (v >> 2) + (v & 3)) * g.ldaux + lane_off;
-                    // weights about to be replaced are touched once: keep them out of the way of the cached activations
-                    pre[mi][ni][v] = EPI == EPI_SGD_UPDATE ? __builtin_nontemporal_load(src) : *src;
-                }
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const uint32_t m = mb + 8 * (v >> 2) + (v & 3);
-                    pre[mi][ni][v] = (n < g.N && m < g.M) ? aux[(uint64_t)m * g.ldaux + n] : 0.f;
-                }
+            for (int ni = 0; ni < 2; ++ni) {
+                SWARM_GLOBAL const float *src = at_bytes(row + 32 * ni, lane_bytes);
+                // weights about to be replaced are touched once: keep them out of the way of the cached activations
+                pre[mi][ni][4 * vq + j] = EPI == EPI_SGD_UPDATE ? __builtin_nontemporal_load(src) : *src;
             }
         }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const uint32_t n = p.n0 + p.wn + 32 * ni + p.r32, m = row0 + 4 * p.half + j;
+                pre[mi][ni][4 * vq + j] = (n < g.N && m < g.M) ? p.aux[(uint64_t)m * g.ldaux + n] : 0.f;
+            }
+    }
+}
+// The K loops below are unrolled over the parts, so that each part's registers are fixed; the run-time
+// copy of the part number keeps the address arithmetic inside the iteration that uses it.
+__device__ __forceinline__ uint32_t at_run_time(uint32_t part) {
+    asm volatile("" : "+s"(part));
+    return part;
+}
+template <int PART> struct Part { static constexpr int value = PART; };
+// Parts [FIRST, AUX_PARTS) for first <= FIRST: what a K loop of `first` iterations has not requested.
+template <int EPI, int FIRST = 0>
+__device__ __forceinline__ void prefetch_aux_rest(const GemmArgs &g, const AuxPos p, uint32_t first, float pre[2][2][16]) {
+    if (!(EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE)) return;
+    if constexpr (FIRST < AUX_PARTS) {
+        if (first <= FIRST) prefetch_aux_rows<EPI, FIRST>(g, p, at_run_time(FIRST), pre);
+        prefetch_aux_rest<EPI, FIRST + 1>(g, p, first, pre);
+    }
 }
 
 // Accumulator layout of a 32x32 block (every 32x32 MFMA shape): register v of lane l holds row
 // 8*(v/4) + 4*(l/32) + v%4, column l%32.
 // LATE: the tile of the other matrix was not requested ahead of the K loop and is read here.
+// scratch: 128 floats of LDS that nothing else uses any more (column sums, when the tile asks for them).
 template <int EPI, bool LATE = false>
-__device__ __forceinline__ void epilogue(const GemmArgs &g, float *C, const float *aux, f16v acc[2][2], uint32_t m0,
-                                         uint32_t n0, uint32_t wm, uint32_t wn, uint32_t half, uint32_t r32, bool full_tile,
-                                         float pre[2][2][16]) {
-    if (LATE) prefetch_aux<EPI>(g, aux, m0, n0, wm, wn, half, r32, full_tile, pre);
+__device__ __forceinline__ void epilogue(const GemmArgs &g, const Tile &t, f16v acc[2][2], uint32_t wm, uint32_t wn,
+                                         uint32_t half, uint32_t r32, bool full_tile, float pre[2][2][16], float *scratch) {
+    float *C = t.C;
+    const float *aux = t.aux;
+    const uint32_t m0 = t.m0, n0 = t.n0;
+    if (LATE) prefetch_aux_rest<EPI>(g, AuxPos{aux, m0, n0, wm, wn, half, r32, full_tile}, 0, pre);
+    float colsum[2] = {0.f, 0.f};
 #pragma unroll
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -158,13 +225,15 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, float *C, const floa
                 if (EPI == EPI_RELU_MASK) c = pre[mi][ni][v] > 0.f ? c : 0.f;
                 if (EPI == EPI_SGD_UPDATE) c = fmaf(-g.lr, c, pre[mi][ni][v]);
                 out[v] = c;
+                if (EPI == EPI_RELU_MASK && (full_tile || mb + 8 * (v >> 2) + (v & 3) < g.M)) colsum[ni] += c;
             }
             if (full_tile) {
-                const uint32_t lane_off = 4 * half * g.ldc + r32;
-                float *base = C + (uint64_t)(m0 + wm + 32 * mi) * g.ldc + n0 + wn + 32 * ni;
+                const uint32_t lane_bytes = 4 * (4 * half * g.ldc + r32);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float *dst = base + (uint64_t)(8 * (v >> 2) + (v & 3)) * g.ldc + lane_off;
+                    SWARM_GLOBAL float *row =
+                        uniform(C + (uint64_t)(m0 + wm + 32 * mi + 8 * (v >> 2) + (v & 3)) * g.ldc + n0 + wn + 32 * ni);
+                    SWARM_GLOBAL float *dst = at_bytes(row, lane_bytes);
                     if (EPI == EPI_SGD_UPDATE) __builtin_nontemporal_store(out[v], dst); else *dst = out[v];
                 }
             } else if (n < g.N) {
@@ -175,70 +244,102 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, float *C, const floa
                 }
             }
         }
+    if (EPI == EPI_RELU_MASK && t.colsum_dst) {          // uniform: every wave of the workgroup takes this path
+        // a column's 128 rows sit in the two halves of a wave and in the two waves with the same wn
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) colsum[ni] += __shfl_xor(colsum[ni], 32);
+        if (wm != 0 && half == 0) {
+            scratch[wn + r32] = colsum[0];
+            scratch[wn + 32 + r32] = colsum[1];
+        }
+        __syncthreads();
+        if (wm == 0 && half == 0) {
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) {
+                const uint32_t n = n0 + wn + 32 * ni + r32;
+                if (n < g.N) t.colsum_dst[n] = fmaf(-g.lr, colsum[ni] + scratch[wn + 32 * ni + r32], t.colsum_src[n]);
+            }
+        }
+    }
 }
 
 // C (M x N) = op(A) op(B) with A_KC: A stored [m][k] else [k][m]; B_KC: B stored [n][k] else [k][n].
 template <bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(256) void mlp_gemm_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(const GemmArgs g) {
     constexpr int A_TILE = A_KC ? TM * LDK : TK * LDR, B_TILE = B_KC ? TN * LDK : TK * LDR;
     __shared__ __attribute__((aligned(16))) float lds_a[2][A_TILE];
     __shared__ __attribute__((aligned(16))) float lds_b[2][B_TILE];
-    const TileId id = tile_of_workgroup(g);
-    if (!id.valid) return;
-    const uint32_t slot = id.slot, node = g.nodes ? g.nodes[slot] : slot;
-    const float *A = g.A + (g.a_by_node ? node : slot) * g.strideA;
-    const float *B = g.B + (g.b_by_node ? node : slot) * g.strideB;
-    float *C = g.C + (g.c_by_node ? node : slot) * g.strideC;
-    const float *aux = g.aux + (g.aux_by_node ? node : slot) * g.strideAux;
-    const uint32_t m0 = id.tile_m * TM, n0 = id.tile_n * TN;
     const uint32_t lane = threadIdx.x & 63u, half = lane >> 5, r32 = lane & 31u;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // scalar: bases stay uniform
     const uint32_t wm = (wave >> 1) * 64, wn = (wave & 1u) * 64;
-
-    f16v acc[2][2];
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-    const bool full_tile = m0 + TM <= g.M && n0 + TN <= g.N;
-    float pre[2][2][16];
-    prefetch_aux<EPI>(g, aux, m0, n0, wm, wn, half, r32, full_tile, pre);
+    const uint32_t slabs = g.K / TK;
 
     f4 ra[2], rb[2];
-    auto fetch = [&](uint32_t k0) {
-        if (A_KC) fetch_kc(A, g.lda, m0, g.M, k0, ra); else fetch_rc(A, g.lda, m0, g.M, k0, ra);
-        if (B_KC) fetch_kc(B, g.ldb, n0, g.N, k0, rb); else fetch_rc(B, g.ldb, n0, g.N, k0, rb);
+    auto fetch = [&](const Tile &t, uint32_t k0) {
+        if (A_KC) fetch_kc(t.A, g.lda, t.m0, g.M, k0, ra); else fetch_rc(t.A, g.lda, t.m0, g.M, k0, wave, ra);
+        if (B_KC) fetch_kc(t.B, g.ldb, t.n0, g.N, k0, rb); else fetch_rc(t.B, g.ldb, t.n0, g.N, k0, wave, rb);
     };
     auto stash = [&](int buf) {
         if (A_KC) stash_kc(lds_a[buf], ra); else stash_rc(lds_a[buf], ra);
         if (B_KC) stash_kc(lds_b[buf], rb); else stash_rc(lds_b[buf], rb);
     };
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    const uint32_t slabs = g.K / TK;
-    for (uint32_t s = 0; s < slabs; ++s) {
-        const int cur = s & 1;
-        if (s + 1 < slabs) fetch((s + 1) * TK);
-        float a[2][8], b[2][8];
+
+    const Tile t = tile_of_id(g, blockIdx.x);
+    if (!t.valid) return;
+    fetch(t, 0);
+    {
+        f16v acc[2][2];
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi) operand<A_KC>(lds_a[cur], wm + 32 * mi + r32, half, a[mi]);
+        for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni) operand<B_KC>(lds_b[cur], wn + 32 * ni + r32, half, b[ni]);
+            for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < 2; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][kk], b[ni][kk], acc[mi][ni], 0, 0, 0);
-        if (s + 1 < slabs) stash(cur ^ 1);
+                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+        const bool full_tile = t.m0 + TM <= g.M && t.n0 + TN <= g.N;
+        float pre[2][2][16];
+        const AuxPos aux_pos{t.aux, t.m0, t.n0, wm, wn, half, r32, full_tile};
+
+        stash(0);
         __syncthreads();
+        // iteration s of the K loop (s % 8 == TURN); the first four also request two parts of the other tile each,
+        // which leaves the rest of even the shortest K loop (K = 128: eight iterations) to cover their latency
+        auto iteration = [&](uint32_t s, auto turn) {
+            constexpr int TURN = decltype(turn)::value, cur = TURN & 1;
+            if (s + 1 < slabs) fetch(t, (s + 1) * TK);
+            if constexpr ((EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE) && 2 * TURN + 1 < AUX_PARTS)
+                if (s < AUX_PARTS / 2) {
+                    prefetch_aux_rows<EPI, 2 * TURN>(g, aux_pos, at_run_time(2 * TURN), pre);
+                    prefetch_aux_rows<EPI, 2 * TURN + 1>(g, aux_pos, at_run_time(2 * TURN + 1), pre);
+                }
+            float a[2][8], b[2][8];
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) operand<A_KC>(lds_a[cur], wm + 32 * mi + r32, half, a[mi]);
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) operand<B_KC>(lds_b[cur], wn + 32 * ni + r32, half, b[ni]);
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][kk], b[ni][kk], acc[mi][ni], 0, 0, 0);
+            if (s + 1 < slabs) stash(cur ^ 1);
+            __syncthreads();
+        };
+        for (uint32_t s = 0; s < slabs; s += AUX_PARTS) {
+            iteration(s, Part<0>{});
+            if (s + 1 < slabs) iteration(s + 1, Part<1>{});
+            if (s + 2 < slabs) iteration(s + 2, Part<2>{});
+            if (s + 3 < slabs) iteration(s + 3, Part<3>{});
+            if (s + 4 < slabs) iteration(s + 4, Part<4>{});
+            if (s + 5 < slabs) iteration(s + 5, Part<5>{});
+            if (s + 6 < slabs) iteration(s + 6, Part<6>{});
+            if (s + 7 < slabs) iteration(s + 7, Part<7>{});
+        }
+        prefetch_aux_rest<EPI>(g, aux_pos, 2 * slabs, pre);    // K shorter than the parts
+
+        epilogue<EPI>(g, t, acc, wm, wn, half, r32, full_tile, pre, lds_a[0]);
     }
-    epilogue<EPI>(g, C, aux, acc, m0, n0, wm, wn, half, r32, full_tile, pre);
 }
 
 // ---- the same GEMMs as three bf16 products -----------------------------------------------------------
@@ -281,16 +382,18 @@ __device__ __forceinline__ LaneKc lane_kc(uint32_t ld, uint32_t row0, uint32_t r
     const uint32_t t = threadIdx.x;
     LaneKc o;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o.off[i] = min(row0 + (t >> 3) + 32 * i, rows - 1) * ld + 4 * (t & 7);
+    for (int i = 0; i < 4; ++i) o.off[i] = 4 * (min(row0 + (t >> 3) + 32 * i, rows - 1) * ld + 4 * (t & 7));   // bytes
     return o;
 }
 // STREAM: the operand is a weight matrix read once per launch (non-temporal), not a cached activation.
 template <bool STREAM>
 __device__ __forceinline__ void fetch3_kc(const float *P, const LaneKc &o, uint32_t k0, f4 r[4]) {
-    const float *base = P + k0;                                        // uniform
+    SWARM_GLOBAL const float *base = (SWARM_GLOBAL const float *)(P + k0);   // measured: no gain from the marker here
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        r[i] = STREAM ? __builtin_nontemporal_load((const f4 *)(base + o.off[i])) : *(const f4 *)(base + o.off[i]);
+    for (int i = 0; i < 4; ++i) {
+        SWARM_GLOBAL const f4 *src = (SWARM_GLOBAL const f4 *)at_bytes(base, o.off[i]);
+        r[i] = STREAM ? __builtin_nontemporal_load(src) : *src;
+    }
 }
 __device__ __forceinline__ void stash3_kc(u4 *hi, u4 *lo, const f4 r[4]) {
     const uint32_t t = threadIdx.x, oct = (t & 7) >> 1, part = t & 1;      // k = 4 (t & 7) = 8 oct + 4 part
@@ -314,10 +417,11 @@ __device__ __forceinline__ void fetch3_rc(const float *P, uint32_t ld, uint32_t 
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const uint32_t oct = (wave >> 1) + 2 * i;
-        const float *base = P + (uint64_t)(k0 + 8 * oct) * ld;          // uniform
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            r[i][j] = STREAM ? __builtin_nontemporal_load(base + (uint64_t)j * ld + row) : base[(uint64_t)j * ld + row];
+        for (int j = 0; j < 8; ++j) {
+            SWARM_GLOBAL const float *src = at_bytes(uniform(P + (uint64_t)(k0 + 8 * oct + j) * ld), 4 * row);
+            r[i][j] = STREAM ? __builtin_nontemporal_load(src) : *src;
+        }
     }
 }
 __device__ __forceinline__ void stash3_rc(u4 *hi, u4 *lo, const float r[2][8]) {
@@ -347,49 +451,45 @@ __device__ __forceinline__ void interleave_matrix_and_vector() {
 template <bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(256, 2) void mlp_gemm3_kernel(const GemmArgs g) {
     __shared__ u4 lds[2][4][SLAB_WORDS];            // buffer x {A hi, A lo, B hi, B lo}
-    const TileId id = tile_of_workgroup(g);
-    if (!id.valid) return;
-    const uint32_t slot = id.slot, node = g.nodes ? g.nodes[slot] : slot;
-    const float *A = g.A + (g.a_by_node ? node : slot) * g.strideA;
-    const float *B = g.B + (g.b_by_node ? node : slot) * g.strideB;
-    float *C = g.C + (g.c_by_node ? node : slot) * g.strideC;
-    const float *aux = g.aux + (g.aux_by_node ? node : slot) * g.strideAux;
-    const uint32_t m0 = id.tile_m * TM, n0 = id.tile_n * TN;
     const uint32_t lane = threadIdx.x & 63u, half = lane >> 5, r32 = lane & 31u;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // scalar: bases stay uniform
     const uint32_t wm = (wave >> 1) * 64, wn = (wave & 1u) * 64;
-
-    f16v acc[2][2];
-#pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-    const bool full_tile = m0 + TM <= g.M && n0 + TN <= g.N;
-    // The weights an update needs are requested ahead of the K loop (its few slabs come from cache, the tile
+    // The weights an update needs are requested during the K loop (its few slabs come from cache, the tile
     // from memory); the ReLU mask is a cached activation and is read in the epilogue, which leaves the
     // registers to the operand pipeline.
     constexpr bool AUX_AHEAD = EPI == EPI_SGD_UPDATE;
+
+    f16v acc[2][2];
     float pre[2][2][16];
-    if (AUX_AHEAD) prefetch_aux<EPI>(g, aux, m0, n0, wm, wn, half, r32, full_tile, pre);
 
     // Operand slabs travel two iterations ahead of their use: global memory -> registers (stage s + 2),
     // registers -> LDS as bf16 hi / lo (stage s + 1), LDS -> matrix cores (stage s).  One slab in flight per
     // workgroup does not cover the memory latency at two workgroups per compute unit.
     struct Stage { f4 ka[4], kb[4]; float ra[2][8], rb[2][8]; };
-    const uint32_t uwave = wave;
-    const LaneKc lane_a = lane_kc(g.lda, m0, g.M), lane_b = lane_kc(g.ldb, n0, g.N);
-    const uint32_t row_a = min(m0 + (threadIdx.x & 127u), g.M - 1), row_b = min(n0 + (threadIdx.x & 127u), g.N - 1);
-    auto fetch = [&](uint32_t k0, Stage &r) {
+    struct Rows { LaneKc a, b; uint32_t row_a, row_b; };       // the lane's part of a tile's operand addresses
+    auto rows_of = [&](const Tile &t) {
+        Rows r{};
+        if (A_KC) r.a = lane_kc(g.lda, t.m0, g.M); else r.row_a = min(t.m0 + (threadIdx.x & 127u), g.M - 1);
+        if (B_KC) r.b = lane_kc(g.ldb, t.n0, g.N); else r.row_b = min(t.n0 + (threadIdx.x & 127u), g.N - 1);
+        return r;
+    };
+    auto fetch = [&](const Tile &t, const Rows &rw, uint32_t k0, Stage &r) {
         // in the forward and backward products B is a weight matrix; in the updates both operands are activations
         constexpr bool B_STREAM = EPI != EPI_SGD_UPDATE;
-        if (A_KC) fetch3_kc<false>(A, lane_a, k0, r.ka); else fetch3_rc<false>(A, g.lda, row_a, uwave, k0, r.ra);
-        if (B_KC) fetch3_kc<B_STREAM>(B, lane_b, k0, r.kb); else fetch3_rc<B_STREAM>(B, g.ldb, row_b, uwave, k0, r.rb);
+        if (A_KC) fetch3_kc<false>(t.A, rw.a, k0, r.ka); else fetch3_rc<false>(t.A, g.lda, rw.row_a, wave, k0, r.ra);
+        if (B_KC) fetch3_kc<B_STREAM>(t.B, rw.b, k0, r.kb); else fetch3_rc<B_STREAM>(t.B, g.ldb, rw.row_b, wave, k0, r.rb);
     };
     auto stash = [&](int buf, const Stage &r) {
         if (A_KC) stash3_kc(lds[buf][0], lds[buf][1], r.ka); else stash3_rc(lds[buf][0], lds[buf][1], r.ra);
         if (B_KC) stash3_kc(lds[buf][2], lds[buf][3], r.kb); else stash3_rc(lds[buf][2], lds[buf][3], r.rb);
+    };
+    auto clear = [&]() {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
     };
     auto multiply = [&](int cur) {
 #pragma unroll
@@ -418,22 +518,46 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm3_kernel(const GemmArgs g) {
         }
     };
     const uint32_t slabs = g.K / TK3;
+    const Tile t = tile_of_id(g, blockIdx.x);
+    if (!t.valid) return;
+    const Rows rw = rows_of(t);
     if (AUX_AHEAD) {                                 // registers hold the weight tile: one slab ahead
         Stage next;
-        fetch(0, next);
-        stash(0, next);
-        __syncthreads();
-        for (uint32_t s = 0; s < slabs; ++s) {
-            const int cur = s & 1;
-            if (s + 1 < slabs) fetch((s + 1) * TK3, next);
-            multiply(cur);
-            if (s + 1 < slabs) stash(cur ^ 1, next);
+        fetch(t, rw, 0, next);
+        {
+            clear();
+            const bool full_tile = t.m0 + TM <= g.M && t.n0 + TN <= g.N;
+            const AuxPos aux_pos{t.aux, t.m0, t.n0, wm, wn, half, r32, full_tile};
+            stash(0, next);
             __syncthreads();
+            // iteration s (s % 4 == TURN); in the first pass it also requests a quarter of the weight tile (K = 128 is
+            // four iterations)
+            auto iteration = [&](uint32_t s, auto turn) {
+                constexpr int TURN = decltype(turn)::value, cur = TURN & 1;
+                if (s + 1 < slabs) fetch(t, rw, (s + 1) * TK3, next);
+                if (s < AUX_PARTS / 2) {
+                    prefetch_aux_rows<EPI, 2 * TURN>(g, aux_pos, at_run_time(2 * TURN), pre);
+                    prefetch_aux_rows<EPI, 2 * TURN + 1>(g, aux_pos, at_run_time(2 * TURN + 1), pre);
+                }
+                multiply(cur);
+                if (s + 1 < slabs) stash(cur ^ 1, next);
+                __syncthreads();
+            };
+            for (uint32_t s = 0; s < slabs; s += 4) {
+                iteration(s, Part<0>{});
+                if (s + 1 < slabs) iteration(s + 1, Part<1>{});
+                if (s + 2 < slabs) iteration(s + 2, Part<2>{});
+                if (s + 3 < slabs) iteration(s + 3, Part<3>{});
+            }
+            prefetch_aux_rest<EPI>(g, aux_pos, 2 * slabs, pre);
+            epilogue<EPI, false>(g, t, acc, wm, wn, half, r32, full_tile, pre, (float *)lds[0][0]);
         }
     } else {
+        clear();
+        const bool full_tile = t.m0 + TM <= g.M && t.n0 + TN <= g.N;
         Stage even, odd;                             // slab s waits in `even` when s is even, else in `odd`
-        fetch(0, even);
-        if (slabs > 1) fetch(TK3, odd);
+        fetch(t, rw, 0, even);
+        if (slabs > 1) fetch(t, rw, TK3, odd);
         stash(0, even);
         __syncthreads();
         // iteration s: request slab s + 2 into the registers slab s has just left, multiply slab s, stage slab s + 1.
@@ -442,12 +566,12 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm3_kernel(const GemmArgs g) {
         // with the vector ALU idle, and then the other way round.
         uint32_t s = 0;
         for (; s + 3 < slabs; s += 2) {
-            fetch((s + 2) * TK3, even);
+            fetch(t, rw, (s + 2) * TK3, even);
             multiply(0);
             stash(1, odd);
             interleave_matrix_and_vector();
             __syncthreads();
-            fetch((s + 3) * TK3, odd);
+            fetch(t, rw, (s + 3) * TK3, odd);
             multiply(1);
             stash(0, even);
             interleave_matrix_and_vector();
@@ -455,13 +579,13 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm3_kernel(const GemmArgs g) {
         }
         for (; s < slabs; ++s) {                     // the last slabs: nothing left to request
             const bool to_even = (s & 1u) != 0;      // slab s + 1 waits in `even` when s is odd
-            if (s + 2 < slabs) { if (to_even) fetch((s + 2) * TK3, odd); else fetch((s + 2) * TK3, even); }
+            if (s + 2 < slabs) { if (to_even) fetch(t, rw, (s + 2) * TK3, odd); else fetch(t, rw, (s + 2) * TK3, even); }
             multiply(s & 1);
             if (s + 1 < slabs) { if (to_even) stash(0, even); else stash(1, odd); }
             __syncthreads();
         }
+        epilogue<EPI, true>(g, t, acc, wm, wn, half, r32, full_tile, pre, (float *)lds[0][0]);
     }
-    epilogue<EPI, !AUX_AHEAD>(g, C, aux, acc, m0, n0, wm, wn, half, r32, full_tile, pre);
 }
 
 // Labels by inverse CDF: y = #{c : cdf[c] <= u}, u = (word >> 8) 2^-24, limited to n_out - 1.
@@ -521,21 +645,47 @@ __device__ __forceinline__ float block_reduce(float v, float *lds, bool is_max) 
     return r;
 }
 
-// In place: logits row -> (softmax - onehot(y)) / batch.
+// In place: logits row -> (softmax - onehot(y)) / batch.  Rows of up to 2048 entries stay in registers between
+// the three passes (maximum, sum of exponentials, result): one read and one write of the row.
 __global__ __launch_bounds__(256) void mlp_softmax_grad_kernel(float *__restrict__ logits,
                                                                const uint32_t *__restrict__ labels, uint32_t n_out,
                                                                uint32_t batch) {
     __shared__ float lds[4];
     const uint32_t slot = blockIdx.y, s = blockIdx.x;
     float *row = logits + ((uint64_t)slot * batch + s) * n_out;
+    const uint32_t y = labels[(uint64_t)slot * batch + s];
+    const float inv_b = 1.0f / (float)batch;
+    constexpr int HELD = 8;
+    if (n_out <= 256 * HELD) {
+        float v[HELD];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < HELD; ++i) {
+            const uint32_t c = threadIdx.x + 256 * i;
+            v[i] = c < n_out ? row[c] : -INFINITY;
+            mx = fmaxf(mx, v[i]);
+        }
+        mx = block_reduce(mx, lds, true);
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < HELD; ++i) {
+            v[i] = expf(v[i] - mx);              // exp(-inf) = 0 for the entries past the row
+            sum += v[i];
+        }
+        sum = block_reduce(sum, lds, false);
+#pragma unroll
+        for (int i = 0; i < HELD; ++i) {
+            const uint32_t c = threadIdx.x + 256 * i;
+            if (c < n_out) row[c] = (v[i] / sum - (c == y ? 1.f : 0.f)) * inv_b;
+        }
+        return;
+    }
     float mx = -INFINITY;
     for (uint32_t c = threadIdx.x; c < n_out; c += 256) mx = fmaxf(mx, row[c]);
     mx = block_reduce(mx, lds, true);
     float sum = 0.f;
     for (uint32_t c = threadIdx.x; c < n_out; c += 256) sum += expf(row[c] - mx);
     sum = block_reduce(sum, lds, false);
-    const uint32_t y = labels[(uint64_t)slot * batch + s];
-    const float inv_b = 1.0f / (float)batch;
     for (uint32_t c = threadIdx.x; c < n_out; c += 256)
         row[c] = (expf(row[c] - mx) / sum - (c == y ? 1.f : 0.f)) * inv_b;
 }
@@ -618,7 +768,11 @@ hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, 
         g.C = o.dhid; g.strideC = (uint64_t)Bt * Hd; g.ldc = Hd;
         g.aux = o.hid; g.strideAux = (uint64_t)Bt * Hd; g.aux_by_node = 0; g.ldaux = Hd;
         g.M = Bt; g.N = Hd; g.K = O;
+        // b1 <- b1 - eta colsum(dpre), inside this GEMM when one tile holds the whole batch
+        const bool b1_inside = Bt <= (uint32_t)TM;
+        if (b1_inside) { g.colsum_src = src + off_b1; g.colsum_dst = W + off_b1; g.strideColsum = d; }
         gemm<true, false, EPI_RELU_MASK>(g, count, o.bf16x3, st);
+        g.colsum_src = nullptr; g.colsum_dst = nullptr;
         // W2 <- W2 - eta dlogits^T hid:  M = out, N = hid, K = batch;  both operands stored [k][row]
         g.A = o.dlogits; g.strideA = (uint64_t)Bt * O; g.a_by_node = 0; g.lda = O;
         g.B = o.hid; g.strideB = (uint64_t)Bt * Hd; g.b_by_node = 0; g.ldb = Hd;
@@ -634,7 +788,8 @@ hipError_t launch_local_mlp(const float *base, float *W, const MlpObjective &o, 
         g.aux = src; g.ldaux = I;
         g.M = Hd; g.N = I; g.K = Bt;
         gemm<false, false, EPI_SGD_UPDATE>(g, count, o.bf16x3, st);
-        mlp_bias_kernel<<<dim3((Hd + 255) / 256, count), 256, 0, st>>>(o.dhid, src, W, nodes, Hd, Bt, d, off_b1, lr);
+        if (!b1_inside)
+            mlp_bias_kernel<<<dim3((Hd + 255) / 256, count), 256, 0, st>>>(o.dhid, src, W, nodes, Hd, Bt, d, off_b1, lr);
     }
     return hipGetLastError();
 }
