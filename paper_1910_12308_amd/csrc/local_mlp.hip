@@ -1,14 +1,16 @@
 // Local SGD steps for the two-layer perceptron objective (in -> hid -> out, ReLU,
 // softmax cross-entropy averaged over the batch) on a synthetic Gaussian mixture.
 // Every node has its own weights, so each step is a *grouped* problem: one launch per
-// GEMM covers all nodes (grid.z), each workgroup computing a 128x128 tile of one node's
-// product on the matrix cores (v_mfma_f32_32x32x2f32, float32 in and out).
+// GEMM covers all nodes (a one-dimensional grid over (node, tile), numbered so that a node's
+// tiles run on one die), each workgroup computing a 128x128 tile of one node's product on the
+// matrix cores (v_mfma_f32_32x32x2f32, float32 in and out; or three bf16 products per term).
 //
 // Per step:  data (labels, features)  ->  hid = relu(x W1^T + b1)  ->  logits = hid W2^T + b2
 //   -> dlogits = (softmax - onehot)/batch -> dpre = (dlogits W2) * [hid > 0]
 //   -> W2 -= eta dlogits^T hid, b2 -= eta colsum(dlogits), W1 -= eta dpre^T x, b1 -= eta colsum(dpre).
 // The weight updates are fused into the epilogues of the two weight-gradient GEMMs, so
-// the gradients never reach memory.
+// the gradients never reach memory; the hidden-layer bias update rides in the epilogue of the
+// backward GEMM (the tile holds the whole batch, so its column sums are the bias gradient).
 //
 // Tiling: 4 waves per workgroup, each wave a 64x64 sub-tile = 2x2 MFMA blocks; K is
 // consumed in slabs of 16 staged through LDS (double buffered, next slab prefetched into
