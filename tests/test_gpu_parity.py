@@ -404,7 +404,9 @@ def test_round_mode_free_running_matches_statistically(gpu, mode):
 
 # ------------------------------------------------------------------ MLP local steps (MFMA GEMMs)
 @pytest.mark.parametrize("arithmetic", ["float32", "three bf16 products"])
-@pytest.mark.parametrize("shape", [(64, 96, 32, 32), (256, 384, 128, 128)])
+# the last shape has a batch taller than one 128-row tile: ragged second tile row, ten K slabs in the update GEMMs,
+# and the hidden-layer bias updated by its own kernel instead of inside the backward GEMM
+@pytest.mark.parametrize("shape", [(64, 96, 32, 32), (256, 384, 128, 128), (64, 96, 32, 160)])
 def test_local_steps_mlp(gpu, shape, arithmetic):
     """Two local steps of the two-layer perceptron on the Gaussian mixture: data generation,
     forward, softmax-CE gradient, backward GEMMs and fused SGD updates against the float64 oracle."""
