@@ -41,7 +41,7 @@ struct swarm_ctx {
 
     float *X = nullptr, *W = nullptr, *Xhat = nullptr;
     uint8_t *ring = nullptr;
-    uint32_t *edges_dev = nullptr, *prio_dev = nullptr, *counts_dev = nullptr, *nodes_dev = nullptr;
+    uint32_t *edges_dev = nullptr, *prio_dev = nullptr, *nodes_dev = nullptr;
     uint32_t *linf_dev = nullptr, *steps_dev = nullptr;   // steps_dev: local steps per slot of a launch (geometric law)
     // batches of Algorithm 1: per interaction a descriptor, the initiator, its step count and its event
     uint8_t *seq_dev = nullptr, *seq_host = nullptr;      // capacity seq_cap interactions each (seq_host pinned)
@@ -60,7 +60,8 @@ struct swarm_ctx {
     hipEvent_t desc_free[DESC_SLOTS] = {nullptr, nullptr, nullptr, nullptr};
     unsigned desc_next = 0;
     uint32_t *match_host = nullptr;              // counts[2] | pairs | singles
-    uint32_t *mpairs_dev = nullptr, *msingles_dev = nullptr;   // outputs of the matching kernel
+    uint32_t *match_dev = nullptr;               // match_host as the device sees it: the matching kernel writes there
+    hipStream_t match_stream = nullptr;          // the matching runs beside the round kernels, not between them
     hipEvent_t match_ready = nullptr;            // the matching of round match_round has reached match_host
     uint64_t match_round = ~0ull;
     double *scalar_host = nullptr;
@@ -326,7 +327,6 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         }
         SWARM_HIP(h, hipMalloc((void **)&h->edges_dev, sizeof(uint32_t) * 2 * cfg->n_edges));
         SWARM_HIP(h, hipMalloc((void **)&h->prio_dev, sizeof(uint32_t) * cfg->n_edges));
-        SWARM_HIP(h, hipMalloc((void **)&h->counts_dev, sizeof(uint32_t) * 2));
         SWARM_HIP(h, hipMalloc((void **)&h->nodes_dev, sizeof(uint32_t) * n));
         SWARM_HIP(h, hipMalloc((void **)&h->linf_dev, sizeof(uint32_t) * PAIR_STRIPES * (n / 2)));
         SWARM_HIP(h, hipMalloc((void **)&h->steps_dev, sizeof(uint32_t) * n));
@@ -344,8 +344,6 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
             SWARM_HIP(h, hipMemcpy(h->scale_state_dev, state.data(), sizeof(uint32_t) * state.size(), hipMemcpyHostToDevice));
         }
         SWARM_HIP(h, hipMalloc((void **)&h->desc_dev, h->desc_bytes));
-        SWARM_HIP(h, hipMalloc((void **)&h->mpairs_dev, sizeof(uint32_t) * 2 * (n / 2)));
-        SWARM_HIP(h, hipMalloc((void **)&h->msingles_dev, sizeof(uint32_t) * n));
         SWARM_HIP(h, hipEventCreateWithFlags(&h->match_ready, hipEventDisableTiming));
         SWARM_HIP(h, hipMalloc((void **)&h->counters_dev, sizeof(DeviceCounters)));
         SWARM_HIP(h, hipMalloc((void **)&h->partials_dev, sizeof(double) * potential_partials(cfg->d)));
@@ -357,6 +355,8 @@ swarm_status swarm_init(const swarm_config *cfg, const float *x0_dev, void *hip_
         }
         SWARM_HIP(h, hipHostMalloc((void **)&h->match_host, sizeof(uint32_t) * (2 + 2 * (n / 2) + n),
                                    hipHostMallocDefault));
+        SWARM_HIP(h, hipHostGetDevicePointer((void **)&h->match_dev, h->match_host, 0));
+        SWARM_HIP(h, hipStreamCreateWithFlags(&h->match_stream, hipStreamNonBlocking));
         SWARM_HIP(h, hipHostMalloc((void **)&h->scalar_host, 64, hipHostMallocDefault));
         SWARM_HIP(h, hipMemcpyAsync(h->edges_dev, h->edges.data(), sizeof(uint32_t) * 2 * cfg->n_edges,
                                     hipMemcpyHostToDevice, h->stream));
@@ -390,9 +390,13 @@ swarm_status swarm_destroy(swarm_t h) {
     free_lsq(h->lsq);
     free_mlp(h->mlp);
     if (h->W == h->X) h->W = nullptr;
-    void *dev[] = {h->X, h->W, h->Xhat, h->ring, h->edges_dev, h->prio_dev, h->counts_dev, h->nodes_dev,
-                   h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev, h->mpairs_dev,
-                   h->msingles_dev, h->steps_dev, h->eps_slots_dev, h->scale_state_dev, h->prefix_stats_dev};
+    if (h->match_stream) {
+        (void)hipStreamSynchronize(h->match_stream);
+        (void)hipStreamDestroy(h->match_stream);
+    }
+    void *dev[] = {h->X, h->W, h->Xhat, h->ring, h->edges_dev, h->prio_dev, h->nodes_dev,
+                   h->linf_dev, h->desc_dev, h->counters_dev, h->partials_dev, h->gamma_dev,
+                   h->steps_dev, h->eps_slots_dev, h->scale_state_dev, h->prefix_stats_dev};
     for (void *p : dev) if (p) (void)hipFree(p);
     for (int s = 0; s < DESC_SLOTS; ++s) {
         if (h->desc_host[s]) (void)hipHostFree(h->desc_host[s]);
@@ -508,20 +512,16 @@ swarm_status swarm_mark_pending(swarm_t h, const uint32_t *nodes, uint32_t count
     return SWARM_OK;
 }
 
-// Enqueue the matching of the current round and its copy to pinned host memory.  The matching
-// depends only on (seed, round, graph), so it can be issued a round ahead: the host then finds
-// it ready instead of draining the stream.
+// Enqueue the matching of a round.  It depends only on (seed, round, graph), so it is issued a round
+// ahead, on a stream of its own (it runs beside the round kernels instead of between them), and it
+// writes its few hundred bytes of results (counts | pairs | unmatched nodes) straight into pinned host
+// memory: the host finds them ready instead of draining the stream, and no copy is launched.
 static swarm_status enqueue_matching(swarm_t h, uint64_t round) {
     const swarm_config &c = h->cfg;
     const uint32_t maxp = c.n / 2;
     SWARM_HIP(h, launch_matching(h->edges_dev, c.n_edges, c.n, c.seed, (uint32_t)round, h->prio_dev,
-                                 h->mpairs_dev, h->msingles_dev, h->counts_dev, h->stream));
-    SWARM_HIP(h, hipMemcpyAsync(h->match_host, h->counts_dev, sizeof(uint32_t) * 2, hipMemcpyDeviceToHost, h->stream));
-    SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2, h->mpairs_dev, sizeof(uint32_t) * 2 * maxp,
-                                hipMemcpyDeviceToHost, h->stream));
-    SWARM_HIP(h, hipMemcpyAsync(h->match_host + 2 + 2 * maxp, h->msingles_dev, sizeof(uint32_t) * c.n,
-                                hipMemcpyDeviceToHost, h->stream));
-    SWARM_HIP(h, hipEventRecord(h->match_ready, h->stream));
+                                 h->match_dev + 2, h->match_dev + 2 + 2 * maxp, h->match_dev, h->match_stream));
+    SWARM_HIP(h, hipEventRecord(h->match_ready, h->match_stream));
     h->match_round = round;
     return SWARM_OK;
 }
