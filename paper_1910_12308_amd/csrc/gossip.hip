@@ -30,7 +30,7 @@ template <int DELTA>
 __global__ __launch_bounds__(WAVES * 64) void average_pairs_kernel(const GossipArgs a) {
     const uint64_t k = ((uint64_t)blockIdx.x * (WAVES * 64) + threadIdx.x) * 4;
     if (k >= a.d) return;
-    const PairDesc pd = a.pairs[blockIdx.y];
+    const PairDesc pd = pair_desc(a, blockIdx.y);
     const uint32_t ni = pd.ni, nj = pd.nj;
     float *xi = a.X + (uint64_t)ni * a.d + k, *xj = a.X + (uint64_t)nj * a.d + k;
     const f4 vi = ldg_nt(xi), vj = ldg_nt(xj);

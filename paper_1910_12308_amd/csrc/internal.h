@@ -37,6 +37,15 @@ struct PairDesc {
 constexpr uint32_t SINGLE_PENDING = 0x80000000u;
 constexpr uint32_t SINGLE_NODE_MASK = 0xFFFFu;
 
+// A round of at most this many pairs and unmatched nodes carries its descriptors in the launch itself
+// (kernel arguments) instead of in device memory: no copy, and no wait for one, ahead of the round's
+// kernels.  Larger rounds read them from the device block the host fills with one copy.
+constexpr uint32_t INLINE_PAIRS = 64, INLINE_SINGLES = 128;
+struct InlineDescs {
+    PairDesc pairs[INLINE_PAIRS];
+    uint32_t singles[INLINE_SINGLES];
+};
+
 struct GossipArgs {
     float *X;                 // n x d current models (updated in place)
     const float *W;           // n x d live copies
@@ -61,7 +70,18 @@ struct GossipArgs {
     uint32_t slot_now;        // ring slot written this round
     uint32_t ring_depth;      // S + 1
     float eps, inv_eps;
+    uint32_t inline_descs;    // 1: the descriptors of this launch are in `inl`, `pairs` / `singles` are not used
+    InlineDescs inl;
 };
+#if defined(__HIPCC__)
+// Descriptor k of the launch (k is uniform: a scalar load either way).
+__device__ __forceinline__ PairDesc pair_desc(const GossipArgs &g, uint32_t k) {
+    return g.inline_descs ? g.inl.pairs[k] : g.pairs[k];
+}
+__device__ __forceinline__ uint32_t single_desc(const GossipArgs &g, uint32_t k) {
+    return g.inline_descs ? g.inl.singles[k] : g.singles[k];
+}
+#endif
 
 // delta_mode: 0 = no node of these pairs has pending steps, 1 = all have, 2 = per-pair flags.
 // stale_mode: 0 = all reads fresh, 1 = all stale, 2 = per-pair flags, 3 = in every pair only the

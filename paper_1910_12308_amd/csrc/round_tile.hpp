@@ -272,7 +272,7 @@ __device__ __forceinline__ void round_pairs_body(const RoundArgs &ra) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t tile = wave_tile(WAVES);
     if (tile * TILE >= ra.g.d) return;
-    const PairDesc pd = ra.g.pairs[blockIdx.y];                    // uniform: one scalar load
+    const PairDesc pd = pair_desc(ra.g, blockIdx.y);               // uniform: one scalar load
     float eps = ra.g.eps, inv_eps = ra.g.inv_eps;
     if (ra.g.pair_linf) {                                          // the pair's own scale from its distance
         const uint32_t *stripes = ra.g.pair_linf + blockIdx.y * PAIR_STRIPES;      // uniform: scalar loads
@@ -291,7 +291,7 @@ __device__ __forceinline__ void round_nodes_body(const RoundArgs &ra) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t tile = wave_tile(WAVES);
     if (tile * TILE >= ra.g.d) return;
-    const PairDesc pd = ra.g.pairs[blockIdx.y >> 1];               // two rows of the grid per pair
+    const PairDesc pd = pair_desc(ra.g, blockIdx.y >> 1);          // two rows of the grid per pair
     const bool second = blockIdx.y & 1u;
     const uint32_t node = second ? pd.nj : pd.ni, partner = second ? pd.ni : pd.nj;
     const uint32_t age = (pd.flags >> (second ? 8 : 0)) & 0xFFu, H = (pd.steps >> (second ? 8 : 0)) & 0xFFu;
@@ -305,7 +305,7 @@ __device__ __forceinline__ void round_singles_body(const RoundArgs &ra) {
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t tile = wave_tile(WAVES);
     if (tile * TILE >= ra.g.d) return;
-    round_single_tile<BITS, SRC, INPLACE>(ra, ra.g.singles[blockIdx.y], tile, lane);
+    round_single_tile<BITS, SRC, INPLACE>(ra, single_desc(ra.g, blockIdx.y), tile, lane);
 }
 
 inline dim3 tile_grid(uint64_t d, uint32_t rows) {
