@@ -32,6 +32,12 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X published dense bf16 matrix rate
 # calibration (see profiles/), at 4-bit codes with stale reads: key = (kernel, bits, stale).
 MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {("gossip", 4, True): 25.99, ("round", 4, True): 33.99}
 BOX_CPU_SHARE = 16             # host cores a one-GPU machine grants, whatever os.cpu_count() shows
+# Vector-ALU side of the one-pass round at 8-bit codes with gradient noise: vector instructions a wave issues per
+# 512-coordinate tile of one node, from the rocprofv3 SQ_INSTS_VALU / SQ_WAVES runs at H = 3 and H = 5 under
+# profiles/ (fused_nodes_kernel 638 / 880, fused_pairs_kernel 1265 / 1749 per pair): 272 + 121 per local step.
+VALU_PER_NODE_TILE_8BIT = (272.0, 121.0)
+# 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz: lane-operations per second the vector ALUs can issue
+VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
 def algorithmic_bytes_per_pair_coordinate(kernel, bits, stale_fraction, inplace=False, prefix=False):
@@ -272,6 +278,21 @@ def roofline(kernel, name, cfg, m, d, inplace=False):
             "ms_per_launch": m["times"]["gossip_ms"] / launches}
 
 
+def alu_roofline(cfg, m, d):
+    """The instruction-issue side of the one-pass round (8-bit codes, gradient noise): from H = 4 on these kernels are
+    bound by the vector ALUs, not by HBM.  None for workloads whose instruction count was not measured."""
+    if cfg["bits"] != 8 or not cfg.get("sigma") or cfg.get("codec") == "prefix":
+        return None
+    per_tile = VALU_PER_NODE_TILE_8BIT[0] + VALU_PER_NODE_TILE_8BIT[1] * cfg["H"]
+    lane_ops = 64.0 * per_tile * 2 * m["interactions"] * ((d + 511) // 512)
+    rate = lane_ops / (m["times"]["gossip_ms"] * 1e-3) / 1e12
+    return {"bound": "alu", "valu_instructions_per_node_tile": per_tile, "achieved": rate, "peak": VALU_PEAK_TLANEOPS,
+            "unit": "T lane-ops/s", "frac": rate / VALU_PEAK_TLANEOPS,
+            "note": "instruction count per tile = the stored SQ_INSTS_VALU / SQ_WAVES figure from "
+                    "profiles/fused_pairs_kernel_config5.md, not counted in this run; a wave64 instruction holds its "
+                    "SIMD's issue port 4 cycles"}
+
+
 def step_roofline(kernel, cfg, m, d, n, inplace=False):
     """Every compulsory byte of the step (pairs and unmatched nodes) over the wall time of the step."""
     bits, S = cfg["bits"], cfg["stale_max"]
@@ -368,6 +389,9 @@ def compact_config(torch, swarm, cfg_id, steps, warmup):
                     "roofline": {k: roof[k] for k in ("kernel", "bound", "bytes_per_pair_coordinate", "achieved", "peak", "unit",
                                                       "frac", "ms_per_launch")},
                     "step_roofline_frac": step_roofline("round", cfg, m, d, n)["frac"]})
+        alu = alu_roofline(cfg, m, d)
+        if alu:
+            rec["alu_roofline"] = alu
     else:   # MLP: the local steps are GEMMs on the matrix cores, the gossip pass is the HBM-bound one
         def step():
             s.local_steps()
@@ -569,6 +593,9 @@ def main():
     }
     if cfg["objective"] == "diag":
         out["step_roofline"] = step_roofline("round" if use_one_pass else "gossip", cfg, main_m, d, n, args.inplace)
+        alu = alu_roofline(cfg, main_m, d) if use_one_pass and not args.prefix and not args.inplace else None
+        if alu:
+            out["alu_roofline"] = alu
     if two_m is not None:
         out["two_call_round"] = two_call_report(two_m)
     if one_m is not None and not use_one_pass:
