@@ -143,10 +143,10 @@ __device__ __forceinline__ void operand(const float *lds, uint32_t row, uint32_t
 
 // Epilogues that need a tile of another matrix (the weights to update, the ReLU mask source) request it
 // during the K loop, so that its HBM latency hides behind the MFMAs instead of serialising compute phase
-// and memory phase.  The 64 values a lane needs are requested in PARTS equal parts, part c after the
-// operand fetch of iteration c: loads return in order, so a request for the whole tile ahead of the loop
-// would hold back every operand slab behind it until the tile has arrived (and leave memory idle for
-// the rest of the loop).  Tiles that lie wholly inside the matrix (all of them when M and N are
+// and memory phase.  The 64 values a lane needs are requested in eight parts, a few after the operand
+// fetch of each of the first iterations: loads return in order, so a request for the whole tile ahead
+// of the loop would hold back every operand slab behind it until the tile has arrived (and leave memory
+// idle for the rest of the loop).  Tiles that lie wholly inside the matrix (all of them when M and N are
 // multiples of 128) take straight-line loads and stores; the guarded path serves ragged edges.
 struct AuxPos { const float *aux; uint32_t m0, n0, wm, wn, half, r32; bool full_tile; };
 constexpr int AUX_PARTS = 8;     // part c = 4 mi + (v / 4): four consecutive rows, both column blocks
@@ -289,59 +289,57 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm_kernel(const GemmArgs g) {
     const Tile t = tile_of_id(g, blockIdx.x);
     if (!t.valid) return;
     fetch(t, 0);
-    {
-        f16v acc[2][2];
+    f16v acc[2][2];
 #pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
+        for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-        const bool full_tile = t.m0 + TM <= g.M && t.n0 + TN <= g.N;
-        float pre[2][2][16];
-        const AuxPos aux_pos{t.aux, t.m0, t.n0, wm, wn, half, r32, full_tile};
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    const bool full_tile = t.m0 + TM <= g.M && t.n0 + TN <= g.N;
+    float pre[2][2][16];
+    const AuxPos aux_pos{t.aux, t.m0, t.n0, wm, wn, half, r32, full_tile};
 
-        stash(0);
+    stash(0);
+    __syncthreads();
+    // iteration s of the K loop (s % 8 == TURN); the first four also request two parts of the other tile each,
+    // which leaves the rest of even the shortest K loop (K = 128: eight iterations) to cover their latency
+    auto iteration = [&](uint32_t s, auto turn) {
+        constexpr int TURN = decltype(turn)::value, cur = TURN & 1;
+        if (s + 1 < slabs) fetch(t, (s + 1) * TK);
+        if constexpr ((EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE) && 2 * TURN + 1 < AUX_PARTS)
+            if (s < AUX_PARTS / 2) {
+                prefetch_aux_rows<EPI, 2 * TURN>(g, aux_pos, at_run_time(2 * TURN), pre);
+                prefetch_aux_rows<EPI, 2 * TURN + 1>(g, aux_pos, at_run_time(2 * TURN + 1), pre);
+            }
+        float a[2][8], b[2][8];
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) operand<A_KC>(lds_a[cur], wm + 32 * mi + r32, half, a[mi]);
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) operand<B_KC>(lds_b[cur], wn + 32 * ni + r32, half, b[ni]);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][kk], b[ni][kk], acc[mi][ni], 0, 0, 0);
+        if (s + 1 < slabs) stash(cur ^ 1);
         __syncthreads();
-        // iteration s of the K loop (s % 8 == TURN); the first four also request two parts of the other tile each,
-        // which leaves the rest of even the shortest K loop (K = 128: eight iterations) to cover their latency
-        auto iteration = [&](uint32_t s, auto turn) {
-            constexpr int TURN = decltype(turn)::value, cur = TURN & 1;
-            if (s + 1 < slabs) fetch(t, (s + 1) * TK);
-            if constexpr ((EPI == EPI_RELU_MASK || EPI == EPI_SGD_UPDATE) && 2 * TURN + 1 < AUX_PARTS)
-                if (s < AUX_PARTS / 2) {
-                    prefetch_aux_rows<EPI, 2 * TURN>(g, aux_pos, at_run_time(2 * TURN), pre);
-                    prefetch_aux_rows<EPI, 2 * TURN + 1>(g, aux_pos, at_run_time(2 * TURN + 1), pre);
-                }
-            float a[2][8], b[2][8];
-#pragma unroll
-            for (int mi = 0; mi < 2; ++mi) operand<A_KC>(lds_a[cur], wm + 32 * mi + r32, half, a[mi]);
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni) operand<B_KC>(lds_b[cur], wn + 32 * ni + r32, half, b[ni]);
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                    for (int ni = 0; ni < 2; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mi][kk], b[ni][kk], acc[mi][ni], 0, 0, 0);
-            if (s + 1 < slabs) stash(cur ^ 1);
-            __syncthreads();
-        };
-        for (uint32_t s = 0; s < slabs; s += AUX_PARTS) {
-            iteration(s, Part<0>{});
-            if (s + 1 < slabs) iteration(s + 1, Part<1>{});
-            if (s + 2 < slabs) iteration(s + 2, Part<2>{});
-            if (s + 3 < slabs) iteration(s + 3, Part<3>{});
-            if (s + 4 < slabs) iteration(s + 4, Part<4>{});
-            if (s + 5 < slabs) iteration(s + 5, Part<5>{});
-            if (s + 6 < slabs) iteration(s + 6, Part<6>{});
-            if (s + 7 < slabs) iteration(s + 7, Part<7>{});
-        }
-        prefetch_aux_rest<EPI>(g, aux_pos, 2 * slabs, pre);    // K shorter than the parts
-
-        epilogue<EPI>(g, t, acc, wm, wn, half, r32, full_tile, pre, lds_a[0]);
+    };
+    for (uint32_t s = 0; s < slabs; s += AUX_PARTS) {
+        iteration(s, Part<0>{});
+        if (s + 1 < slabs) iteration(s + 1, Part<1>{});
+        if (s + 2 < slabs) iteration(s + 2, Part<2>{});
+        if (s + 3 < slabs) iteration(s + 3, Part<3>{});
+        if (s + 4 < slabs) iteration(s + 4, Part<4>{});
+        if (s + 5 < slabs) iteration(s + 5, Part<5>{});
+        if (s + 6 < slabs) iteration(s + 6, Part<6>{});
+        if (s + 7 < slabs) iteration(s + 7, Part<7>{});
     }
+    prefetch_aux_rest<EPI>(g, aux_pos, 2 * slabs, pre);    // K shorter than the parts
+
+    epilogue<EPI>(g, t, acc, wm, wn, half, r32, full_tile, pre, lds_a[0]);
 }
 
 // ---- the same GEMMs as three bf16 products -----------------------------------------------------------
@@ -526,34 +524,32 @@ __global__ __launch_bounds__(256, 2) void mlp_gemm3_kernel(const GemmArgs g) {
     if (AUX_AHEAD) {                                 // registers hold the weight tile: one slab ahead
         Stage next;
         fetch(t, rw, 0, next);
-        {
-            clear();
-            const bool full_tile = t.m0 + TM <= g.M && t.n0 + TN <= g.N;
-            const AuxPos aux_pos{t.aux, t.m0, t.n0, wm, wn, half, r32, full_tile};
-            stash(0, next);
-            __syncthreads();
-            // iteration s (s % 4 == TURN); in the first pass it also requests a quarter of the weight tile (K = 128 is
-            // four iterations)
-            auto iteration = [&](uint32_t s, auto turn) {
-                constexpr int TURN = decltype(turn)::value, cur = TURN & 1;
-                if (s + 1 < slabs) fetch(t, rw, (s + 1) * TK3, next);
-                if (s < AUX_PARTS / 2) {
-                    prefetch_aux_rows<EPI, 2 * TURN>(g, aux_pos, at_run_time(2 * TURN), pre);
-                    prefetch_aux_rows<EPI, 2 * TURN + 1>(g, aux_pos, at_run_time(2 * TURN + 1), pre);
-                }
-                multiply(cur);
-                if (s + 1 < slabs) stash(cur ^ 1, next);
-                __syncthreads();
-            };
-            for (uint32_t s = 0; s < slabs; s += 4) {
-                iteration(s, Part<0>{});
-                if (s + 1 < slabs) iteration(s + 1, Part<1>{});
-                if (s + 2 < slabs) iteration(s + 2, Part<2>{});
-                if (s + 3 < slabs) iteration(s + 3, Part<3>{});
+        clear();
+        const bool full_tile = t.m0 + TM <= g.M && t.n0 + TN <= g.N;
+        const AuxPos aux_pos{t.aux, t.m0, t.n0, wm, wn, half, r32, full_tile};
+        stash(0, next);
+        __syncthreads();
+        // iteration s (s % 4 == TURN); in the first pass it also requests a quarter of the weight tile (K = 128 is
+        // four iterations)
+        auto iteration = [&](uint32_t s, auto turn) {
+            constexpr int TURN = decltype(turn)::value, cur = TURN & 1;
+            if (s + 1 < slabs) fetch(t, rw, (s + 1) * TK3, next);
+            if (s < AUX_PARTS / 2) {
+                prefetch_aux_rows<EPI, 2 * TURN>(g, aux_pos, at_run_time(2 * TURN), pre);
+                prefetch_aux_rows<EPI, 2 * TURN + 1>(g, aux_pos, at_run_time(2 * TURN + 1), pre);
             }
-            prefetch_aux_rest<EPI>(g, aux_pos, 2 * slabs, pre);
-            epilogue<EPI, false>(g, t, acc, wm, wn, half, r32, full_tile, pre, (float *)lds[0][0]);
+            multiply(cur);
+            if (s + 1 < slabs) stash(cur ^ 1, next);
+            __syncthreads();
+        };
+        for (uint32_t s = 0; s < slabs; s += 4) {
+            iteration(s, Part<0>{});
+            if (s + 1 < slabs) iteration(s + 1, Part<1>{});
+            if (s + 2 < slabs) iteration(s + 2, Part<2>{});
+            if (s + 3 < slabs) iteration(s + 3, Part<3>{});
         }
+        prefetch_aux_rest<EPI>(g, aux_pos, 2 * slabs, pre);
+        epilogue<EPI, false>(g, t, acc, wm, wn, half, r32, full_tile, pre, (float *)lds[0][0]);
     } else {
         clear();
         const bool full_tile = t.m0 + TM <= g.M && t.n0 + TN <= g.N;
