@@ -5,6 +5,7 @@
 #include "internal.h"
 #include "philox.hpp"
 #include "quant.hpp"
+#include "uniform_address.hpp"
 
 namespace swarm {
 
@@ -25,6 +26,13 @@ __device__ __forceinline__ uint64_t wave_tile(uint32_t waves_per_group) {
 
 __device__ __forceinline__ f4 ldg_nt(const float *p) { return __builtin_nontemporal_load((const f4 *)p); }
 __device__ __forceinline__ void stg_nt(float *p, f4 v) { __builtin_nontemporal_store(v, (f4 *)p); }
+// The same at `row` (the same address in every lane: a tile's first coordinate) plus the lane's offset in floats.
+__device__ __forceinline__ f4 ldg_nt(const float *row, uint32_t off) {
+    return __builtin_nontemporal_load((SWARM_GLOBAL const f4 *)at_bytes(uniform(row), 4u * off));
+}
+__device__ __forceinline__ void stg_nt(float *row, uint32_t off, f4 v) {
+    __builtin_nontemporal_store(v, (SWARM_GLOBAL f4 *)at_bytes(uniform(row), 4u * off));
+}
 __device__ __forceinline__ uint32_t swap_with_neighbour(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
 }
@@ -44,6 +52,17 @@ template <int BITS>
 __device__ __forceinline__ void store_code(uint8_t *row, uint64_t f, uint64_t c) {
     __builtin_nontemporal_store((typename CodeWord<BITS>::type)c,
                                 (typename CodeWord<BITS>::type *)(row + f * (BITS / 2)));
+}
+// The same for a tile's codes: `tile_codes` is the same address in every lane, f the lane's float4 within the tile.
+template <int BITS>
+__device__ __forceinline__ uint64_t load_tile_code(const uint8_t *tile_codes, uint32_t f) {
+    typedef typename CodeWord<BITS>::type Word;
+    return (uint64_t)__builtin_nontemporal_load((SWARM_GLOBAL const Word *)at_bytes(uniform(tile_codes), f * (BITS / 2)));
+}
+template <int BITS>
+__device__ __forceinline__ void store_tile_code(uint8_t *tile_codes, uint32_t f, uint64_t c) {
+    typedef typename CodeWord<BITS>::type Word;
+    __builtin_nontemporal_store((Word)c, (SWARM_GLOBAL Word *)at_bytes(uniform(tile_codes), f * (BITS / 2)));
 }
 
 // The two random words of the float4 this lane holds in the tile's first half (lo*)

@@ -75,11 +75,15 @@ struct GossipArgs {
 };
 #if defined(__HIPCC__)
 // Descriptor k of the launch (k is uniform: a scalar load either way).
+// The fields are read from the first lane explicitly, so that everything derived from them (row bases, ring
+// slots) provably lives in scalar registers whichever kind of load fetched the descriptor.
+__device__ __forceinline__ uint32_t first_lane(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 __device__ __forceinline__ PairDesc pair_desc(const GossipArgs &g, uint32_t k) {
-    return g.inline_descs ? g.inl.pairs[k] : g.pairs[k];
+    const PairDesc pd = g.inline_descs ? g.inl.pairs[k] : g.pairs[k];
+    return PairDesc{first_lane(pd.ni), first_lane(pd.nj), first_lane(pd.flags), first_lane(pd.steps)};
 }
 __device__ __forceinline__ uint32_t single_desc(const GossipArgs &g, uint32_t k) {
-    return g.inline_descs ? g.inl.singles[k] : g.singles[k];
+    return first_lane(g.inline_descs ? g.inl.singles[k] : g.singles[k]);
 }
 #endif
 

@@ -18,8 +18,8 @@
 // 0-31 carry one k index and lanes 32-63 another, and any pairing is valid as long as A and
 // B agree, so lanes 0-31 take k 0..7 of the slab and lanes 32-63 take k 8..15: operands
 // whose k runs contiguously in memory are fetched from LDS with two 128-bit reads.
-#include <type_traits>
 #include "internal.h"
+#include "uniform_address.hpp"
 #include "objectives.h"
 #include "philox.hpp"
 
@@ -74,24 +74,6 @@ __device__ __forceinline__ Tile tile_of_id(const GemmArgs &g, uint32_t id) {
     t.m0 = (r / g.tiles_n) * TM;
     t.n0 = (r % g.tiles_n) * TN;
     return t;
-}
-
-// Global accesses are written as a uniform address plus the lane's 32-bit byte offset (plus a small
-// constant), the form the load and store instructions take directly (scalar base, vector offset).  The
-// marker keeps the uniform part in scalar registers: without it the compiler adds the lane's offset to
-// the base once and then carries 64-bit per-lane addresses, two vector registers and two vector adds
-// per access, and the registers it recycles for them make loads wait for one another.
-#define SWARM_GLOBAL __attribute__((address_space(1)))      // device memory, as opposed to a generic address
-template <typename T>
-__device__ __forceinline__ SWARM_GLOBAL T *uniform(T *p) {
-    SWARM_GLOBAL T *q = (SWARM_GLOBAL T *)p;
-    asm volatile("" : "+s"(q));
-    return q;
-}
-template <typename T>
-__device__ __forceinline__ SWARM_GLOBAL T *at_bytes(SWARM_GLOBAL T *p, uint32_t bytes) {
-    typedef typename std::conditional<std::is_const<T>::value, const char, char>::type Byte;
-    return (SWARM_GLOBAL T *)((SWARM_GLOBAL Byte *)p + bytes);
 }
 
 // Load a 128 x 16 slab of an operand whose k index is contiguous in memory: P[row * ld + k].

@@ -76,15 +76,15 @@ __device__ __forceinline__ NodeRows load_rows(const RoundArgs &ra, uint32_t node
     NodeRows r;
     const f4 zero = {0.f, 0.f, 0.f, 0.f};
     const float *x = a.X + at;
-    r.xA = ldg_nt(x + t.oA); r.xB = ldg_nt(x + t.oB);
+    r.xA = ldg_nt(x, t.oA); r.xB = ldg_nt(x, t.oB);
     r.uA = r.uB = r.vA = r.vB = zero;
     if (steps_inside(SRC)) {
         const float *pa = ra.A + at, *pc = ra.C + at;
-        r.uA = ldg_nt(pa + t.oA); r.uB = ldg_nt(pa + t.oB);
-        r.vA = ldg_nt(pc + t.oA); r.vB = ldg_nt(pc + t.oB);
+        r.uA = ldg_nt(pa, t.oA); r.uB = ldg_nt(pa, t.oB);
+        r.vA = ldg_nt(pc, t.oA); r.vB = ldg_nt(pc, t.oB);
     } else if (SRC == SRC_LIVE || (SRC == SRC_FLAGGED && pending)) {
         const float *w = a.W + at;
-        r.uA = ldg_nt(w + t.oA); r.uB = ldg_nt(w + t.oB);
+        r.uA = ldg_nt(w, t.oA); r.uB = ldg_nt(w, t.oB);
     }
     return r;
 }
@@ -143,13 +143,13 @@ __device__ __forceinline__ void round_pair_tile(const RoundArgs &ra, const PairD
     uint64_t seenjA = 0, seenjB = 0, seeniA = 0, seeniB = 0;       // partner codes as read
     if (stale_i) {   // i reads what j published si rounds ago
         const uint8_t *src = ring_tile<BITS>(a, slot_of_age(a, si), nj, t);
-        seenjA = load_code<BITS>(src, t.oA / 4);
-        seenjB = load_code<BITS>(src, t.oB / 4);
+        seenjA = load_tile_code<BITS>(src, t.oA / 4);
+        seenjB = load_tile_code<BITS>(src, t.oB / 4);
     }
     if (stale_j) {
         const uint8_t *src = ring_tile<BITS>(a, slot_of_age(a, sj), ni, t);
-        seeniA = load_code<BITS>(src, t.oA / 4);
-        seeniB = load_code<BITS>(src, t.oB / 4);
+        seeniA = load_tile_code<BITS>(src, t.oA / 4);
+        seeniB = load_tile_code<BITS>(src, t.oB / 4);
     }
     const NodeTerms ti = node_terms<SRC, INPLACE>(ra, ri, ni, pend_i, pd.steps & 0xFFu, t);
     const NodeTerms tj = node_terms<SRC, INPLACE>(ra, rj, nj, pend_j, (pd.steps >> 8) & 0xFFu, t);
@@ -188,12 +188,12 @@ __device__ __forceinline__ void round_pair_tile(const RoundArgs &ra, const PairD
     float *xi = a.X + (uint64_t)ni * a.d + t.base, *xj = a.X + (uint64_t)nj * a.d + t.base;
     uint8_t *pub_i = ring_tile<BITS>(a, a.slot_now, ni, t), *pub_j = ring_tile<BITS>(a, a.slot_now, nj, t);
     if (t.inA) {
-        stg_nt(xi + t.cA, oiA); stg_nt(xj + t.cA, ojA);
-        store_code<BITS>(pub_i, t.cA / 4, ciA); store_code<BITS>(pub_j, t.cA / 4, cjA);
+        stg_nt(xi, t.cA, oiA); stg_nt(xj, t.cA, ojA);
+        store_tile_code<BITS>(pub_i, t.cA / 4, ciA); store_tile_code<BITS>(pub_j, t.cA / 4, cjA);
     }
     if (t.inB) {
-        stg_nt(xi + t.cB, oiB); stg_nt(xj + t.cB, ojB);
-        store_code<BITS>(pub_i, t.cB / 4, ciB); store_code<BITS>(pub_j, t.cB / 4, cjB);
+        stg_nt(xi, t.cB, oiB); stg_nt(xj, t.cB, ojB);
+        store_tile_code<BITS>(pub_i, t.cB / 4, ciB); store_tile_code<BITS>(pub_j, t.cB / 4, cjB);
     }
     report(a.counters, (t.inA ? failsA : 0) + (t.inB ? failsB : 0), (t.inA && clampedA) || (t.inB && clampedB));
 }
@@ -209,7 +209,7 @@ __device__ __forceinline__ void round_node_tile(const RoundArgs &ra, uint32_t no
     const TilePos t = tile_pos<FULL>(tile, lane, a.d);
     const NodeRows r = load_rows<SRC>(ra, node, pending, t);
     const uint8_t *src = ring_tile<BITS>(a, slot_of_age(a, age), partner, t);
-    const uint64_t seenA = load_code<BITS>(src, t.oA / 4), seenB = load_code<BITS>(src, t.oB / 4);
+    const uint64_t seenA = load_tile_code<BITS>(src, t.oA / 4), seenB = load_tile_code<BITS>(src, t.oB / 4);
     const NodeTerms m = node_terms<SRC, INPLACE>(ra, r, node, pending, H, t);
     const LaneRandom rnd = row_random(a.seed, node, a.event, tile, lane);
     const ReadScale rs = read_scale(a, age, a.eps, a.inv_eps);
@@ -231,8 +231,8 @@ __device__ __forceinline__ void round_node_tile(const RoundArgs &ra, uint32_t no
     }
     float *x = a.X + (uint64_t)node * a.d + t.base;
     uint8_t *pub = ring_tile<BITS>(a, a.slot_now, node, t);
-    if (t.inA) { stg_nt(x + t.cA, oA); store_code<BITS>(pub, t.cA / 4, codeA); }
-    if (t.inB) { stg_nt(x + t.cB, oB); store_code<BITS>(pub, t.cB / 4, codeB); }
+    if (t.inA) { stg_nt(x, t.cA, oA); store_tile_code<BITS>(pub, t.cA / 4, codeA); }
+    if (t.inB) { stg_nt(x, t.cB, oB); store_tile_code<BITS>(pub, t.cB / 4, codeB); }
     report(a.counters, 0, (t.inA && clampedA) || (t.inB && clampedB));
 }
 
@@ -255,14 +255,14 @@ __device__ __forceinline__ void round_single_tile(const RoundArgs &ra, uint32_t 
         const uint64_t cA = round_float4<BITS>(m.qA, rnd.a0, rnd.a1, inv_now, z, clampedA);
         const uint64_t cB = round_float4<BITS>(m.qB, rnd.b0, rnd.b1, inv_now, z, clampedB);
         uint8_t *pub = ring_tile<BITS>(a, a.slot_now, u, t);
-        if (t.inA) store_code<BITS>(pub, t.cA / 4, cA);
-        if (t.inB) store_code<BITS>(pub, t.cB / 4, cB);
+        if (t.inA) store_tile_code<BITS>(pub, t.cA / 4, cA);
+        if (t.inB) store_tile_code<BITS>(pub, t.cB / 4, cB);
         report(a.counters, 0, (t.inA && clampedA) || (t.inB && clampedB));
     }
     if (steps_inside(SRC) || pending) {          // X_u <- w_u: the live copy itself, or the steps just taken
         float *xu = a.X + (uint64_t)u * a.d + t.base;
-        if (t.inA) stg_nt(xu + t.cA, m.wA);
-        if (t.inB) stg_nt(xu + t.cB, m.wB);
+        if (t.inA) stg_nt(xu, t.cA, m.wA);
+        if (t.inB) stg_nt(xu, t.cB, m.wB);
     }
 }
 
