@@ -34,8 +34,9 @@ MEASURED_TRAFFIC_PER_PAIR_COORDINATE = {("gossip", 4, True): 25.99, ("round", 4,
 BOX_CPU_SHARE = 16             # host cores a one-GPU machine grants, whatever os.cpu_count() shows
 # Vector-ALU side of the one-pass round at 8-bit codes with gradient noise: vector instructions a wave issues per
 # 512-coordinate tile of one node, from the rocprofv3 SQ_INSTS_VALU / SQ_WAVES runs at H = 3 and H = 5 under
-# profiles/ (fused_nodes_kernel 638 / 880, fused_pairs_kernel 1265 / 1749 per pair): 272 + 121 per local step.
-VALU_PER_NODE_TILE_8BIT = (272.0, 121.0)
+# profiles/ (fused_nodes_kernel 647 / 889, fused_pairs_kernel 1276 / 1760 per pair): 121 per local step and, taking
+# the smaller of the two kernels' figures, 275 that do not depend on H.
+VALU_PER_NODE_TILE_8BIT = (275.0, 121.0)
 # 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz: lane-operations per second the vector ALUs can issue
 VALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
