@@ -56,3 +56,19 @@ def ring_row(cpu, node, age=0):
     depth = cpu.S + 1
     last = (cpu.round - 1) % depth if cpu.round else 0
     return cpu.ring[(last - age) % depth][node]
+
+
+def disjoint_prefix(c, limit):
+    """How many of the oracle's next interactions touch pairwise disjoint nodes (without stepping it)."""
+    t0, used, k = c.interactions, set(), 0
+    try:
+        while k < limit:
+            c.interactions = t0 + k
+            i, j = c.sample_pair()
+            if i in used or j in used:
+                break
+            used |= {i, j}
+            k += 1
+    finally:
+        c.interactions = t0
+    return k

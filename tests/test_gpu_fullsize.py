@@ -9,7 +9,7 @@ import torch
 import workloads as wl
 from oracle.objectives import DiagQuadratic, MixtureMLP
 from oracle.swarm import SwarmOracle
-from helpers import TOL_ELEMENTWISE, TOL_TWO_STAGE, TOL_GEMM, assert_close
+from helpers import TOL_ELEMENTWISE, TOL_TWO_STAGE, TOL_GEMM, assert_close, disjoint_prefix
 
 pytestmark = pytest.mark.gpu
 
@@ -140,3 +140,80 @@ def test_mlp_config_full_size_sampled_nodes(gpu, arithmetic):
         want = (z[u] + seen) * (0.5 * eps) + (W[u] - X[u].astype(np.float64))
         assert np.array_equal(g.read_codes(u), qz.pack(qz.code(z[u], bits), bits)), f"codes of node {u}"
         assert_close(g.read_models(gpu.COMM, node0=u, count=1)[0], want, TOL_GEMM, f"X of node {u}")
+
+
+def test_algorithm1_run_config4_shape_full_size(gpu):
+    """Algorithm 1 at config 4's shape with fresh reads, the run `bench.py --sequential` times.  Teacher-forced on
+    column windows: from the oracle's state, the next interactions that touch disjoint nodes -- one launch of the
+    batched run, local steps inside -- against the oracle taking them one after the other (codes bit-exact: nothing
+    quantized there depends on the device's own float32 steps).  Then a longer run with dependent interactions on
+    whole rows against one swarm_sample_pair + swarm_interact per step on a second handle, bit for bit."""
+    cfg = wl.CONFIGS[4]
+    n, d, bits, H, lr, sigma, eps, seed = cfg["n"], cfg["d"], cfg["bits"], cfg["H"], cfg["lr"], cfg["sigma"], 0.5, 4
+    edges = graph_of(cfg)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(44)
+    a = torch.empty((n, d), dtype=torch.float32, device="cuda").uniform_(cfg["a_lo"], cfg["a_hi"], generator=gen)
+    c = torch.empty((n, d), dtype=torch.float32, device="cuda").normal_(0.0, 1.0, generator=gen)
+    g = gpu.Swarm(n, d, edges, bits, eps, H, lr, 0, seed)
+    g.set_objective_diag(a, c, sigma)
+    g.models_view(gpu.COMM).normal_(0.0, 0.7, generator=gen)
+    g.models_view(gpu.SNAP).copy_(g.models_view(gpu.COMM)).add_(0.01 * torch.randn(n, 1, generator=gen, device="cuda"))
+    torch.cuda.synchronize()
+    width = 6 * 512 + 8
+    starts = [0, 8 * (d // 24) + 8, d - width]
+    oracles = []
+    for k0 in starts:
+        o = SwarmOracle(n, d, edges, bits, eps, H, lr, 0, seed, k0=k0, k1=k0 + width)
+        o.objective = DiagQuadratic(a[:, k0:k0 + width].cpu().numpy(), c[:, k0:k0 + width].cpu().numpy(), sigma, k0=k0)
+        o.X[:] = g.read_models(gpu.COMM, k0=k0, length=width)
+        o.Xhat[:] = g.read_models(gpu.SNAP, k0=k0, length=width)
+        oracles.append(o)
+    widest = 0
+    for rep in range(4):
+        for o, k0 in zip(oracles, starts):
+            g.write_models(gpu.COMM, o.X, k0=k0)
+            g.write_models(gpu.SNAP, o.Xhat, k0=k0)
+        k = disjoint_prefix(oracles[0], n // 2)
+        widest = max(widest, k)
+        pairs, launches = g.run_sequential(k)
+        assert launches == 1
+        for o, k0 in zip(oracles, starts):
+            steps = [o.step_sequential() for _ in range(k)]
+            assert [tuple(p) for p in pairs.tolist()] == steps
+            for i, j in steps:
+                for node in (i, j):
+                    got = g.read_codes(node, byte0=k0 * bits // 8, length=width * bits // 8)
+                    assert np.array_equal(got, o.ring[0][node]), f"register of node {node}, window {k0}, launch {rep}"
+            assert_close(g.read_models(gpu.COMM, k0=k0, length=width), o.X, TOL_TWO_STAGE, f"X window {k0} launch {rep}")
+            assert_close(g.read_models(gpu.SNAP, k0=k0, length=width), o.Xhat, TOL_TWO_STAGE, f"snapshots window {k0}")
+        cnt = g.counters()
+        assert cnt["interactions"] == oracles[0].interactions
+    assert widest >= 2
+    g.close()
+    # dependent interactions, whole rows: the batched run against one call per interaction
+    T = 48
+    twins = []
+    for _ in range(2):
+        t = gpu.Swarm(n, d, edges, bits, eps, H, lr, 0, seed)
+        t.set_objective_diag(a, c, sigma)
+        gen.manual_seed(45)
+        t.models_view(gpu.COMM).normal_(0.0, 0.7, generator=gen)
+        t.models_view(gpu.SNAP).copy_(t.models_view(gpu.COMM)).add_(0.01 * torch.randn(n, 1, generator=gen, device="cuda"))
+        twins.append(t)
+    g1, g2 = twins
+    torch.cuda.synchronize()
+    assert torch.equal(g1.models_view(gpu.COMM), g2.models_view(gpu.COMM))
+    drawn = []
+    for t in range(T):
+        i, j = g1.sample_pair()
+        drawn.append((i, j))
+        g1.interact(i, j)
+    pairs, launches = g2.run_sequential(T)
+    assert [tuple(p) for p in pairs.tolist()] == drawn and 1 < launches < T
+    torch.cuda.synchronize()
+    assert torch.equal(g1.models_view(gpu.COMM), g2.models_view(gpu.COMM))
+    assert torch.equal(g1.models_view(gpu.SNAP), g2.models_view(gpu.SNAP))
+    for node in sorted({v for p in drawn for v in p})[:8]:
+        assert np.array_equal(g1.read_codes(node), g2.read_codes(node)), f"register of node {node}"
+    assert g1.counters() == g2.counters()

@@ -6,7 +6,7 @@ import torch
 
 import workloads as wl
 from oracle.objectives import DiagQuadratic, LeastSquares
-from helpers import TOL_ELEMENTWISE, TOL_TWO_STAGE, TOL_GEMM, assert_close, make_both
+from helpers import TOL_ELEMENTWISE, TOL_TWO_STAGE, TOL_GEMM, assert_close, disjoint_prefix, make_both
 
 pytestmark = pytest.mark.gpu
 
@@ -91,22 +91,6 @@ def test_batched_run_equals_one_interaction_per_call_bit_for_bit(gpu, kind):
     assert g2.sample_pair() == g1.sample_pair()              # both stand at the same interaction number
     if kind in ("least squares", "no objective, caller's steps"):   # the steps are a kernel of their own: same live copies
         assert np.array_equal(g2.read_models(gpu.LIVE), g1.read_models(gpu.LIVE))
-
-
-def disjoint_prefix(c, limit):
-    """How many of the oracle's next interactions touch pairwise disjoint nodes (without stepping it)."""
-    t0, used, k = c.interactions, set(), 0
-    try:
-        while k < limit:
-            c.interactions = t0 + k
-            i, j = c.sample_pair()
-            if i in used or j in used:
-                break
-            used |= {i, j}
-            k += 1
-    finally:
-        c.interactions = t0
-    return k
 
 
 @pytest.mark.parametrize("kind", ["least squares", "diag", "diag, geometric steps", "diag, prefix registers",
