@@ -649,7 +649,8 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     auto single_entry = [&](uint32_t u) {
         return u | (fused ? draw_steps(c, u, (uint32_t)h->round) << 16 : 0u) | (h->pending[u] ? SINGLE_PENDING : 0u);
     };
-    const bool inline_descs = npairs <= INLINE_PAIRS && nsingles <= INLINE_SINGLES && !pair_scale_policy;
+    const bool inline_descs = npairs <= INLINE_PAIRS && nsingles <= INLINE_SINGLES && !pair_scale_policy &&
+                              c.codec != SWARM_CODEC_PREFIX;     // those kernels read the device block only
     if (!inline_descs) {
         uint8_t *slot = nullptr;
         unsigned slot_index = 0;
