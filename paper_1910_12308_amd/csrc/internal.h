@@ -37,15 +37,6 @@ struct PairDesc {
 constexpr uint32_t SINGLE_PENDING = 0x80000000u;
 constexpr uint32_t SINGLE_NODE_MASK = 0xFFFFu;
 
-// A round of at most this many pairs and unmatched nodes carries its descriptors in the launch itself
-// (kernel arguments) instead of in device memory: no copy, and no wait for one, ahead of the round's
-// kernels.  Larger rounds read them from the device block the host fills with one copy.
-constexpr uint32_t INLINE_PAIRS = 64, INLINE_SINGLES = 128;
-struct InlineDescs {
-    PairDesc pairs[INLINE_PAIRS];
-    uint32_t singles[INLINE_SINGLES];
-};
-
 struct GossipArgs {
     float *X;                 // n x d current models (updated in place)
     const float *W;           // n x d live copies
@@ -70,43 +61,17 @@ struct GossipArgs {
     uint32_t slot_now;        // ring slot written this round
     uint32_t ring_depth;      // S + 1
     float eps, inv_eps;
-    uint32_t inline_descs;    // 1: the descriptors of this launch are in `inl`, `pairs` / `singles` are not used
-    InlineDescs inl;
 };
 #if defined(__HIPCC__)
-// Descriptor k of the launch (k is uniform: a scalar load either way).
-// The fields are read from the first lane explicitly, so that everything derived from them (row bases, ring
-// slots) provably lives in scalar registers whichever kind of load fetched the descriptor.
+// Descriptor k of the launch (k is uniform: a scalar load).  The fields are read from the first lane
+// explicitly, so that everything derived from them (row bases, ring slots) provably lives in scalar
+// registers.
 __device__ __forceinline__ uint32_t first_lane(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
-// The kernel-argument entry is read unconditionally (index wrapped into the array), together with the other
-// arguments: a wave of a small round then has its descriptor after one round trip of scalar loads, with no
-// load that depends on an earlier one.  The device block is read through the constant address space, so that
-// it is a scalar load too (a choice between a kernel-argument array and a pointer otherwise becomes one
-// generic pointer and a vector load); it is written by a copy ordered ahead of the launch and by nothing
-// during it.
-#define SWARM_CONSTANT __attribute__((address_space(4)))
 __device__ __forceinline__ PairDesc pair_desc(const GossipArgs &g, uint32_t k) {
-    PairDesc pd = g.inl.pairs[k % INLINE_PAIRS];
-    if (!g.inline_descs) {
-        typedef uint32_t Words __attribute__((ext_vector_type(4), aligned(4)));
-        const Words w = *(SWARM_CONSTANT const Words *)(g.pairs + k);
-        pd = PairDesc{w.x, w.y, w.z, w.w};
-        asm volatile("" : "+s"(pd.ni), "+s"(pd.nj), "+s"(pd.flags), "+s"(pd.steps));   // keeps the two loads apart
-    }
+    const PairDesc pd = g.pairs[k];
     return PairDesc{first_lane(pd.ni), first_lane(pd.nj), first_lane(pd.flags), first_lane(pd.steps)};
 }
-__device__ __forceinline__ uint32_t single_desc(const GossipArgs &g, uint32_t k) {
-    uint32_t v = g.inl.singles[k % INLINE_SINGLES];
-    if (!g.inline_descs) {
-        v = *(SWARM_CONSTANT const uint32_t *)(g.singles + k);
-        asm volatile("" : "+s"(v));
-    }
-    return first_lane(v);
-}
-// The device block only, for kernels whose rounds never carry their descriptors in the launch (the
-// multi-resolution codec: measured 2 % faster without the second source).
-__device__ __forceinline__ PairDesc block_pair_desc(const GossipArgs &g, uint32_t k) { return g.pairs[k]; }
-__device__ __forceinline__ uint32_t block_single_desc(const GossipArgs &g, uint32_t k) { return g.singles[k]; }
+__device__ __forceinline__ uint32_t single_desc(const GossipArgs &g, uint32_t k) { return first_lane(g.singles[k]); }
 #endif
 
 // delta_mode: 0 = no node of these pairs has pending steps, 1 = all have, 2 = per-pair flags.

@@ -266,7 +266,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_nodes_kernel(const PrefixAr
     const GossipArgs &a = pa.g;
     TileGeometry g;
     if (!geometry(a.d, WAVES, g)) return;
-    const PairDesc pd = block_pair_desc(a, blockIdx.y >> 1);
+    const PairDesc pd = pair_desc(a, blockIdx.y >> 1);
     const bool second = blockIdx.y & 1u;
     const uint32_t node = second ? pd.nj : pd.ni, partner = second ? pd.ni : pd.nj;
     const uint32_t age = (pd.flags >> (second ? 8 : 0)) & 0xFFu, H = (pd.steps >> (second ? 8 : 0)) & 0xFFu;
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_pairs_kernel(const PrefixAr
     const GossipArgs &a = pa.g;
     TileGeometry g;
     if (!geometry(a.d, WAVES, g)) return;
-    const PairDesc pd = block_pair_desc(a, blockIdx.y);
+    const PairDesc pd = pair_desc(a, blockIdx.y);
     const uint32_t si = pd.flags & 0xFFu, sj = (pd.flags >> 8) & 0xFFu;
     const LaneWeights lw = lane_weights(g.lane);
     const NodeTile ti = prepare<LOCAL, INPLACE, NOISE>(pa, pd.ni, pd.steps & 0xFFu, pd.flags & (1u << 16), g.tile, g.lane,
@@ -329,7 +329,7 @@ __global__ __launch_bounds__(WAVES * 64) void prefix_singles_kernel(const Prefix
     const GossipArgs &a = pa.g;
     TileGeometry g;
     if (!geometry(a.d, WAVES, g)) return;
-    const uint32_t entry = block_single_desc(a, blockIdx.y);
+    const uint32_t entry = single_desc(a, blockIdx.y);
     const uint32_t u = entry & SINGLE_NODE_MASK;
     const NodeTile t = prepare<LOCAL, INPLACE, NOISE>(pa, u, (entry >> 16) & 0xFFu, entry & SINGLE_PENDING, g.tile, g.lane,
                                                       g.lA, g.lB, g.inA, g.inB, lane_weights(g.lane));

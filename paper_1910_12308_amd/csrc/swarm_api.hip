@@ -644,14 +644,10 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
     const int group_mode[3] = {delta_mode == 2 ? 2 : 0, 1, 3};
 
     // Per-round metadata: one descriptor per pair (nodes, staleness, pending flags) and the unmatched
-    // nodes.  A small round carries them in its launches; otherwise they are staged in pinned memory and
-    // copied with one transfer (the per-pair scale pre-pass reads them from the device as well).
-    auto single_entry = [&](uint32_t u) {
-        return u | (fused ? draw_steps(c, u, (uint32_t)h->round) << 16 : 0u) | (h->pending[u] ? SINGLE_PENDING : 0u);
-    };
-    const bool inline_descs = npairs <= INLINE_PAIRS && nsingles <= INLINE_SINGLES && !pair_scale_policy &&
-                              c.codec != SWARM_CODEC_PREFIX;     // those kernels read the device block only
-    if (!inline_descs) {
+    // nodes, staged in pinned memory and copied with one transfer.  (Carrying them in the kernel arguments
+    // of small rounds instead was measured: the copy costs the step nothing, a second source of descriptors
+    // costs the kernels 0.5 to 2 %.)
+    {
         uint8_t *slot = nullptr;
         unsigned slot_index = 0;
         const swarm_status rc = acquire_desc(h, &slot, &slot_index);
@@ -660,19 +656,14 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
         for (int gidx = 0; gidx < 3; ++gidx)
             for (const PairDesc &desc : groups[gidx]) *pd++ = desc;
         uint32_t *sg = (uint32_t *)(slot + h->off_singles);
-        for (uint32_t k = 0; k < nsingles; ++k) sg[k] = single_entry(singles[k]);
+        for (uint32_t k = 0; k < nsingles; ++k)
+            sg[k] = singles[k] | (fused ? draw_steps(c, singles[k], (uint32_t)h->round) << 16 : 0u) |
+                    (h->pending[singles[k]] ? SINGLE_PENDING : 0u);
         SWARM_HIP(h, hipMemcpyAsync(h->desc_dev, slot, h->desc_bytes, hipMemcpyHostToDevice, h->stream));
         SWARM_HIP(h, hipEventRecord(h->desc_free[slot_index], h->stream));
     }
 
     GossipArgs a = gossip_args(h, (uint32_t)h->round, (uint32_t)(h->round % (c.stale_max + 1)));
-    a.inline_descs = inline_descs ? 1u : 0u;
-    if (inline_descs)
-        for (uint32_t k = 0; k < nsingles; ++k) a.inl.singles[k] = single_entry(singles[k]);
-    // the pairs of group gidx for a launch: in its arguments, or as the next stretch of the device block
-    auto select_group = [&](GossipArgs &ga, int gidx) {
-        if (inline_descs) std::copy(groups[gidx].begin(), groups[gidx].end(), ga.inl.pairs);
-    };
     SWARM_TRY(record_timing(h, h->ev_gossip, h->timed_gossip, 0));
     const bool inplace = c.apply_mode == SWARM_APPLY_INPLACE;
     if (c.codec == SWARM_CODEC_PREFIX) {
@@ -682,7 +673,6 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
         GossipArgs ga = a;
         const uint32_t counts[3] = {(uint32_t)groups[0].size(), (uint32_t)groups[1].size(), (uint32_t)groups[2].size()};
         for (int gidx = 0; gidx < 3; ++gidx) {
-            select_group(ga, gidx);
             SWARM_HIP(h, launch_prefix(ga, local, inplace, c.lr, gidx == 1 ? 1 : 0, counts[gidx], h->stream));
             ga.pairs += counts[gidx];
         }
@@ -699,8 +689,7 @@ static swarm_status round_impl(swarm_t h, const uint32_t *pairs_host, uint32_t n
             if (pair_scale_policy) ga.pair_linf = h->linf_dev;
             for (int gidx = 0; gidx < 3; ++gidx) {
                 const uint32_t count = (uint32_t)groups[gidx].size();
-                select_group(ga, gidx);
-                if (fused)
+                    if (fused)
                     SWARM_HIP(h, launch_fused_pairs(ga, h->diag, c.bits, inplace, c.H, c.lr, group_mode[gidx], count, h->stream));
                 else
                     SWARM_HIP(h, launch_gossip_pairs(ga, c.bits, delta_mode, group_mode[gidx], count, h->stream));
