@@ -626,6 +626,35 @@ def test_matching_large_graphs(gpu, case):
     assert g.counters()["interactions"] == c.interactions
 
 
+def test_largest_swarm_and_one_node_more(gpu):
+    """n = 4096, the most the boundary takes (the matching of a round runs in one workgroup), on a random
+    4-regular graph: matching, codes and models of a one-pass round against the oracle; n = 4097 is refused."""
+    n, d, H, lr, bits, eps = 4096, 16, 2, 0.1, 8, 2.0 ** -4
+    edges = wl.random_regular_graph(n, 4, 21)
+    a, cc = wl.diag_quadratic_data(n, d, 13, shift_sigma=0.2)
+    g, c = make_both(gpu, n, d, edges, bits, eps, H, lr, 1, seed=99)
+    c.objective = DiagQuadratic(a, cc, 0.05)
+    g.set_objective_diag(torch.from_numpy(a).cuda(), torch.from_numpy(cc).cuda(), 0.05)
+    gen = np.random.Generator(np.random.PCG64(99))
+    for r in range(2):
+        c.X[:] = models(gen, 1, d) + models(gen, n, d, 0.05)
+        c.pending[:] = False
+        force_state(gpu, g, c)
+        pairs, stale = c.sample_matching(), c.sample_stale()
+        assert np.array_equal(g.sample_matching(), pairs.astype(np.uint32)) and len(pairs) > 1500
+        c.local_steps()
+        c.gossip_round(pairs, stale)
+        g.round_fused(None, stale.astype(np.uint8))
+        for i in (0, 1, n // 2, n - 2, n - 1):
+            assert np.array_equal(g.read_codes(i), ring_row(c, i)), f"register of node {i}, round {r}"
+        assert_close(g.read_models(gpu.COMM), c.X, TOL_TWO_STAGE, f"X after round {r}")
+    assert g.counters()["interactions"] == c.interactions
+    ring = np.array([(i, (i + 1) % (n + 1)) for i in range(n + 1)], dtype=np.uint32)
+    with pytest.raises(gpu.SwarmError) as err:
+        gpu.Swarm(n + 1, d, ring, bits, eps, H, lr, 1, 99)
+    assert "EINVAL" in str(err.value)
+
+
 def test_smallest_swarm_and_empty_rounds(gpu):
     """n = 2, d = 8 (one Philox call per row), rounds with no pair, H = 0."""
     g, c = make_both(gpu, 2, 8, [(0, 1)], 8, 0.25, 0, 0.0, 1, seed=1)
